@@ -1,0 +1,165 @@
+"""ctypes front end of the CPU oracle (oracle/fastgl_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Only tests/, the smoke check and the benchmark's
+cpu_baseline leg may import this package; the product path never does.  It
+works on host numpy arrays and imports nothing from the GPU package.
+
+Formulas: paper Section 2.1 Eq. 1 (forward) and Section 4.2 Eq. 5 (backward,
+read as the transpose of Eq. 1 applied to the upstream gradient).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fastgl_oracle.c")
+_LIB = os.path.join(_HERE, "libfastgl_oracle.so")
+
+MODES = {"sum": 0, "mean": 1, "gcn": 2}
+DTYPES = {"f32": 0, "bf16": 1}
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (generic x86-64 so the .so runs on any host)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        agg = [p, p, p, i64, i64, i64, i64, i32, i32, p, p]
+        for name in ("fastgl_oracle_aggregate_fwd", "fastgl_oracle_aggregate_bwd",
+                     "fastgl_oracle_par_aggregate_fwd", "fastgl_oracle_par_aggregate_bwd"):
+            getattr(L, name).argtypes = agg
+            getattr(L, name).restype = i32
+        L.fastgl_oracle_degrees.argtypes = [p, p, i64, i64, i64, p, p]
+        L.fastgl_oracle_degrees.restype = i32
+        L.fastgl_oracle_transpose.argtypes = [p, p, i64, i64, i64, p, p, p]
+        L.fastgl_oracle_transpose.restype = i32
+        L.fastgl_oracle_long_rows.argtypes = [p, i64, ctypes.c_int32, ctypes.c_int32, p, p]
+        L.fastgl_oracle_long_rows.restype = i64
+        L.fastgl_oracle_gather_rows.argtypes = [p, p, i64, i64, i32, p]
+        L.fastgl_oracle_gather_rows.restype = i32
+        L.fastgl_oracle_double_to_bf16.argtypes = [ctypes.c_double]
+        L.fastgl_oracle_double_to_bf16.restype = ctypes.c_uint16
+        L.fastgl_oracle_num_threads.restype = i32
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _feat_array(a, dtype):
+    want = np.float32 if dtype == "f32" else np.uint16
+    a = np.ascontiguousarray(a)
+    if a.dtype != want:
+        raise TypeError(f"{dtype} features must be {want} (bf16 as uint16 bit patterns)")
+    return a
+
+
+def _aggregate(fn, indptr, indices, edge_w, num_src, mode, dtype, inp, out_rows):
+    indptr, indices = _i32(indptr), _i32(indices)
+    inp = _feat_array(inp, dtype)
+    num_dst = indptr.shape[0] - 1
+    feat = inp.shape[1]
+    w = None if edge_w is None else np.ascontiguousarray(edge_w, dtype=np.float32)
+    out = np.empty((out_rows, feat), dtype=inp.dtype)
+    rc = fn(_ptr(indptr), _ptr(indices), _ptr(w), num_dst, num_src, indices.shape[0], feat,
+            MODES[mode], DTYPES[dtype], _ptr(inp), _ptr(out))
+    if rc:
+        raise RuntimeError(f"oracle returned {rc}")
+    return out
+
+
+def aggregate_fwd(indptr, indices, edge_w, num_src, mode, dtype, X):
+    assert X.shape[0] == num_src
+    return _aggregate(lib().fastgl_oracle_aggregate_fwd, indptr, indices, edge_w, num_src,
+                      mode, dtype, X, len(indptr) - 1)
+
+
+def aggregate_bwd(indptr, indices, edge_w, num_src, mode, dtype, G):
+    assert G.shape[0] == len(indptr) - 1
+    return _aggregate(lib().fastgl_oracle_aggregate_bwd, indptr, indices, edge_w, num_src,
+                      mode, dtype, G, num_src)
+
+
+def par_aggregate_fwd(indptr, indices, edge_w, num_src, mode, dtype, X):
+    return _aggregate(lib().fastgl_oracle_par_aggregate_fwd, indptr, indices, edge_w, num_src,
+                      mode, dtype, X, len(indptr) - 1)
+
+
+def par_aggregate_bwd(indptr, indices, edge_w, num_src, mode, dtype, G):
+    return _aggregate(lib().fastgl_oracle_par_aggregate_bwd, indptr, indices, edge_w, num_src,
+                      mode, dtype, G, num_src)
+
+
+def degrees(indptr, indices, num_src):
+    indptr, indices = _i32(indptr), _i32(indices)
+    num_dst = indptr.shape[0] - 1
+    din = np.empty(num_dst, np.int32)
+    dout = np.empty(num_src, np.int32)
+    rc = lib().fastgl_oracle_degrees(_ptr(indptr), _ptr(indices), num_dst, num_src,
+                                     indices.shape[0], _ptr(din), _ptr(dout))
+    if rc:
+        raise ValueError("index out of range")
+    return din, dout
+
+
+def transpose(indptr, indices, num_src):
+    indptr, indices = _i32(indptr), _i32(indices)
+    num_dst = indptr.shape[0] - 1
+    e = indices.shape[0]
+    pT = np.empty(num_src + 1, np.int32)
+    iT = np.empty(e, np.int32)
+    perm = np.empty(e, np.int32)
+    rc = lib().fastgl_oracle_transpose(_ptr(indptr), _ptr(indices), num_dst, num_src, e,
+                                       _ptr(pT), _ptr(iT), _ptr(perm))
+    if rc:
+        raise RuntimeError(f"oracle returned {rc}")
+    return pT, iT, perm
+
+
+def long_rows(rowptr, threshold, chunk):
+    rowptr = _i32(rowptr)
+    n = rowptr.shape[0] - 1
+    rows = np.empty(n + 1, np.int32)
+    cptr = np.empty(n + 2, np.int32)
+    k = lib().fastgl_oracle_long_rows(_ptr(rowptr), n, threshold, chunk, _ptr(rows), _ptr(cptr))
+    return rows[:k].copy(), cptr[:k + 1].copy()
+
+
+def gather_rows(table, ids, dtype):
+    table = _feat_array(table, dtype)
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    out = np.empty((ids.shape[0], table.shape[1]), dtype=table.dtype)
+    lib().fastgl_oracle_gather_rows(_ptr(table), _ptr(ids), ids.shape[0], table.shape[1],
+                                    DTYPES[dtype], _ptr(out))
+    return out
+
+
+def double_to_bf16(x: float) -> int:
+    return int(lib().fastgl_oracle_double_to_bf16(float(x)))
+
+
+def num_threads() -> int:
+    return int(lib().fastgl_oracle_num_threads())
