@@ -1,0 +1,218 @@
+"""ctypes binding of libfastgl_agg.so - same names as the C ABI, argument
+marshalling only.  PyTorch supplies device memory and the stream handle; every
+step of the computation runs in the library's kernels.  There is no fallback:
+if the library is missing or an entry point fails, this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfastgl_agg.so")
+
+FASTGL_OK = 0
+FASTGL_ERR_INVALID_ARG, FASTGL_ERR_UNSUPPORTED, FASTGL_ERR_WORKSPACE, FASTGL_ERR_HIP = 1, 2, 3, 4
+MODES = {"sum": 0, "mean": 1, "gcn": 2}
+DTYPES = {"f32": 0, "bf16": 1}
+PLAN_FWD, PLAN_BWD, PLAN_ALL = 1, 2, 3
+
+EXPORTS = [
+    "fastgl_block_aggregate_fwd", "fastgl_block_aggregate_bwd", "fastgl_block_plan_bytes",
+    "fastgl_block_plan_create", "fastgl_block_plan_export", "fastgl_block_plan_destroy",
+    "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk",
+    "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
+]
+
+
+class FastglError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"fastgl status {status}: {msg}")
+        self.status = status
+
+
+class PlanView(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in (
+        "din", "dout", "indptr_T", "indices_T", "perm", "dst_inv", "dst_rsqrt", "src_rsqrt",
+        "long_dst", "chunk_ptr_dst", "long_src", "chunk_ptr_src", "counters")]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        p, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+        agg = [p, p, p, i64, i64, i64, i64, i32, i32, p, p, p, p, sz, p]
+        L.fastgl_block_aggregate_fwd.argtypes = agg
+        L.fastgl_block_aggregate_bwd.argtypes = agg
+        L.fastgl_block_plan_bytes.argtypes = [i64, i64, i64]
+        L.fastgl_block_plan_bytes.restype = sz
+        L.fastgl_block_plan_create.argtypes = [p, p, i64, i64, i64, i32, p, sz, p, ctypes.POINTER(p)]
+        L.fastgl_block_plan_export.argtypes = [p, ctypes.POINTER(PlanView)]
+        L.fastgl_block_plan_destroy.argtypes = [p]
+        L.fastgl_block_plan_destroy.restype = None
+        L.fastgl_block_workspace_bytes.argtypes = [i64, i64, i64, i64, i32]
+        L.fastgl_block_workspace_bytes.restype = sz
+        L.fastgl_long_row_threshold.restype = ctypes.c_int32
+        L.fastgl_long_row_chunk.restype = ctypes.c_int32
+        L.fastgl_gather_rows.argtypes = [p, i64, p, i64, i64, i32, p, p]
+        L.fastgl_block_validate.argtypes = [p, p, i64, i64, i64, p, ctypes.POINTER(i64), p]
+        L.fastgl_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def fastgl_last_error() -> str:
+    return lib().fastgl_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != FASTGL_OK:
+        raise FastglError(status, fastgl_last_error())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous device tensor of {dtype}")
+    return t
+
+
+def _feat_dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return DTYPES["f32"]
+    if t.dtype == torch.bfloat16:
+        return DTYPES["bf16"]
+    raise TypeError("features must be float32 or bfloat16")
+
+
+def fastgl_long_row_threshold() -> int:
+    return int(lib().fastgl_long_row_threshold())
+
+
+def fastgl_long_row_chunk() -> int:
+    return int(lib().fastgl_long_row_chunk())
+
+
+def fastgl_block_plan_bytes(num_dst: int, num_src: int, num_edges: int) -> int:
+    return int(lib().fastgl_block_plan_bytes(num_dst, num_src, num_edges))
+
+
+def fastgl_block_workspace_bytes(num_dst: int, num_src: int, num_edges: int, feat: int, dtype: str) -> int:
+    return int(lib().fastgl_block_workspace_bytes(num_dst, num_src, num_edges, feat, DTYPES[dtype]))
+
+
+class Plan:
+    """Owner of one fastgl_plan handle and of the device buffer behind it."""
+
+    def __init__(self, handle, mem, indptr, indices, num_src):
+        self.handle, self.mem = handle, mem
+        self.indptr, self.indices, self.num_src = indptr, indices, num_src
+
+    def export(self) -> PlanView:
+        v = PlanView()
+        _check(lib().fastgl_block_plan_export(self.handle, ctypes.byref(v)))
+        return v
+
+    def destroy(self) -> None:
+        if self.handle is not None:
+            lib().fastgl_block_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.destroy()
+
+
+def fastgl_block_plan_create(indptr: torch.Tensor, indices: torch.Tensor, num_src: int,
+                             parts: int = PLAN_ALL, plan_mem: Optional[torch.Tensor] = None) -> Plan:
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    num_dst, num_edges = indptr.numel() - 1, indices.numel()
+    if plan_mem is None:
+        nbytes = fastgl_block_plan_bytes(num_dst, num_src, num_edges)
+        plan_mem = torch.empty(nbytes, dtype=torch.uint8, device=indptr.device)
+    out = ctypes.c_void_p()
+    _check(lib().fastgl_block_plan_create(_ptr(indptr), _ptr(indices), num_dst, num_src, num_edges, parts,
+                                          _ptr(plan_mem), plan_mem.numel(), _stream(), ctypes.byref(out)))
+    return Plan(out, plan_mem, indptr, indices, num_src)
+
+
+def _aggregate(fn, indptr, indices, edge_w, num_src, mode, inp, out, plan, workspace):
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    if edge_w is not None:
+        _dev(edge_w, torch.float32, "edge_w")
+    dt = _feat_dtype(inp)
+    _dev(inp, inp.dtype, "input features")
+    _dev(out, inp.dtype, "output features")
+    num_dst, num_edges, feat = indptr.numel() - 1, indices.numel(), inp.shape[1]
+    if workspace is None:
+        nbytes = int(lib().fastgl_block_workspace_bytes(num_dst, num_src, num_edges, feat, dt))
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=inp.device)
+    _check(fn(_ptr(indptr), _ptr(indices), _ptr(edge_w), num_dst, num_src, num_edges, feat, MODES[mode], dt,
+              _ptr(inp), _ptr(out), plan.handle if plan is not None else None, _ptr(workspace),
+              workspace.numel(), _stream()))
+    return out
+
+
+def fastgl_block_aggregate_fwd(indptr, indices, edge_w, num_src: int, mode: str, X: torch.Tensor,
+                               out: Optional[torch.Tensor] = None, plan: Optional[Plan] = None,
+                               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if X.shape[0] != num_src:
+        raise ValueError("X must have num_src rows")
+    if out is None:
+        out = torch.empty((indptr.numel() - 1, X.shape[1]), dtype=X.dtype, device=X.device)
+    elif out.shape != (indptr.numel() - 1, X.shape[1]):
+        raise ValueError("out must be [num_dst, feat]")
+    return _aggregate(lib().fastgl_block_aggregate_fwd, indptr, indices, edge_w, num_src, mode, X, out,
+                      plan, workspace)
+
+
+def fastgl_block_aggregate_bwd(indptr, indices, edge_w, num_src: int, mode: str, grad_out: torch.Tensor,
+                               grad_X: Optional[torch.Tensor] = None, plan: Optional[Plan] = None,
+                               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if grad_out.shape[0] != indptr.numel() - 1:
+        raise ValueError("grad_out must have num_dst rows")
+    if grad_X is None:
+        grad_X = torch.empty((num_src, grad_out.shape[1]), dtype=grad_out.dtype, device=grad_out.device)
+    elif grad_X.shape != (num_src, grad_out.shape[1]):
+        raise ValueError("grad_X must be [num_src, feat]")
+    return _aggregate(lib().fastgl_block_aggregate_bwd, indptr, indices, edge_w, num_src, mode, grad_out,
+                      grad_X, plan, workspace)
+
+
+def fastgl_gather_rows(table: torch.Tensor, ids: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    dt = _feat_dtype(table)
+    _dev(table, table.dtype, "table")
+    _dev(ids, torch.int64, "ids")
+    if out is None:
+        out = torch.empty((ids.numel(), table.shape[1]), dtype=table.dtype, device=table.device)
+    _dev(out, table.dtype, "out")
+    _check(lib().fastgl_gather_rows(_ptr(table), table.shape[0], _ptr(ids), ids.numel(), table.shape[1], dt,
+                                    _ptr(out), _stream()))
+    return out
+
+
+def fastgl_block_validate(indptr: torch.Tensor, indices: torch.Tensor, num_src: int) -> int:
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    scratch = torch.empty(2, dtype=torch.int64, device=indptr.device)
+    n = ctypes.c_int64(-1)
+    _check(lib().fastgl_block_validate(_ptr(indptr), _ptr(indices), indptr.numel() - 1, num_src,
+                                       indices.numel(), _ptr(scratch), ctypes.byref(n), _stream()))
+    return int(n.value)

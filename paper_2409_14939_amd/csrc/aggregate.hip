@@ -1,0 +1,402 @@
+// Pull-mode block aggregation for gfx950 (paper Section 2.1 Eq. 1 forward;
+// Section 4.2 Eq. 5 backward, run as the same pull over the transposed CSR).
+//
+//   out[r,:] = rowscale(len_r) * sum_{k in row r} a_k * colscale[col_k] * in[col_k,:]
+//
+// Mapping to the machine.  A feature row is cut into slices of VB bytes (16 when
+// the row size allows, so one lane moves one dwordx4) and a "group" of G lanes
+// (a power of two, <= 64) covers G consecutive slices.  One group owns one
+// (row, column tile) unit from start to end, so each output element has a single
+// writer and the summation order is fixed: results do not depend on scheduling.
+// The partial sum lives in registers (the paper keeps it in shared memory on its
+// GPU; with one lane per slice registers serve the same purpose at no traffic).
+// The lanes of a group fetch the row's column ids and weights with one coalesced
+// load and hand them round with cross-lane reads, then issue up to 8 independent
+// row gathers before the first use.
+//
+// f32 rows accumulate in fp64, bf16 rows in fp32; one rounding at the store.
+//
+// Rows longer than kLongThreshold edges are not walked by one group: they are
+// cut into chunks of kLongChunk edges that any group can take; the partial sums
+// go to the workspace and are added in chunk order by a second kernel, so the
+// result is still deterministic.
+#include "internal.h"
+
+namespace fastgl {
+
+constexpr int kUnroll = 8;
+
+template <int DT> struct AccT { using type = double; };
+template <> struct AccT<FASTGL_BF16> { using type = float; };
+
+template <int DT, int VB> struct Slice {
+    static constexpr int NW = VB >= 4 ? VB / 4 : 1;                           // 32-bit words held per lane
+    static constexpr int NE = DT == FASTGL_F32 ? VB / 4 : VB / 2;             // elements per lane
+    using acc_t = typename AccT<DT>::type;
+
+    __device__ static __forceinline__ void load(const char *p, uint32_t (&r)[NW])
+    {
+        if constexpr (VB == 16) {
+            uint4 v = *reinterpret_cast<const uint4 *>(p);
+            r[0] = v.x; r[1] = v.y; r[2] = v.z; r[3] = v.w;
+        } else if constexpr (VB == 8) {
+            uint2 v = *reinterpret_cast<const uint2 *>(p);
+            r[0] = v.x; r[1] = v.y;
+        } else if constexpr (VB == 4) {
+            r[0] = *reinterpret_cast<const uint32_t *>(p);
+        } else {
+            r[0] = *reinterpret_cast<const uint16_t *>(p);
+        }
+    }
+
+    template <bool HASW>
+    __device__ static __forceinline__ void fma(acc_t (&acc)[NE], const uint32_t (&r)[NW], acc_t w)
+    {
+        if constexpr (DT == FASTGL_F32) {
+#pragma unroll
+            for (int i = 0; i < NW; ++i) {
+                double x = (double)__uint_as_float(r[i]);
+                acc[i] = HASW ? __builtin_fma(x, w, acc[i]) : acc[i] + x;
+            }
+        } else if constexpr (VB >= 4) {
+#pragma unroll
+            for (int i = 0; i < NW; ++i) {
+                float lo = __uint_as_float(r[i] << 16), hi = __uint_as_float(r[i] & 0xFFFF0000u);
+                acc[2 * i] = HASW ? __builtin_fmaf(lo, w, acc[2 * i]) : acc[2 * i] + lo;
+                acc[2 * i + 1] = HASW ? __builtin_fmaf(hi, w, acc[2 * i + 1]) : acc[2 * i + 1] + hi;
+            }
+        } else {
+            float lo = __uint_as_float(r[0] << 16);
+            acc[0] = HASW ? __builtin_fmaf(lo, w, acc[0]) : acc[0] + lo;
+        }
+    }
+
+    __device__ static __forceinline__ uint32_t to_bf16(float f)
+    {
+        uint32_t u = __float_as_uint(f);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;   // keep NaN quiet
+        return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;                    // nearest even
+    }
+
+    __device__ static __forceinline__ void store(char *p, const acc_t (&acc)[NE], acc_t scale)
+    {
+        uint32_t r[NW];
+        if constexpr (DT == FASTGL_F32) {
+#pragma unroll
+            for (int i = 0; i < NW; ++i) r[i] = __float_as_uint((float)(acc[i] * scale));
+        } else if constexpr (VB >= 4) {
+#pragma unroll
+            for (int i = 0; i < NW; ++i)
+                r[i] = to_bf16(acc[2 * i] * scale) | (to_bf16(acc[2 * i + 1] * scale) << 16);
+        } else {
+            r[0] = to_bf16(acc[0] * scale);
+        }
+        if constexpr (VB == 16) *reinterpret_cast<uint4 *>(p) = make_uint4(r[0], r[1], r[2], r[3]);
+        else if constexpr (VB == 8) *reinterpret_cast<uint2 *>(p) = make_uint2(r[0], r[1]);
+        else if constexpr (VB == 4) *reinterpret_cast<uint32_t *>(p) = r[0];
+        else *reinterpret_cast<uint16_t *>(p) = (uint16_t)r[0];
+    }
+};
+
+struct PullParams {
+    const int32_t *rowptr, *col, *eid;
+    const float *edge_w, *col_scale;
+    const char *in;
+    char *out;
+    int64_t num_units;        // rows * ntiles
+    int32_t ntiles;           // column tiles per row
+    int32_t G;                // lanes per group (power of two)
+    int32_t row_mode;
+    int32_t long_thr;         // rows longer than this are left to the chunk kernels
+    int64_t row_bytes;        // bytes of one feature row
+    int64_t feat;
+    int64_t blocks_per_xcd;   // logical blocks each L2 domain owns
+    const int32_t *long_rows, *chunk_ptr, *n_long, *n_chunks;
+    char *partials;
+};
+
+template <typename acc_t>
+__device__ __forceinline__ acc_t row_scale(int mode, int len)
+{
+    acc_t d = (acc_t)(len < 1 ? 1 : len);
+    if (mode == 1) return (acc_t)1 / d;
+    if (mode == 2) return (acc_t)1 / (acc_t)sqrt((double)d);
+    return (acc_t)1;
+}
+
+template <typename T> __device__ __forceinline__ T shfl_t(T v, int src);
+template <> __device__ __forceinline__ float shfl_t<float>(float v, int src) { return __shfl(v, src, kWave); }
+template <> __device__ __forceinline__ double shfl_t<double>(double v, int src) { return __shfl(v, src, kWave); }
+
+// Accumulate edges [beg,end) of one row into acc.  `sub` is the lane's slot in
+// its group, `gbase` the wave lane of the group's slot 0, `p_in` the lane's
+// byte offset inside a feature row (valid only if `active`).
+template <int DT, int VB, bool HASW>
+__device__ __forceinline__ void walk_edges(const PullParams &P, int beg, int end, int sub, int gbase,
+                                           int64_t lane_off, bool active,
+                                           typename Slice<DT, VB>::acc_t (&acc)[Slice<DT, VB>::NE])
+{
+    using S = Slice<DT, VB>;
+    using acc_t = typename S::acc_t;
+    const int G = P.G;
+    for (int k0 = beg; k0 < end; k0 += G) {
+        const int n = end - k0 < G ? end - k0 : G;
+        int myc = 0;
+        acc_t myw = (acc_t)1;
+        if (sub < n) {
+            myc = P.col[k0 + sub];
+            if (HASW) {
+                if (P.edge_w) myw = (acc_t)P.edge_w[P.eid ? P.eid[k0 + sub] : k0 + sub];
+                if (P.col_scale) myw *= (acc_t)P.col_scale[myc];
+            }
+        }
+        for (int j0 = 0; j0 < n; j0 += kUnroll) {
+            uint32_t raw[kUnroll][S::NW];
+            acc_t w[kUnroll];
+#pragma unroll
+            for (int t = 0; t < kUnroll; ++t) {
+                const int j = j0 + t;
+                const int src = gbase + (j & (G - 1));
+                const int c = __shfl(myc, src, kWave);
+                if (HASW) w[t] = shfl_t<acc_t>(myw, src);
+                if (j < n && active) S::load(P.in + (int64_t)c * P.row_bytes + lane_off, raw[t]);
+            }
+#pragma unroll
+            for (int t = 0; t < kUnroll; ++t)
+                if (j0 + t < n && active) S::template fma<HASW>(acc, raw[t], HASW ? w[t] : (acc_t)1);
+        }
+    }
+}
+
+// Workgroup ids are dealt round-robin to the 8 L2 domains; give each domain a
+// contiguous run of logical blocks so neighbouring rows share one L2.
+__device__ __forceinline__ int64_t logical_block(int64_t per_xcd)
+{
+    return (int64_t)(blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+}
+
+template <int DT, int VB, bool HASW>
+__global__ __launch_bounds__(kBlock) void k_pull_rows(PullParams P)
+{
+    using S = Slice<DT, VB>;
+    using acc_t = typename S::acc_t;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
+    const int64_t unit = (logical_block(P.blocks_per_xcd) * kBlock + tid) / P.G;
+    if (unit >= P.num_units) return;
+    const int64_t row = unit / P.ntiles;
+    const int tile = (int)(unit - row * P.ntiles);
+    const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
+    const bool active = lane_off < P.row_bytes;
+    const int beg = P.rowptr[row], end = P.rowptr[row + 1];
+    if (end - beg > P.long_thr) return;
+    acc_t acc[S::NE];
+#pragma unroll
+    for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
+    walk_edges<DT, VB, HASW>(P, beg, end, sub, gbase, lane_off, active, acc);
+    if (active) S::store(P.out + row * P.row_bytes + lane_off, acc, row_scale<acc_t>(P.row_mode, end - beg));
+}
+
+// One unit = (chunk of a long row, column tile); grid-stride over a count that
+// lives in device memory, so the host never needs to know the degrees.
+template <int DT, int VB, bool HASW>
+__global__ __launch_bounds__(kBlock) void k_pull_chunks(PullParams P)
+{
+    using S = Slice<DT, VB>;
+    using acc_t = typename S::acc_t;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
+    const int n_long = *P.n_long;
+    const int64_t total = (int64_t)(*P.n_chunks) * P.ntiles;
+    const int64_t stride = (int64_t)gridDim.x * kBlock / P.G;
+    for (int64_t unit = ((int64_t)blockIdx.x * kBlock + tid) / P.G; unit < total; unit += stride) {
+        const int chunk = (int)(unit / P.ntiles);
+        const int tile = (int)(unit - (int64_t)chunk * P.ntiles);
+        int lo = 0, hi = n_long;   // chunk_ptr[lo] <= chunk < chunk_ptr[hi]
+        while (hi - lo > 1) {
+            int mid = lo + ((hi - lo) >> 1);
+            if (P.chunk_ptr[mid] <= chunk) lo = mid; else hi = mid;
+        }
+        const int row = P.long_rows[lo];
+        const int rbeg = P.rowptr[row], rend = P.rowptr[row + 1];
+        const int beg = rbeg + (chunk - P.chunk_ptr[lo]) * kLongChunk;
+        const int end = beg + kLongChunk < rend ? beg + kLongChunk : rend;
+        const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
+        const bool active = lane_off < P.row_bytes;
+        acc_t acc[S::NE];
+#pragma unroll
+        for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
+        walk_edges<DT, VB, HASW>(P, beg, end, sub, gbase, lane_off, active, acc);
+        if (active) {
+            acc_t *dst = reinterpret_cast<acc_t *>(P.partials) + (int64_t)chunk * P.feat +
+                         ((int64_t)tile * P.G + sub) * S::NE;
+#pragma unroll
+            for (int i = 0; i < S::NE; ++i) dst[i] = acc[i];
+        }
+    }
+}
+
+template <int DT, int VB>
+__global__ __launch_bounds__(kBlock) void k_reduce_chunks(PullParams P)
+{
+    using S = Slice<DT, VB>;
+    using acc_t = typename S::acc_t;
+    const int tid = threadIdx.x;
+    const int sub = tid & (P.G - 1);
+    const int64_t total = (int64_t)(*P.n_long) * P.ntiles;
+    const int64_t stride = (int64_t)gridDim.x * kBlock / P.G;
+    for (int64_t unit = ((int64_t)blockIdx.x * kBlock + tid) / P.G; unit < total; unit += stride) {
+        const int li = (int)(unit / P.ntiles);
+        const int tile = (int)(unit - (int64_t)li * P.ntiles);
+        const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
+        if (lane_off >= P.row_bytes) continue;
+        const int row = P.long_rows[li];
+        acc_t acc[S::NE];
+#pragma unroll
+        for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
+        const acc_t *src = reinterpret_cast<const acc_t *>(P.partials) + ((int64_t)tile * P.G + sub) * S::NE;
+        for (int c = P.chunk_ptr[li]; c < P.chunk_ptr[li + 1]; ++c) {
+#pragma unroll
+            for (int i = 0; i < S::NE; ++i) acc[i] += src[(int64_t)c * P.feat + i];
+        }
+        const int len = P.rowptr[row + 1] - P.rowptr[row];
+        S::store(P.out + (int64_t)row * P.row_bytes + lane_off, acc, row_scale<acc_t>(P.row_mode, len));
+    }
+}
+
+template <int VB>
+__global__ __launch_bounds__(kBlock) void k_gather_rows(const char *__restrict__ table,
+                                                        const int64_t *__restrict__ ids, int64_t num_units,
+                                                        int32_t ntiles, int32_t G, int64_t row_bytes,
+                                                        char *__restrict__ out)
+{
+    const int tid = threadIdx.x;
+    const int sub = tid & (G - 1);
+    const int64_t unit = ((int64_t)blockIdx.x * kBlock + tid) / G;
+    if (unit >= num_units) return;
+    const int64_t row = unit / ntiles;
+    const int tile = (int)(unit - row * ntiles);
+    const int64_t lane_off = ((int64_t)tile * G + sub) * VB;
+    if (lane_off >= row_bytes) return;
+    uint32_t r[Slice<FASTGL_BF16, VB>::NW];
+    Slice<FASTGL_BF16, VB>::load(table + ids[row] * row_bytes + lane_off, r);
+    char *p = out + row * row_bytes + lane_off;
+    if constexpr (VB == 16) *reinterpret_cast<uint4 *>(p) = make_uint4(r[0], r[1], r[2], r[3]);
+    else if constexpr (VB == 8) *reinterpret_cast<uint2 *>(p) = make_uint2(r[0], r[1]);
+    else if constexpr (VB == 4) *reinterpret_cast<uint32_t *>(p) = r[0];
+    else *reinterpret_cast<uint16_t *>(p) = (uint16_t)r[0];
+}
+
+// ------------------------------------------------------------- host side ----
+// Largest slice width (bytes) that divides the row size and the buffer alignment.
+static int pick_slice_bytes(int64_t row_bytes, const void *a, const void *b, int elem)
+{
+    uintptr_t bits = (uintptr_t)a | (uintptr_t)b | (uintptr_t)row_bytes;
+    for (int vb = 16; vb > elem; vb >>= 1)
+        if ((bits & (uintptr_t)(vb - 1)) == 0) return vb;
+    return elem;
+}
+
+static void group_shape(int64_t row_bytes, int vb, int *G, int *ntiles)
+{
+    int64_t slices = row_bytes / vb;
+    int g = 1;
+    while (g < kWave && g < slices) g <<= 1;
+    *G = g;
+    *ntiles = (int)ceil_div(slices, g);
+}
+
+template <int DT, int VB>
+static fastgl_status launch_typed(const PullParams &P, bool hasw, bool with_long, int64_t nblocks, hipStream_t s)
+{
+    if (nblocks > 0) {
+        dim3 grid((unsigned)(P.blocks_per_xcd * kXcds));
+        if (hasw) hipLaunchKernelGGL((k_pull_rows<DT, VB, true>), grid, dim3(kBlock), 0, s, P);
+        else hipLaunchKernelGGL((k_pull_rows<DT, VB, false>), grid, dim3(kBlock), 0, s, P);
+        FASTGL_LAUNCH_CHECK("k_pull_rows");
+    }
+    if (with_long) {
+        dim3 grid(2048);
+        if (hasw) hipLaunchKernelGGL((k_pull_chunks<DT, VB, true>), grid, dim3(kBlock), 0, s, P);
+        else hipLaunchKernelGGL((k_pull_chunks<DT, VB, false>), grid, dim3(kBlock), 0, s, P);
+        FASTGL_LAUNCH_CHECK("k_pull_chunks");
+        hipLaunchKernelGGL((k_reduce_chunks<DT, VB>), dim3(512), dim3(kBlock), 0, s, P);
+        FASTGL_LAUNCH_CHECK("k_reduce_chunks");
+    }
+    return FASTGL_OK;
+}
+
+fastgl_status launch_pull(const PullDesc &d, hipStream_t s)
+{
+    if (d.num_rows == 0) return FASTGL_OK;
+    const int elem = d.dtype == FASTGL_F32 ? 4 : 2;
+    PullParams P;
+    P.rowptr = d.rowptr; P.col = d.col; P.eid = d.eid;
+    P.edge_w = d.edge_w; P.col_scale = d.col_scale;
+    P.in = (const char *)d.in; P.out = (char *)d.out;
+    P.row_bytes = d.feat * elem;
+    P.feat = d.feat;
+    P.row_mode = d.row_mode;
+    const int vb = pick_slice_bytes(P.row_bytes, d.in, d.out, elem);
+    int G, ntiles;
+    group_shape(P.row_bytes, vb, &G, &ntiles);
+    P.G = G; P.ntiles = ntiles;
+    P.num_units = d.num_rows * ntiles;
+    const bool with_long = d.long_rows != nullptr;
+    P.long_thr = with_long ? kLongThreshold : INT32_MAX;
+    P.long_rows = d.long_rows; P.chunk_ptr = d.chunk_ptr; P.n_long = d.n_long; P.n_chunks = d.n_chunks;
+    P.partials = (char *)d.partials;
+    const int64_t nblocks = ceil_div(P.num_units * G, kBlock);
+    P.blocks_per_xcd = ceil_div(nblocks, kXcds);
+    if (P.blocks_per_xcd * kXcds > 0x7FFFFFFFLL) {
+        set_error("block too large for one launch (%lld workgroups)", (long long)nblocks);
+        return FASTGL_ERR_UNSUPPORTED;
+    }
+    const bool hasw = d.edge_w != nullptr || d.col_scale != nullptr;
+#define FASTGL_CASE(DT, VB) return launch_typed<DT, VB>(P, hasw, with_long, nblocks, s)
+    if (d.dtype == FASTGL_F32) {
+        switch (vb) {
+            case 16: FASTGL_CASE(FASTGL_F32, 16);
+            case 8: FASTGL_CASE(FASTGL_F32, 8);
+            default: FASTGL_CASE(FASTGL_F32, 4);
+        }
+    } else {
+        switch (vb) {
+            case 16: FASTGL_CASE(FASTGL_BF16, 16);
+            case 8: FASTGL_CASE(FASTGL_BF16, 8);
+            case 4: FASTGL_CASE(FASTGL_BF16, 4);
+            default: FASTGL_CASE(FASTGL_BF16, 2);
+        }
+    }
+#undef FASTGL_CASE
+}
+
+fastgl_status launch_gather_rows(const void *table, const int64_t *ids, int64_t n, int64_t feat,
+                                 fastgl_dtype dtype, void *out, hipStream_t s)
+{
+    if (n == 0) return FASTGL_OK;
+    const int elem = dtype == FASTGL_F32 ? 4 : 2;
+    const int64_t row_bytes = feat * elem;
+    const int vb = pick_slice_bytes(row_bytes, table, out, elem);
+    int G, ntiles;
+    group_shape(row_bytes, vb, &G, &ntiles);
+    const int64_t units = n * ntiles;
+    const int64_t nblocks = ceil_div(units * G, kBlock);
+    if (nblocks > 0x7FFFFFFFLL) {
+        set_error("gather too large for one launch");
+        return FASTGL_ERR_UNSUPPORTED;
+    }
+    dim3 grid((unsigned)nblocks);
+    const char *t = (const char *)table;
+    char *o = (char *)out;
+    switch (vb) {
+        case 16: hipLaunchKernelGGL(k_gather_rows<16>, grid, dim3(kBlock), 0, s, t, ids, units, ntiles, G, row_bytes, o); break;
+        case 8: hipLaunchKernelGGL(k_gather_rows<8>, grid, dim3(kBlock), 0, s, t, ids, units, ntiles, G, row_bytes, o); break;
+        case 4: hipLaunchKernelGGL(k_gather_rows<4>, grid, dim3(kBlock), 0, s, t, ids, units, ntiles, G, row_bytes, o); break;
+        default: hipLaunchKernelGGL(k_gather_rows<2>, grid, dim3(kBlock), 0, s, t, ids, units, ntiles, G, row_bytes, o); break;
+    }
+    FASTGL_LAUNCH_CHECK("k_gather_rows");
+    return FASTGL_OK;
+}
+
+}  // namespace fastgl

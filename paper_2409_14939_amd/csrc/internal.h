@@ -1,0 +1,91 @@
+// Internal declarations shared by the translation units of libfastgl_agg.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fastgl_agg.h"
+
+namespace fastgl {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;            // threads per workgroup (4 wavefronts)
+constexpr int kLongThreshold = 256;    // rows longer than this go through the chunked path
+constexpr int kLongChunk = 128;        // edges per partial-sum chunk
+constexpr int kMaxScanBlocks = 1024;   // blocks of a two-kernel scan / compaction
+constexpr int kRadixBits = 8;
+constexpr int kRadixBins = 1 << kRadixBits;
+constexpr int kSortTile = 256;         // keys ranked per step by one sort block
+constexpr int kXcds = 8;               // workgroups are dealt round-robin to 8 L2 domains
+
+void set_error(const char *fmt, ...);
+fastgl_status hip_fail(hipError_t e, const char *what);
+
+#define FASTGL_HIP(call)                                                    \
+    do {                                                                    \
+        hipError_t e__ = (call);                                            \
+        if (e__ != hipSuccess) return ::fastgl::hip_fail(e__, #call);       \
+    } while (0)
+
+#define FASTGL_LAUNCH_CHECK(name)                                           \
+    do {                                                                    \
+        hipError_t e__ = hipGetLastError();                                 \
+        if (e__ != hipSuccess) return ::fastgl::hip_fail(e__, name);        \
+    } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Upper bounds used to size the bucket arrays without knowing the degrees.
+inline int64_t cap_long_rows(int64_t num_edges) { return num_edges / (kLongThreshold + 1) + 1; }
+inline int64_t cap_chunks(int64_t num_edges) { return num_edges / kLongChunk + cap_long_rows(num_edges) + 1; }
+
+}  // namespace fastgl
+
+// Host handle of a plan: device pointers carved out of the caller's buffer.
+struct fastgl_plan {
+    int64_t num_dst, num_src, num_edges;
+    const int32_t *indptr, *indices;
+    int parts;
+    int32_t *din, *dout, *indptr_T, *indices_T, *perm;
+    float *dst_inv, *dst_rsqrt, *src_rsqrt;
+    int32_t *long_dst, *chunk_ptr_dst, *long_src, *chunk_ptr_src;
+    int32_t *counters;      // [4] n_long_dst, n_chunks_dst, n_long_src, n_chunks_src
+    // scratch
+    int32_t *sort_buf[4];   // ping-pong keys / values, num_edges each
+    int32_t *radix_cnt;     // kRadixBins * sort blocks
+    int32_t *block_sums;    // 2 * kMaxScanBlocks
+};
+
+namespace fastgl {
+
+size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges);
+fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipStream_t s);
+
+struct PullDesc {
+    const int32_t *rowptr;     // [num_rows+1]
+    const int32_t *col;        // [nnz] gathered row of `in` per edge
+    const int32_t *eid;        // [nnz] index into edge_w, or NULL for identity
+    const float *edge_w;       // or NULL
+    const float *col_scale;    // [rows of in] or NULL
+    int row_mode;              // 0: none, 1: 1/len, 2: 1/sqrt(len)  (len clamped to >= 1)
+    int64_t num_rows;          // rows of out
+    int64_t num_cols;          // rows of in
+    int64_t nnz;
+    int64_t feat;
+    fastgl_dtype dtype;
+    const void *in;
+    void *out;
+    // long-row bucket (device-resident counts)
+    const int32_t *long_rows, *chunk_ptr, *n_long, *n_chunks;
+    void *partials;            // cap_chunks * feat accumulators
+};
+
+fastgl_status launch_pull(const PullDesc &d, hipStream_t s);
+fastgl_status launch_gather_rows(const void *table, const int64_t *ids, int64_t n, int64_t feat,
+                                 fastgl_dtype dtype, void *out, hipStream_t s);
+fastgl_status validate_block(const int32_t *indptr, const int32_t *indices, int64_t num_dst,
+                             int64_t num_src, int64_t num_edges, void *scratch, int64_t *n_violations,
+                             hipStream_t s);
+
+}  // namespace fastgl

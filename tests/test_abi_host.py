@@ -1,0 +1,79 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared
+symbol, and rejects bad arguments before any GPU work (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2409_14939_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "fastgl_agg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fastgl_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = B.lib()
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_constants_and_sizes():
+    assert B.fastgl_long_row_threshold() >= B.fastgl_long_row_chunk() > 0
+    small = B.fastgl_block_plan_bytes(10, 10, 10)
+    big = B.fastgl_block_plan_bytes(1000, 1000, 100000)
+    assert 0 < small < big
+    assert B.fastgl_block_workspace_bytes(10, 10, 10, 8, "f32") > small
+    assert B.fastgl_block_plan_bytes(-1, 10, 10) == 0
+    assert B.fastgl_block_workspace_bytes(10, 10, 10, 0, "f32") == 0
+
+
+FAKE = ctypes.c_void_p(0x1000)     # aligned, never dereferenced: the calls below fail before any launch
+
+
+def fwd(indptr=FAKE, indices=FAKE, w=None, nd=4, ns=4, ne=4, feat=8, mode=0, dt=0, X=FAKE, out=FAKE,
+        plan=None, ws=FAKE, wsb=1 << 30):
+    return B.lib().fastgl_block_aggregate_fwd(indptr, indices, w, nd, ns, ne, feat, mode, dt, X, out, plan,
+                                              ws, wsb, None)
+
+
+@pytest.mark.parametrize("kw,status,text", [
+    (dict(nd=-1), B.FASTGL_ERR_INVALID_ARG, "negative"),
+    (dict(feat=0), B.FASTGL_ERR_INVALID_ARG, "feat"),
+    (dict(mode=3), B.FASTGL_ERR_INVALID_ARG, "mode"),
+    (dict(dt=2), B.FASTGL_ERR_INVALID_ARG, "dtype"),
+    (dict(indptr=None), B.FASTGL_ERR_INVALID_ARG, "indptr"),
+    (dict(indices=None), B.FASTGL_ERR_INVALID_ARG, "indices"),
+    (dict(X=None), B.FASTGL_ERR_INVALID_ARG, "NULL"),
+    (dict(out=ctypes.c_void_p(0x1002)), B.FASTGL_ERR_INVALID_ARG, "aligned"),
+    (dict(ws=None), B.FASTGL_ERR_INVALID_ARG, "workspace"),
+    (dict(ws=ctypes.c_void_p(0x1010)), B.FASTGL_ERR_INVALID_ARG, "workspace"),
+    (dict(wsb=16), B.FASTGL_ERR_WORKSPACE, "too small"),
+    (dict(ns=2 ** 31), B.FASTGL_ERR_UNSUPPORTED, "2^31"),
+    (dict(nd=0, ne=3), B.FASTGL_ERR_INVALID_ARG, "at least one"),
+])
+def test_bad_arguments_are_refused_before_launch(kw, status, text):
+    assert fwd(**kw) == status
+    assert text in B.fastgl_last_error()
+
+
+def test_plan_and_gather_argument_checks():
+    L = B.lib()
+    out = ctypes.c_void_p()
+    assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 7, FAKE, 1 << 30, None, ctypes.byref(out)) == B.FASTGL_ERR_INVALID_ARG
+    assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 3, FAKE, 8, None, ctypes.byref(out)) == B.FASTGL_ERR_WORKSPACE
+    assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 3, None, 1 << 30, None, ctypes.byref(out)) == B.FASTGL_ERR_INVALID_ARG
+    assert out.value is None
+    assert L.fastgl_block_plan_export(None, None) == B.FASTGL_ERR_INVALID_ARG
+    L.fastgl_block_plan_destroy(None)
+    assert L.fastgl_gather_rows(FAKE, 10, FAKE, 3, 0, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert L.fastgl_gather_rows(None, 10, FAKE, 3, 8, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    n = ctypes.c_int64()
+    assert L.fastgl_block_validate(FAKE, FAKE, 4, 4, 4, None, ctypes.byref(n), None) == B.FASTGL_ERR_INVALID_ARG

@@ -1,0 +1,223 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element, on the same seeded inputs.  Tolerances: fp32 1e-5 relative + 1e-6
+absolute, bf16 2e-2 relative (+1e-5 absolute); integer bookkeeping bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import blockgen as bg
+import oracle
+from paper_2409_14939_amd import binding as B
+from gpu_util import (assert_close, dev_feat, dev_i32, host_feat, make_inputs, read_f32, read_i32)
+
+pytestmark = pytest.mark.gpu
+MODES = ["sum", "mean", "gcn"]
+
+
+def run_both(blk, w, mode, dtype, X, G, use_plan):
+    ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
+    wd = None if w is None else torch.from_numpy(w).cuda()
+    plan = B.fastgl_block_plan_create(ip, ix, blk.num_src) if use_plan else None
+    out = B.fastgl_block_aggregate_fwd(ip, ix, wd, blk.num_src, mode, dev_feat(X, dtype), plan=plan)
+    dX = B.fastgl_block_aggregate_bwd(ip, ix, wd, blk.num_src, mode, dev_feat(G, dtype), plan=plan)
+    torch.cuda.synchronize()
+    return host_feat(out, dtype), host_feat(dX, dtype)
+
+
+def check_block(blk, mode, dtype, feat, weighted, use_plan, seed, what):
+    rng = np.random.default_rng(seed)
+    w = rng.standard_normal(blk.num_edges).astype(np.float32) if weighted else None
+    X = make_inputs(rng, blk.num_src, feat, dtype)
+    G = make_inputs(rng, blk.num_dst, feat, dtype)
+    print(f"case {what} mode={mode} dtype={dtype} F={feat} weighted={weighted} plan={use_plan} "
+          f"dst={blk.num_dst} src={blk.num_src} E={blk.num_edges}", flush=True)
+    out, dX = run_both(blk, w, mode, dtype, X, G, use_plan)
+    assert_close(out, oracle.aggregate_fwd(blk.indptr, blk.indices, w, blk.num_src, mode, dtype, X), dtype,
+                 what + " fwd")
+    assert_close(dX, oracle.aggregate_bwd(blk.indptr, blk.indices, w, blk.num_src, mode, dtype, G), dtype,
+                 what + " bwd")
+
+
+def ragged_block(seed=21):
+    # several workgroups of rows, a ragged tail, empty rows, duplicate edges, rows
+    # above the long-row threshold (one spanning many chunks), unreferenced sources
+    rng = np.random.default_rng(seed)
+    return bg.random_block(rng, 1237, 3001, 6.0, empty_frac=0.15, hub_rows=5, hub_deg=1500)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("feat", [1, 3, 32, 64, 100, 128, 256, 602])
+def test_parity_ragged(dtype, mode, feat):
+    weighted = (feat % 3) == 0 or feat == 100
+    use_plan = feat not in (3, 128)
+    check_block(ragged_block(), mode, dtype, feat, weighted, use_plan, 100 + feat, "ragged")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_parity_degenerate(dtype):
+    rng = np.random.default_rng(5)
+    cases = {
+        "no-edges": bg.random_block(rng, 9, 17, 0.0, empty_frac=1.0),
+        "one-by-one": bg.Block(np.array([0, 1], np.int32), np.array([0], np.int32), 1, 1),
+        "single-hub": bg.random_block(rng, 1, 50, 0.0, empty_frac=0.0, hub_rows=1, hub_deg=5000),
+        "exact-threshold": bg.random_block(rng, 3, 40, 0.0, empty_frac=0.0, hub_rows=3,
+                                           hub_deg=B.fastgl_long_row_threshold()),
+        "threshold-plus-one": bg.random_block(rng, 3, 40, 0.0, empty_frac=0.0, hub_rows=3,
+                                              hub_deg=B.fastgl_long_row_threshold() + 1),
+    }
+    for name, blk in cases.items():
+        for mode in MODES:
+            check_block(blk, mode, dtype, 20, True, True, 7, name)
+            check_block(blk, mode, dtype, 20, False, False, 7, name)
+
+
+def test_zero_sized_blocks():
+    ip = dev_i32(np.zeros(1, np.int32))
+    ix = torch.empty(0, dtype=torch.int32, device="cuda")
+    X = torch.randn(5, 8, device="cuda")
+    out = B.fastgl_block_aggregate_fwd(ip, ix, None, 5, "sum", X)            # num_dst == 0
+    assert out.shape == (0, 8)
+    dX = B.fastgl_block_aggregate_bwd(ip, ix, None, 5, "gcn", torch.empty(0, 8, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.all(dX == 0) and dX.shape == (5, 8)
+    ip = dev_i32(np.zeros(4, np.int32))
+    out = B.fastgl_block_aggregate_fwd(ip, ix, None, 0, "mean", torch.empty(0, 8, device="cuda"))  # num_src == 0
+    torch.cuda.synchronize()
+    assert torch.all(out == 0) and out.shape == (3, 8)
+
+
+def check_bookkeeping(blk, what):
+    print(f"bookkeeping {what} dst={blk.num_dst} src={blk.num_src} E={blk.num_edges}", flush=True)
+    ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
+    assert B.fastgl_block_validate(ip, ix, blk.num_src) == 0
+    plan = B.fastgl_block_plan_create(ip, ix, blk.num_src)
+    v = plan.export()
+    e, nd, ns = blk.num_edges, blk.num_dst, blk.num_src
+    din, dout = oracle.degrees(blk.indptr, blk.indices, ns)
+    pT, iT, perm = oracle.transpose(blk.indptr, blk.indices, ns)
+    assert np.array_equal(read_i32(plan, v.din, nd), din)
+    assert np.array_equal(read_i32(plan, v.dout, ns), dout)
+    assert np.array_equal(read_i32(plan, v.indptr_T, ns + 1), pT)
+    assert np.array_equal(read_i32(plan, v.perm, e), perm)
+    assert np.array_equal(read_i32(plan, v.indices_T, e), iT)
+    thr, ch = B.fastgl_long_row_threshold(), B.fastgl_long_row_chunk()
+    cnt = read_i32(plan, v.counters, 4)
+    for rowptr, lr, cp, c in ((blk.indptr, v.long_dst, v.chunk_ptr_dst, cnt[0:2]),
+                              (pT, v.long_src, v.chunk_ptr_src, cnt[2:4])):
+        rows, cptr = oracle.long_rows(rowptr, thr, ch)
+        assert c[0] == rows.shape[0] and c[1] == cptr[-1]
+        assert np.array_equal(read_i32(plan, lr, rows.shape[0]), rows)
+        assert np.array_equal(read_i32(plan, cp, rows.shape[0] + 1), cptr)
+    # scale factors: correctly rounded fp32 of the fp64 value
+    np.testing.assert_allclose(read_f32(plan, v.dst_inv, nd), 1.0 / np.maximum(din, 1), rtol=1e-6)
+    np.testing.assert_allclose(read_f32(plan, v.dst_rsqrt, nd), 1.0 / np.sqrt(np.maximum(din, 1)), rtol=1e-6)
+    np.testing.assert_allclose(read_f32(plan, v.src_rsqrt, ns), 1.0 / np.sqrt(np.maximum(dout, 1)), rtol=1e-6)
+    plan.destroy()
+
+
+def test_bookkeeping_bit_exact_small():
+    rng = np.random.default_rng(31)
+    check_bookkeeping(ragged_block(), "ragged")
+    check_bookkeeping(bg.random_block(rng, 9, 17, 0.0, empty_frac=1.0), "no-edges")
+    check_bookkeeping(bg.random_block(rng, 70000, 300, 3.0), "few-sources")          # one radix pass... two
+    check_bookkeeping(bg.random_block(rng, 300, 70000, 40.0, hub_rows=2, hub_deg=9000), "many-sources")
+    check_bookkeeping(bg.make_config(1).blocks[0], "config1")
+
+
+def test_validate_counts_violations():
+    blk = ragged_block()
+    bad = blk.indices.copy()
+    bad[5] = blk.num_src
+    bad[77] = -1
+    ptr = blk.indptr.copy()
+    ptr[10], ptr[11] = ptr[11], ptr[10] - 0   # make one decreasing step if the two differ
+    n = B.fastgl_block_validate(dev_i32(blk.indptr), dev_i32(bad), blk.num_src)
+    assert n == 2
+    if blk.indptr[10] != blk.indptr[11]:
+        assert B.fastgl_block_validate(dev_i32(ptr), dev_i32(blk.indices), blk.num_src) >= 1
+
+
+def test_deterministic_bitwise():
+    blk = ragged_block()
+    rng = np.random.default_rng(3)
+    X = make_inputs(rng, blk.num_src, 100, "f32")
+    G = make_inputs(rng, blk.num_dst, 100, "f32")
+    a = run_both(blk, None, "gcn", "f32", X, G, True)
+    b = run_both(blk, None, "gcn", "f32", X, G, False)
+    assert a[0].tobytes() == b[0].tobytes() and a[1].tobytes() == b[1].tobytes()
+
+
+def test_gather_rows():
+    rng = np.random.default_rng(4)
+    for dtype, feat in (("bf16", 128), ("f32", 100), ("bf16", 7), ("f32", 602)):
+        T = make_inputs(rng, 5000, feat, dtype)
+        ids = rng.integers(0, 5000, size=1777)
+        got = B.fastgl_gather_rows(dev_feat(T, dtype), torch.from_numpy(ids).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(host_feat(got, dtype), oracle.gather_rows(T, ids, dtype))
+
+
+# ---- the five workloads at full size --------------------------------------------------
+def check_workload(w, layers=None):
+    for li, (blk, feat) in enumerate(zip(w.blocks, w.widths)):
+        if layers is not None and li not in layers:
+            continue
+        check_bookkeeping(blk, f"{w.name} layer {li}")
+        check_block(blk, w.mode, w.dtype, feat, False, True, w.seed + li, f"{w.name} layer {li}")
+
+
+def test_config1_tiny():
+    check_workload(bg.make_config(1))
+
+
+def test_config2_products_shaped():
+    check_workload(bg.make_config(2))
+
+
+def test_config3_reddit_shaped():
+    check_workload(bg.make_config(3))
+
+
+def test_config5_skew_stress():
+    check_workload(bg.make_config(5, width=32))
+    w = bg.make_config(5, width=256)
+    blk = w.blocks[0]
+    check_block(blk, w.mode, w.dtype, 256, False, True, w.seed, w.name)
+
+
+def test_config4_papers_shaped_table_gather():
+    """bf16 feature table of the full 111M x 128 shape lives on the device; the
+    sampled source rows are gathered by global id, then aggregated layer by layer."""
+    w = bg.make_config(4)
+    n, feat = w.table_rows, w.widths[0]
+    print(f"filling {n} x {feat} bf16 table", flush=True)
+    table = torch.empty((n, feat), dtype=torch.bfloat16, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(w.seed)
+    step = 8_000_000
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        table[lo:hi] = torch.randn((hi - lo, feat), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    gid = torch.from_numpy(w.src_gid).cuda()
+    X0 = B.fastgl_gather_rows(table, gid)
+    torch.cuda.synchronize()
+    ref_rows = table.index_select(0, gid)          # library path, independent of the kernel under test
+    assert torch.equal(X0.view(torch.int16), ref_rows.view(torch.int16))
+    X0_host = host_feat(X0, "bf16")
+    del table
+    blk = w.blocks[0]
+    rng = np.random.default_rng(w.seed)
+    ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
+    out = B.fastgl_block_aggregate_fwd(ip, ix, None, blk.num_src, w.mode, X0)
+    torch.cuda.synchronize()
+    assert_close(host_feat(out, "bf16"),
+                 oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, "bf16", X0_host),
+                 "bf16", "config4 layer 0 fwd from gathered table rows")
+    G = make_inputs(rng, blk.num_dst, feat, "bf16")
+    dX = B.fastgl_block_aggregate_bwd(ip, ix, None, blk.num_src, w.mode, dev_feat(G, "bf16"))
+    torch.cuda.synchronize()
+    assert_close(host_feat(dX, "bf16"),
+                 oracle.aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, "bf16", G),
+                 "bf16", "config4 layer 0 bwd")
+    check_workload(w, layers=[1, 2])
