@@ -1,0 +1,253 @@
+"""Benchmark of the block-aggregation hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one sampled mini-batch of the
+products-shaped 3-layer GCN workload: for every layer, build the block's
+bookkeeping (plan) and run the forward aggregation; then run the backward
+aggregation of every layer in reverse order.  All inputs are synthetic, seeded
+and already resident in HBM when the timed region starts.
+
+Prints ONE JSON line:
+  value     aggregated GEdges/s = 2 * sum(E_layer) / step time (plan build included)
+  roofline  achieved HBM GB/s of the dominant kernel from compulsory bytes
+            (indptr + indices + unique source rows + output) against 8 TB/s
+  cpu_baseline  the CPU oracle's parallel variant timed on the host cores
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "aggregated GEdges/s (fwd+bwd) and achieved HBM GB/s vs peak, 1 MI355X"
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
+# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
+# summaries live under profiles/.  None until measured for the current kernel.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def compulsory_bytes(rowptr_rows, nnz, used_in_rows, out_rows, feat, elem):
+    """indptr + indices + each referenced input row once + every output row once."""
+    return 4 * (rowptr_rows + 1) + 4 * nnz + used_in_rows * feat * elem + out_rows * feat * elem
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline)")
+    ap.add_argument("--width", type=int, default=32, help="feature width of config 5")
+    ap.add_argument("--fanout-order", default="A", choices=["A", "B"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verbose", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
+              "(data-parallel training gives every GPU its own mini-batch and needs no "
+              "communication in the aggregation path)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import blockgen as bg
+    from paper_2409_14939_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    t0 = time.time()
+    w = bg.make_config(args.config, fanout_order=args.fanout_order, width=args.width)
+    gen_s = time.time() - t0
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    elem = 4 if w.dtype == "f32" else 2
+
+    layers = []
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed)
+    ws_bytes = 0
+    for blk, feat in zip(w.blocks, w.widths):
+        L = dict(blk=blk, feat=feat)
+        L["indptr"] = torch.from_numpy(blk.indptr).to(dev)
+        L["indices"] = torch.from_numpy(blk.indices).to(dev)
+        L["X"] = torch.randn((blk.num_src, feat), generator=g, device=dev, dtype=torch.float32).to(tdt)
+        L["G"] = torch.randn((blk.num_dst, feat), generator=g, device=dev, dtype=torch.float32).to(tdt)
+        L["out"] = torch.empty((blk.num_dst, feat), device=dev, dtype=tdt)
+        L["dX"] = torch.empty((blk.num_src, feat), device=dev, dtype=tdt)
+        L["plan_mem"] = torch.empty(B.fastgl_block_plan_bytes(blk.num_dst, blk.num_src, blk.num_edges),
+                                    dtype=torch.uint8, device=dev)
+        ws_bytes = max(ws_bytes, B.fastgl_block_workspace_bytes(blk.num_dst, blk.num_src, blk.num_edges,
+                                                                feat, w.dtype))
+        din = np.diff(blk.indptr)
+        dout = np.bincount(blk.indices, minlength=blk.num_src)
+        L["bytes_fwd"] = compulsory_bytes(blk.num_dst, blk.num_edges, int((dout > 0).sum()), blk.num_dst, feat, elem)
+        L["bytes_bwd"] = compulsory_bytes(blk.num_src, blk.num_edges, int((din > 0).sum()), blk.num_src, feat, elem)
+        layers.append(L)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    table = gid = None
+    gather_bytes = 0
+    if w.src_gid is not None:
+        # config 4: the raw features sit in a device-resident table and are gathered by global id
+        feat0 = w.widths[0]
+        table = torch.empty((w.table_rows, feat0), dtype=tdt, device=dev)
+        for lo in range(0, w.table_rows, 8_000_000):
+            hi = min(w.table_rows, lo + 8_000_000)
+            table[lo:hi] = torch.randn((hi - lo, feat0), generator=g, device=dev, dtype=torch.float32).to(tdt)
+        gid = torch.from_numpy(w.src_gid).to(dev)
+        gather_bytes = 8 * gid.numel() + 2 * gid.numel() * feat0 * elem
+    total_edges = w.total_edges()
+    bytes_step = sum(L["bytes_fwd"] + L["bytes_bwd"] for L in layers) + gather_bytes
+
+    def make_plan(L):
+        return B.fastgl_block_plan_create(L["indptr"], L["indices"], L["blk"].num_src, B.PLAN_ALL, L["plan_mem"])
+
+    def fwd(L, plan):
+        B.fastgl_block_aggregate_fwd(L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, L["X"],
+                                     out=L["out"], plan=plan, workspace=workspace)
+
+    def bwd(L, plan):
+        B.fastgl_block_aggregate_bwd(L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, L["G"],
+                                     grad_X=L["dX"], plan=plan, workspace=workspace)
+
+    # the dominant kernel: forward pull over the input-layer block
+    dom = max(range(len(layers)), key=lambda i: layers[i]["bytes_fwd"])
+    dom_ev = []
+
+    def step(timed_dom=False):
+        plans = []
+        if table is not None:
+            B.fastgl_gather_rows(table, gid, out=layers[0]["X"])
+        for i, L in enumerate(layers):
+            p = make_plan(L)
+            plans.append(p)
+            if timed_dom and i == dom:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fwd(L, p)
+                e1.record()
+                dom_ev.append((e0, e1))
+            else:
+                fwd(L, p)
+        for L, p in zip(reversed(layers), reversed(plans)):
+            bwd(L, p)
+        return plans
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timed_dom=True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in dom_ev]))
+
+    # breakdown (not part of the headline): plan / forward / backward, and a step
+    # with plans built once ("cached plan")
+    def timed(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    reps = max(5, args.steps // 2)
+    plans = [make_plan(L) for L in layers]
+    plan_ms = timed(lambda: [make_plan(L) for L in layers], reps)
+    fwd_ms = timed(lambda: [fwd(L, p) for L, p in zip(layers, plans)], reps)
+    bwd_ms = timed(lambda: [bwd(L, p) for L, p in zip(reversed(layers), reversed(plans))], reps)
+    per_layer = []
+    for i, (L, p) in enumerate(zip(layers, plans)):
+        f = timed(lambda: fwd(L, p), reps)
+        b = timed(lambda: bwd(L, p), reps)
+        per_layer.append(dict(layer=i, num_dst=L["blk"].num_dst, num_src=L["blk"].num_src,
+                              E=L["blk"].num_edges, feat=L["feat"],
+                              fwd_ms=round(f, 4), bwd_ms=round(b, 4),
+                              fwd_gbps=round(L["bytes_fwd"] / f / 1e6, 1),
+                              bwd_gbps=round(L["bytes_bwd"] / b / 1e6, 1)))
+
+    value = 2.0 * total_edges / (ms_step * 1e-3) / 1e9
+    domL = layers[dom]
+    achieved = domL["bytes_fwd"] / (dom_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.config, "fwd", dom))
+    result = {
+        "metric": METRIC,
+        "value": round(value, 4),
+        "unit": "GEdges/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "config_id": args.config, "seed": w.seed,
+                   "fanout_order": args.fanout_order, "mode": w.mode, "widths": w.widths,
+                   "total_edges": total_edges, "accumulate": "f64" if w.dtype == "f32" else "f32",
+                   "step": "per layer: plan build + forward; then backward per layer (reverse)"},
+        "hbm_gbps_compulsory": round(bytes_step / (ms_step * 1e-3) / 1e9, 1),
+        "hbm_frac_of_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "compulsory_bytes_per_step": int(bytes_step),
+        "breakdown_ms": {"plan": round(plan_ms, 4), "fwd": round(fwd_ms, 4), "bwd": round(bwd_ms, 4),
+                         "cached_plan_step": round(fwd_ms + bwd_ms, 4)},
+        "value_cached_plan": round(2.0 * total_edges / ((fwd_ms + bwd_ms) * 1e-3) / 1e9, 4),
+        "hbm_frac_cached_plan": round(bytes_step / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "layers": per_layer,
+        "roofline": {"bound": "hbm", "kernel": f"forward aggregation call, layer {dom} (k_pull_rows)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "launch_ms": round(dom_ms, 4), "algorithmic_bytes": int(domL["bytes_fwd"])},
+        "gen_seconds": round(gen_s, 2),
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: the same workload, the layers in order until ~20 s of CPU work
+        budget, spent, edges_done, reps_done = 20.0, 0.0, 0, 0
+        sample = []
+        for i, L in enumerate(layers):
+            blk = L["blk"]
+            if w.dtype == "f32":
+                Xh, Gh = L["X"].cpu().numpy(), L["G"].cpu().numpy()
+            else:
+                Xh = L["X"].view(torch.int16).cpu().numpy().view(np.uint16)
+                Gh = L["G"].view(torch.int16).cpu().numpy().view(np.uint16)
+            t0 = time.perf_counter()
+            oracle.par_aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Xh)
+            oracle.par_aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Gh)
+            dt = time.perf_counter() - t0
+            spent += dt
+            edges_done += 2 * blk.num_edges
+            sample.append(i)
+            if spent > budget:
+                break
+        result["cpu_baseline"] = {
+            "value": round(edges_done / spent / 1e9, 5), "unit": "GEdges/s",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"parallel oracle variant (fp32 accumulate, OpenMP rows), fwd+bwd once over layers "
+                      f"{sample} of the same workload ({edges_done // 2} edges), {spent:.2f} s",
+        }
+    if args.verbose:
+        print(json.dumps(result, indent=1), file=sys.stderr)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

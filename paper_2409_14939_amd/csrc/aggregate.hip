@@ -17,9 +17,9 @@
 // f32 rows accumulate in fp64, bf16 rows in fp32; one rounding at the store.
 //
 // Rows longer than kLongThreshold edges are not walked by one group: they are
-// cut into chunks of kLongChunk edges that any group can take; the partial sums
-// go to the workspace and are added in chunk order by a second kernel, so the
-// result is still deterministic.
+// cut into chunks of kLongChunk edges that any group can take (in the same
+// launch); the partial sums go to the workspace and are added in chunk order by
+// a second, small kernel, so the result is still deterministic.
 #include "internal.h"
 
 namespace fastgl {
@@ -175,41 +175,18 @@ __device__ __forceinline__ int64_t logical_block(int64_t per_xcd)
     return (int64_t)(blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
 }
 
+// Chunks of long rows: one unit = (chunk, column tile).  The number of chunks
+// lives in device memory, so the host never needs to know the degrees; groups
+// stride over the units and write fp64 / fp32 partial sums to the workspace.
 template <int DT, int VB, bool HASW>
-__global__ __launch_bounds__(kBlock) void k_pull_rows(PullParams P)
+__device__ __forceinline__ void pull_chunks(const PullParams &P, int64_t first_unit, int64_t stride, int sub,
+                                            int gbase)
 {
     using S = Slice<DT, VB>;
     using acc_t = typename S::acc_t;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
-    const int64_t unit = (logical_block(P.blocks_per_xcd) * kBlock + tid) / P.G;
-    if (unit >= P.num_units) return;
-    const int64_t row = unit / P.ntiles;
-    const int tile = (int)(unit - row * P.ntiles);
-    const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
-    const bool active = lane_off < P.row_bytes;
-    const int beg = P.rowptr[row], end = P.rowptr[row + 1];
-    if (end - beg > P.long_thr) return;
-    acc_t acc[S::NE];
-#pragma unroll
-    for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
-    walk_edges<DT, VB, HASW>(P, beg, end, sub, gbase, lane_off, active, acc);
-    if (active) S::store(P.out + row * P.row_bytes + lane_off, acc, row_scale<acc_t>(P.row_mode, end - beg));
-}
-
-// One unit = (chunk of a long row, column tile); grid-stride over a count that
-// lives in device memory, so the host never needs to know the degrees.
-template <int DT, int VB, bool HASW>
-__global__ __launch_bounds__(kBlock) void k_pull_chunks(PullParams P)
-{
-    using S = Slice<DT, VB>;
-    using acc_t = typename S::acc_t;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
     const int n_long = *P.n_long;
     const int64_t total = (int64_t)(*P.n_chunks) * P.ntiles;
-    const int64_t stride = (int64_t)gridDim.x * kBlock / P.G;
-    for (int64_t unit = ((int64_t)blockIdx.x * kBlock + tid) / P.G; unit < total; unit += stride) {
+    for (int64_t unit = first_unit; unit < total; unit += stride) {
         const int chunk = (int)(unit / P.ntiles);
         const int tile = (int)(unit - (int64_t)chunk * P.ntiles);
         int lo = 0, hi = n_long;   // chunk_ptr[lo] <= chunk < chunk_ptr[hi]
@@ -234,6 +211,33 @@ __global__ __launch_bounds__(kBlock) void k_pull_chunks(PullParams P)
             for (int i = 0; i < S::NE; ++i) dst[i] = acc[i];
         }
     }
+}
+
+// One launch covers every row: each group first takes its share of the long-row
+// chunks (usually none), then walks its own (row, column tile) unit unless that
+// row is a long one.  k_reduce_chunks finishes the long rows afterwards.
+template <int DT, int VB, bool HASW>
+__global__ __launch_bounds__(kBlock) void k_pull_rows(PullParams P)
+{
+    using S = Slice<DT, VB>;
+    using acc_t = typename S::acc_t;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
+    const int64_t unit = (logical_block(P.blocks_per_xcd) * kBlock + tid) / P.G;
+    if (P.long_rows)
+        pull_chunks<DT, VB, HASW>(P, unit, (int64_t)gridDim.x * kBlock / P.G, sub, gbase);
+    if (unit >= P.num_units) return;
+    const int64_t row = unit / P.ntiles;
+    const int tile = (int)(unit - row * P.ntiles);
+    const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
+    const bool active = lane_off < P.row_bytes;
+    const int beg = P.rowptr[row], end = P.rowptr[row + 1];
+    if (end - beg > P.long_thr) return;
+    acc_t acc[S::NE];
+#pragma unroll
+    for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
+    walk_edges<DT, VB, HASW>(P, beg, end, sub, gbase, lane_off, active, acc);
+    if (active) S::store(P.out + row * P.row_bytes + lane_off, acc, row_scale<acc_t>(P.row_mode, end - beg));
 }
 
 template <int DT, int VB>
@@ -316,10 +320,6 @@ static fastgl_status launch_typed(const PullParams &P, bool hasw, bool with_long
         FASTGL_LAUNCH_CHECK("k_pull_rows");
     }
     if (with_long) {
-        dim3 grid(2048);
-        if (hasw) hipLaunchKernelGGL((k_pull_chunks<DT, VB, true>), grid, dim3(kBlock), 0, s, P);
-        else hipLaunchKernelGGL((k_pull_chunks<DT, VB, false>), grid, dim3(kBlock), 0, s, P);
-        FASTGL_LAUNCH_CHECK("k_pull_chunks");
         hipLaunchKernelGGL((k_reduce_chunks<DT, VB>), dim3(512), dim3(kBlock), 0, s, P);
         FASTGL_LAUNCH_CHECK("k_reduce_chunks");
     }
