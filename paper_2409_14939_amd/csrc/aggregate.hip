@@ -20,11 +20,15 @@
 // cut into chunks of kLongChunk edges that any group can take (in the same
 // launch); the partial sums go to the workspace and are added in chunk order by
 // a second, small kernel, so the result is still deterministic.
+#include <stdlib.h>
+
 #include "internal.h"
 
 namespace fastgl {
 
 constexpr int kUnroll = 8;
+constexpr int kRowsPerGroup = 8;
+constexpr int kXcdRun = 16;
 
 template <int DT> struct AccT { using type = double; };
 template <> struct AccT<FASTGL_BF16> { using type = float; };
@@ -103,14 +107,17 @@ struct PullParams {
     const float *edge_w, *col_scale;
     const char *in;
     char *out;
-    int64_t num_units;        // rows * ntiles
+    int64_t num_units;        // row sets * ntiles
     int32_t ntiles;           // column tiles per row
     int32_t G;                // lanes per group (power of two)
+    int32_t rpg;              // consecutive rows owned by one group (<= G)
+    int64_t num_rows;
     int32_t row_mode;
     int32_t long_thr;         // rows longer than this are left to the chunk kernels
     int64_t row_bytes;        // bytes of one feature row
     int64_t feat;
-    int64_t blocks_per_xcd;   // logical blocks each L2 domain owns
+    int32_t xcd_run;          // consecutive logical blocks handed to one L2 domain
+    int64_t num_blocks;       // launched blocks (multiple of kXcds * xcd_run)
     const int32_t *long_rows, *chunk_ptr, *n_long, *n_chunks;
     char *partials;
 };
@@ -128,51 +135,107 @@ template <typename T> __device__ __forceinline__ T shfl_t(T v, int src);
 template <> __device__ __forceinline__ float shfl_t<float>(float v, int src) { return __shfl(v, src, kWave); }
 template <> __device__ __forceinline__ double shfl_t<double>(double v, int src) { return __shfl(v, src, kWave); }
 
-// Accumulate edges [beg,end) of one row into acc.  `sub` is the lane's slot in
-// its group, `gbase` the wave lane of the group's slot 0, `p_in` the lane's
-// byte offset inside a feature row (valid only if `active`).
-template <int DT, int VB, bool HASW>
-__device__ __forceinline__ void walk_edges(const PullParams &P, int beg, int end, int sub, int gbase,
-                                           int64_t lane_off, bool active,
-                                           typename Slice<DT, VB>::acc_t (&acc)[Slice<DT, VB>::NE])
+// Workgroup ids are dealt round-robin to the 8 L2 domains.  Logical blocks (and
+// with them rows) are handed out in runs of P.xcd_run consecutive blocks per
+// domain: neighbouring rows share one L2 (they touch neighbouring source rows and
+// the same output cache lines), while every domain still gets a sample of the
+// whole row range, so skewed blocks (all hubs at low ids) stay balanced.
+__device__ __forceinline__ int64_t logical_block(int run)
+{
+    const int64_t x = blockIdx.x % kXcds, q = blockIdx.x / kXcds;
+    return ((q / run) * kXcds + x) * run + q % run;
+}
+
+// Column ids and weights of up to G consecutive edges, one per lane of a group.
+template <bool HASW, typename acc_t>
+__device__ __forceinline__ int load_cols(const PullParams &P, int k, int kend)
+{
+    return k < kend ? P.col[k] : 0;
+}
+
+template <bool HASW, typename acc_t>
+__device__ __forceinline__ acc_t load_weight(const PullParams &P, int k, int kend, int c)
+{
+    acc_t w = (acc_t)1;
+    if (HASW && k < kend) {
+        if (P.edge_w) w = (acc_t)P.edge_w[P.eid ? P.eid[k] : k];
+        if (P.col_scale) w *= (acc_t)P.col_scale[c];
+    }
+    return w;
+}
+
+// A group walks the edges of a run of consecutive rows [ia, ib) of its row set as
+// ONE flat edge list, so that kUnroll row gathers are in flight whatever the row
+// lengths are (sampled blocks have rows of 1-15 edges, transposed ones of 0-3),
+// and closes a row (scale, round, store, clear the sum) whenever the edge index
+// passes the row's end.  pb / pe: lane i of the group holds rowptr of its i-th row.
+// Column ids are fetched two chunks ahead and weights one chunk ahead of use.
+// PARTIAL: the "row" is a chunk of a long row; its unscaled sum goes to slot r0 of
+// the partial-sum buffer instead of the output.
+template <int DT, int VB, bool HASW, bool PARTIAL>
+__device__ __forceinline__ void walk_run(const PullParams &P, int64_t r0, int ia, int ib, int pb, int pe,
+                                         int sub, int gbase, int64_t lane_off, bool active)
 {
     using S = Slice<DT, VB>;
     using acc_t = typename S::acc_t;
     const int G = P.G;
-    for (int k0 = beg; k0 < end; k0 += G) {
-        const int n = end - k0 < G ? end - k0 : G;
-        int myc = 0;
-        acc_t myw = (acc_t)1;
-        if (sub < n) {
-            myc = P.col[k0 + sub];
-            if (HASW) {
-                if (P.edge_w) myw = (acc_t)P.edge_w[P.eid ? P.eid[k0 + sub] : k0 + sub];
-                if (P.col_scale) myw *= (acc_t)P.col_scale[myc];
+    const int ebeg = __shfl(pb, gbase + ia, kWave), eend = __shfl(pe, gbase + ib - 1, kWave);
+    int row = ia;
+    int rend = __shfl(pe, gbase + row, kWave);
+    acc_t acc[S::NE];
+#pragma unroll
+    for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
+
+    auto close_row = [&]() {
+        if constexpr (PARTIAL) {
+            if (active) {
+                acc_t *dst = reinterpret_cast<acc_t *>(P.partials) + r0 * P.feat + lane_off / VB * S::NE;
+#pragma unroll
+                for (int i = 0; i < S::NE; ++i) dst[i] = acc[i];
             }
+        } else {
+            const int len = rend - __shfl(pb, gbase + row, kWave);
+            if (active)
+                S::store(P.out + (r0 + row) * P.row_bytes + lane_off, acc, row_scale<acc_t>(P.row_mode, len));
         }
+#pragma unroll
+        for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
+        ++row;
+        rend = __shfl(pe, gbase + (row < ib ? row : ib - 1), kWave);
+    };
+
+    int cur_c = load_cols<HASW, acc_t>(P, ebeg + sub, eend);
+    int nxt_c = load_cols<HASW, acc_t>(P, ebeg + G + sub, eend);
+    acc_t cur_w = load_weight<HASW, acc_t>(P, ebeg + sub, eend, cur_c);
+    for (int k0 = ebeg; k0 < eend; k0 += G) {
+        const int n = eend - k0 < G ? eend - k0 : G;
+        const int nn_c = load_cols<HASW, acc_t>(P, k0 + 2 * G + sub, eend);
+        const acc_t nxt_w = load_weight<HASW, acc_t>(P, k0 + G + sub, eend, nxt_c);
         for (int j0 = 0; j0 < n; j0 += kUnroll) {
             uint32_t raw[kUnroll][S::NW];
-            acc_t w[kUnroll];
 #pragma unroll
             for (int t = 0; t < kUnroll; ++t) {
                 const int j = j0 + t;
-                const int src = gbase + (j & (G - 1));
-                const int c = __shfl(myc, src, kWave);
-                if (HASW) w[t] = shfl_t<acc_t>(myw, src);
+                const int c = __shfl(cur_c, gbase + (j & (G - 1)), kWave);
                 if (j < n && active) S::load(P.in + (int64_t)c * P.row_bytes + lane_off, raw[t]);
             }
 #pragma unroll
-            for (int t = 0; t < kUnroll; ++t)
-                if (j0 + t < n && active) S::template fma<HASW>(acc, raw[t], HASW ? w[t] : (acc_t)1);
+            for (int t = 0; t < kUnroll; ++t) {
+                const int j = j0 + t;
+                acc_t w = (acc_t)1;
+                if (HASW) w = shfl_t<acc_t>(cur_w, gbase + (j & (G - 1)));
+                if (j < n) {
+                    const int e = k0 + j;
+                    while (e >= rend) close_row();
+                    if (active) S::template fma<HASW>(acc, raw[t], w);
+                }
+            }
         }
+        cur_c = nxt_c;
+        cur_w = nxt_w;
+        nxt_c = nn_c;
     }
-}
-
-// Workgroup ids are dealt round-robin to the 8 L2 domains; give each domain a
-// contiguous run of logical blocks so neighbouring rows share one L2.
-__device__ __forceinline__ int64_t logical_block(int64_t per_xcd)
-{
-    return (int64_t)(blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    while (row < ib) close_row();
 }
 
 // Chunks of long rows: one unit = (chunk, column tile).  The number of chunks
@@ -182,8 +245,6 @@ template <int DT, int VB, bool HASW>
 __device__ __forceinline__ void pull_chunks(const PullParams &P, int64_t first_unit, int64_t stride, int sub,
                                             int gbase)
 {
-    using S = Slice<DT, VB>;
-    using acc_t = typename S::acc_t;
     const int n_long = *P.n_long;
     const int64_t total = (int64_t)(*P.n_chunks) * P.ntiles;
     for (int64_t unit = first_unit; unit < total; unit += stride) {
@@ -199,45 +260,46 @@ __device__ __forceinline__ void pull_chunks(const PullParams &P, int64_t first_u
         const int beg = rbeg + (chunk - P.chunk_ptr[lo]) * kLongChunk;
         const int end = beg + kLongChunk < rend ? beg + kLongChunk : rend;
         const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
-        const bool active = lane_off < P.row_bytes;
-        acc_t acc[S::NE];
-#pragma unroll
-        for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
-        walk_edges<DT, VB, HASW>(P, beg, end, sub, gbase, lane_off, active, acc);
-        if (active) {
-            acc_t *dst = reinterpret_cast<acc_t *>(P.partials) + (int64_t)chunk * P.feat +
-                         ((int64_t)tile * P.G + sub) * S::NE;
-#pragma unroll
-            for (int i = 0; i < S::NE; ++i) dst[i] = acc[i];
-        }
+        walk_run<DT, VB, HASW, true>(P, chunk, 0, 1, beg, end, sub, gbase, lane_off, lane_off < P.row_bytes);
     }
 }
 
-// One launch covers every row: each group first takes its share of the long-row
-// chunks (usually none), then walks its own (row, column tile) unit unless that
-// row is a long one.  k_reduce_chunks finishes the long rows afterwards.
+// One launch covers every row.  Each group first takes its share of the long-row
+// chunks (usually none), then its own set of P.rpg consecutive rows (x one column
+// tile), skipping rows that are long.  k_reduce_chunks finishes the long rows.
 template <int DT, int VB, bool HASW>
 __global__ __launch_bounds__(kBlock) void k_pull_rows(PullParams P)
 {
-    using S = Slice<DT, VB>;
-    using acc_t = typename S::acc_t;
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
-    const int64_t unit = (logical_block(P.blocks_per_xcd) * kBlock + tid) / P.G;
+    const int64_t unit = (logical_block(P.xcd_run) * kBlock + tid) / P.G;
     if (P.long_rows)
         pull_chunks<DT, VB, HASW>(P, unit, (int64_t)gridDim.x * kBlock / P.G, sub, gbase);
     if (unit >= P.num_units) return;
-    const int64_t row = unit / P.ntiles;
-    const int tile = (int)(unit - row * P.ntiles);
+    const int64_t rg = unit / P.ntiles;
+    const int tile = (int)(unit - rg * P.ntiles);
     const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
     const bool active = lane_off < P.row_bytes;
-    const int beg = P.rowptr[row], end = P.rowptr[row + 1];
-    if (end - beg > P.long_thr) return;
-    acc_t acc[S::NE];
-#pragma unroll
-    for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
-    walk_edges<DT, VB, HASW>(P, beg, end, sub, gbase, lane_off, active, acc);
-    if (active) S::store(P.out + row * P.row_bytes + lane_off, acc, row_scale<acc_t>(P.row_mode, end - beg));
+    const int64_t r0 = rg * P.rpg;
+    const int nrows = P.num_rows - r0 < P.rpg ? (int)(P.num_rows - r0) : P.rpg;
+    int pb = 0, pe = 0;
+    if (sub < nrows) {
+        pb = P.rowptr[r0 + sub];
+        pe = P.rowptr[r0 + sub + 1];
+    }
+    const unsigned long long gmask = P.G == kWave ? ~0ull : ((1ull << P.G) - 1ull);
+    unsigned long long lm = (__ballot(sub < nrows && pe - pb > P.long_thr) >> gbase) & gmask;
+    int i = 0;
+    while (i < nrows) {
+        if ((lm >> i) & 1ull) {   // a long row: its chunks were handled above
+            ++i;
+            continue;
+        }
+        const unsigned long long rest = lm >> i;
+        const int j = rest ? i + (__ffsll((long long)rest) - 1) : nrows;
+        walk_run<DT, VB, HASW, false>(P, r0, i, j, pb, pe, sub, gbase, lane_off, active);
+        i = j;
+    }
 }
 
 template <int DT, int VB>
@@ -292,6 +354,12 @@ __global__ __launch_bounds__(kBlock) void k_gather_rows(const char *__restrict__
 }
 
 // ------------------------------------------------------------- host side ----
+static int tune(const char *name, int dflt)   // development knob
+{
+    const char *v = getenv(name);
+    return v ? atoi(v) : dflt;
+}
+
 // Largest slice width (bytes) that divides the row size and the buffer alignment.
 static int pick_slice_bytes(int64_t row_bytes, const void *a, const void *b, int elem)
 {
@@ -314,7 +382,7 @@ template <int DT, int VB>
 static fastgl_status launch_typed(const PullParams &P, bool hasw, bool with_long, int64_t nblocks, hipStream_t s)
 {
     if (nblocks > 0) {
-        dim3 grid((unsigned)(P.blocks_per_xcd * kXcds));
+        dim3 grid((unsigned)P.num_blocks);
         if (hasw) hipLaunchKernelGGL((k_pull_rows<DT, VB, true>), grid, dim3(kBlock), 0, s, P);
         else hipLaunchKernelGGL((k_pull_rows<DT, VB, false>), grid, dim3(kBlock), 0, s, P);
         FASTGL_LAUNCH_CHECK("k_pull_rows");
@@ -341,14 +409,24 @@ fastgl_status launch_pull(const PullDesc &d, hipStream_t s)
     int G, ntiles;
     group_shape(P.row_bytes, vb, &G, &ntiles);
     P.G = G; P.ntiles = ntiles;
-    P.num_units = d.num_rows * ntiles;
+    P.num_rows = d.num_rows;
+    // rows per group: enough to amortise the row-pointer / column-id latency over
+    // many gathers, few enough to keep >= ~8K wavefronts in the launch
+    int64_t rpg = d.num_rows * G / ((int64_t)kWave * 8192);
+    const int maxrpg = tune("FASTGL_RPG", kRowsPerGroup);
+    if (rpg > maxrpg) rpg = maxrpg;
+    if (rpg > G) rpg = G;
+    if (rpg < 1) rpg = 1;
+    P.rpg = (int)rpg;
+    P.num_units = ceil_div(d.num_rows, rpg) * ntiles;
     const bool with_long = d.long_rows != nullptr;
     P.long_thr = with_long ? kLongThreshold : INT32_MAX;
     P.long_rows = d.long_rows; P.chunk_ptr = d.chunk_ptr; P.n_long = d.n_long; P.n_chunks = d.n_chunks;
     P.partials = (char *)d.partials;
     const int64_t nblocks = ceil_div(P.num_units * G, kBlock);
-    P.blocks_per_xcd = ceil_div(nblocks, kXcds);
-    if (P.blocks_per_xcd * kXcds > 0x7FFFFFFFLL) {
+    P.xcd_run = tune("FASTGL_XCD_RUN", kXcdRun);
+    P.num_blocks = ceil_div(nblocks, (int64_t)kXcds * P.xcd_run) * kXcds * P.xcd_run;
+    if (P.num_blocks > 0x7FFFFFFFLL) {
         set_error("block too large for one launch (%lld workgroups)", (long long)nblocks);
         return FASTGL_ERR_UNSUPPORTED;
     }
