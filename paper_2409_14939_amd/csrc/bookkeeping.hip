@@ -1,17 +1,32 @@
 // Per-block integer bookkeeping on the GPU: degrees, scale factors, a stable
 // transpose of the CSR (LSD radix sort of (source id, edge id)), and degree
 // buckets (ordered compaction of long rows).  Everything is integer work with
-// a single valid answer, so no float atomics and no order-dependent results.
+// a single valid answer: no float atomics, no order-dependent results, and (on
+// the full-plan path) no global atomics at all.
 //
 // Why it exists: the backward pass (paper Section 4.2, Eq. 5) gathers along
 // the reversed edges; pulling along a transposed CSR keeps one writer per
 // output row, as the forward pass has (Section 4.2: a target's aggregation is
-// completed by one owner).
+// completed by one owner).  Every sampled block is new, so this work is part of
+// each iteration and is kept to a handful of launches:
+//
+//   per radix pass (8-bit digit)   k_sort_hist, k_sort_scatter
+//   after the last pass            k_row_starts   (indptr_T from the sorted keys)
+//   degree buckets, per side       k_rows_count, k_rows_fill
+//
+// The destination-side bucket kernels ride along in the first pass's two
+// launches as extra workgroups, so a full plan with a 3-pass sort is 9 launches.
 #include "internal.h"
 
 namespace fastgl {
 
-// ---------------------------------------------------------------- scans ----
+constexpr int kSortThreads = 1024;                   // 16 wavefronts per sort workgroup
+constexpr int kSortWaves = kSortThreads / kWave;
+constexpr int kSortItems = 4;                        // keys per thread and step
+constexpr int kSortStep = kSortThreads * kSortItems; // keys ranked per step by one workgroup
+constexpr int kMaxSortBlocks = 256;
+
+// -------------------------------------------------- block-wide primitives ----
 __device__ __forceinline__ int wave_incl_scan(int v)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -23,17 +38,16 @@ __device__ __forceinline__ int wave_incl_scan(int v)
     return v;
 }
 
-// Exclusive scan over the 256 threads of a block; *total = block sum.
-// `lds` needs kBlock / kWave ints and is free again on return.
+// Exclusive scan over all threads of the block (any multiple of 64 up to 1024);
+// *total = block sum.  `lds` needs 16 ints and is free again on return.
 __device__ __forceinline__ int block_excl_scan(int v, int *total, int *lds)
 {
-    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
     int inc = wave_incl_scan(v);
     if (lane == kWave - 1) lds[w] = inc;
     __syncthreads();
     int off = 0, tot = 0;
-#pragma unroll
-    for (int i = 0; i < kBlock / kWave; ++i) {
+    for (int i = 0; i < nw; ++i) {
         int s = lds[i];
         if (i < w) off += s;
         tot += s;
@@ -50,6 +64,278 @@ __device__ __forceinline__ int block_sum(int v, int *lds)
     return tot;
 }
 
+// ---------------------------------------- degrees + long-row buckets (roles) ----
+struct RowsArgs {
+    const int32_t *rowptr;   // [n+1]
+    int64_t n, per;          // block b owns rows [b*per, min(n,(b+1)*per))
+    int nb;
+    int32_t *len_out;        // [n] or NULL
+    float *inv, *rsq;        // [n] or NULL: 1/max(len,1), 1/sqrt(max(len,1))
+    int32_t *counts;         // [2*nb] per-block (long rows, chunks)
+    int32_t *long_rows, *chunk_ptr, *totals;
+};
+
+// Pass 1 over row pointers: row lengths, scale factors, and per-block counts of
+// long rows / their chunks.
+__device__ __forceinline__ void rows_count(const RowsArgs &A, int b, int *lds)
+{
+    int64_t beg = b * A.per, end = beg + A.per < A.n ? beg + A.per : A.n;
+    int nl = 0, nc = 0;
+    for (int64_t r = beg + threadIdx.x; r < end; r += blockDim.x) {
+        int len = A.rowptr[r + 1] - A.rowptr[r];
+        if (A.len_out) A.len_out[r] = len;
+        double d = (double)(len < 1 ? 1 : len);
+        if (A.inv) A.inv[r] = (float)(1.0 / d);
+        if (A.rsq) A.rsq[r] = (float)(1.0 / sqrt(d));
+        if (len > kLongThreshold) {
+            nl += 1;
+            nc += (len + kLongChunk - 1) / kLongChunk;
+        }
+    }
+    nl = block_sum(nl, lds);
+    nc = block_sum(nc, lds);
+    if (threadIdx.x == 0) {
+        A.counts[2 * b] = nl;
+        A.counts[2 * b + 1] = nc;
+    }
+}
+
+// Pass 2: ordered compaction.  long_rows ascending; chunk_ptr[i] = first chunk of
+// the i-th long row; totals[0] = number of long rows, totals[1] = number of chunks.
+__device__ __forceinline__ void rows_fill(const RowsArgs &A, int b, int *lds)
+{
+    int pl = 0, pc = 0;
+    for (int i = threadIdx.x; i < A.nb; i += blockDim.x) {
+        if (i < b) {
+            pl += A.counts[2 * i];
+            pc += A.counts[2 * i + 1];
+        }
+    }
+    int cl = block_sum(pl, lds);
+    int cc = block_sum(pc, lds);
+    int64_t beg = b * A.per, end = beg + A.per < A.n ? beg + A.per : A.n;
+    const bool any = A.counts[2 * b] != 0;      // block-uniform: most blocks have no long row
+    for (int64_t base = beg; any && base < end; base += blockDim.x) {
+        int64_t r = base + threadIdx.x;
+        int len = r < end ? A.rowptr[r + 1] - A.rowptr[r] : 0;
+        int isl = len > kLongThreshold ? 1 : 0;
+        int nch = isl ? (len + kLongChunk - 1) / kLongChunk : 0;
+        int tl, tc;
+        int el = block_excl_scan(isl, &tl, lds);
+        int ec = block_excl_scan(nch, &tc, lds);
+        if (isl) {
+            A.long_rows[cl + el] = (int32_t)r;
+            A.chunk_ptr[cl + el] = cc + ec;
+        }
+        cl += tl;
+        cc += tc;
+    }
+    if (b == A.nb - 1 && threadIdx.x == 0) {
+        A.chunk_ptr[cl] = cc;
+        A.totals[0] = cl;
+        A.totals[1] = cc;
+    }
+}
+
+__global__ __launch_bounds__(kSortThreads) void k_rows_count(RowsArgs A)
+{
+    __shared__ int lds[16];
+    rows_count(A, blockIdx.x, lds);
+}
+
+__global__ __launch_bounds__(kSortThreads) void k_rows_fill(RowsArgs A)
+{
+    __shared__ int lds[16];
+    rows_fill(A, blockIdx.x, lds);
+}
+
+// ------------------------------------------------------------ radix sort ----
+struct SortArgs {
+    const int32_t *keys_in, *vals_in;   // vals_in == NULL: the identity (first pass)
+    int32_t *keys_out, *vals_out;
+    int64_t n, per;                     // block b owns keys [b*per, min(n,(b+1)*per))
+    int nb, shift;
+    int32_t *cnt;                       // [nb][256] digit counts per block
+    // first pass: also record the destination row of every edge
+    const int32_t *indptr;
+    int32_t num_dst;
+    int32_t *edge_dst;                  // [n]; written by the first pass, read by the last
+    int32_t *dst_out;                   // last pass: [n] destination row in sorted order
+};
+
+// largest u in [lo, hi) with indptr[u] <= e  (the destination row that owns edge e)
+__device__ __forceinline__ int32_t owner_row(const int32_t *__restrict__ indptr, int32_t lo, int32_t hi, int32_t e)
+{
+    while (hi - lo > 1) {   // invariant: indptr[lo] <= e < indptr[hi]
+        int32_t mid = lo + ((hi - lo) >> 1);
+        if (indptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Digit histogram of the block's key range.  FIRST: also expand the CSR row ids
+// (edge_dst[e] = row owning e), searching only the rows this block's edges touch.
+// Workgroups beyond S.nb run the destination-side row count.
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void k_sort_hist(SortArgs S, RowsArgs R)
+{
+    __shared__ int h[kRadixBins];
+    __shared__ int lds[16];
+    if ((int)blockIdx.x >= S.nb) {
+        rows_count(R, blockIdx.x - S.nb, lds);
+        return;
+    }
+    if (threadIdx.x < kRadixBins) h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t beg = blockIdx.x * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
+    int32_t rlo = 0, rhi = 1;
+    if (FIRST && beg < end) {
+        rlo = owner_row(S.indptr, 0, S.num_dst, (int32_t)beg);
+        rhi = owner_row(S.indptr, rlo, S.num_dst, (int32_t)(end - 1)) + 1;
+    }
+    for (int64_t i = beg + threadIdx.x; i < end; i += kSortThreads) {
+        atomicAdd(&h[(S.keys_in[i] >> S.shift) & (kRadixBins - 1)], 1);
+        if (FIRST) S.edge_dst[i] = owner_row(S.indptr, rlo, rhi, (int32_t)i);
+    }
+    __syncthreads();
+    if (threadIdx.x < kRadixBins) S.cnt[(int64_t)blockIdx.x * kRadixBins + threadIdx.x] = h[threadIdx.x];
+}
+
+// Stable scatter of one digit.  Every workgroup derives its own output offsets
+// from the [nb][256] count table (no separate scan launch): for digit d,
+//   base = sum_{d' < d} total[d'] + sum_{b' < b} cnt[b'][d].
+// Within a step of 4096 keys each wavefront owns 256 consecutive keys and ranks
+// them 64 at a time: lanes with equal digits find each other with 8 ballots, the
+// running per-wavefront digit counts live in LDS, and a column scan over the 16
+// wavefronts turns them into absolute positions.
+// LAST: write sorted keys, the permutation, and the destination row of each edge.
+// Workgroups beyond S.nb run the destination-side row fill (first pass only).
+template <bool LAST>
+__global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsArgs R, int rows_role)
+{
+    __shared__ int running[kRadixBins];
+    __shared__ int wcnt[kSortWaves][kRadixBins];
+    __shared__ int lds[16];
+    const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
+    if ((int)blockIdx.x >= S.nb) {
+        if (rows_role) rows_fill(R, blockIdx.x - S.nb, lds);
+        return;
+    }
+    const int b = blockIdx.x;
+    {   // offsets of this block's digits
+        const int d = t & (kRadixBins - 1), part = t / kRadixBins;   // 4 parts share the blocks
+        int below = 0, total = 0;
+        for (int bb = part; bb < S.nb; bb += kSortThreads / kRadixBins) {
+            int c = S.cnt[(int64_t)bb * kRadixBins + d];
+            total += c;
+            if (bb < b) below += c;
+        }
+        wcnt[part][d] = below;
+        wcnt[4 + part][d] = total;
+        __syncthreads();
+        int tot = 0, bel = 0;
+        if (t < kRadixBins) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                bel += wcnt[k][t];
+                tot += wcnt[4 + k][t];
+            }
+        }
+        int dummy;
+        int ex = block_excl_scan(t < kRadixBins ? tot : 0, &dummy, lds);   // threads >= 256 add 0 after the digits
+        if (t < kRadixBins) running[t] = ex + bel;
+        __syncthreads();
+    }
+    const int64_t beg = b * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
+    for (int64_t step = beg; step < end; step += kSortStep) {
+#pragma unroll
+        for (int k = 0; k < kSortWaves * kRadixBins / kSortThreads; ++k)
+            (&wcnt[0][0])[k * kSortThreads + t] = 0;
+        __syncthreads();
+        int32_t key[kSortItems], val[kSortItems];
+        int rank[kSortItems], dig[kSortItems];
+        bool ok[kSortItems];
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            const int64_t idx = step + (int64_t)w * (kWave * kSortItems) + i * kWave + lane;
+            ok[i] = idx < end;
+            key[i] = ok[i] ? S.keys_in[idx] : 0;
+            val[i] = ok[i] ? (S.vals_in ? S.vals_in[idx] : (int32_t)idx) : 0;
+            dig[i] = (key[i] >> S.shift) & (kRadixBins - 1);
+        }
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            unsigned long long mask = __ballot(ok[i]);
+#pragma unroll
+            for (int bit = 0; bit < kRadixBits; ++bit) {
+                const bool one = (dig[i] >> bit) & 1;
+                const unsigned long long bl = __ballot(one);
+                mask &= one ? bl : ~bl;
+            }
+            const int lower = __popcll(mask & ((1ull << lane) - 1ull));
+            const int prior = ok[i] ? wcnt[w][dig[i]] : 0;   // count from this wavefront's earlier rounds
+            rank[i] = prior + lower;
+            // the LDS read above is issued before this write by the same wavefront
+            if (ok[i] && lower == 0) wcnt[w][dig[i]] = prior + __popcll(mask);
+        }
+        __syncthreads();
+        if (t < kRadixBins) {   // column scan over the wavefronts -> absolute bases
+            int run = running[t];
+#pragma unroll
+            for (int k = 0; k < kSortWaves; ++k) {
+                int c = wcnt[k][t];
+                wcnt[k][t] = run;
+                run += c;
+            }
+            running[t] = run;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            if (!ok[i]) continue;
+            const int pos = wcnt[w][dig[i]] + rank[i];
+            if (LAST) {
+                S.keys_out[pos] = key[i];
+                S.vals_out[pos] = val[i];
+                S.dst_out[pos] = S.edge_dst[val[i]];
+            } else {
+                S.keys_out[pos] = key[i];
+                S.vals_out[pos] = val[i];
+            }
+        }
+        __syncthreads();   // wcnt is cleared at the top of the next step
+    }
+}
+
+// indptr_T from the sorted source ids: position k starts every source id in
+// (key[k-1], key[k]].  k == n closes the tail.  Gaps (sources without edges) are
+// short in practice; a long one is filled by the whole wavefront together.
+__global__ __launch_bounds__(kBlock) void k_row_starts(const int32_t *__restrict__ keys, int64_t n,
+                                                       int64_t num_src, int32_t *__restrict__ indptr_T)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    for (int64_t base = (int64_t)blockIdx.x * kBlock; base <= n; base += (int64_t)gridDim.x * kBlock) {
+        const int64_t k = base + threadIdx.x;
+        int64_t prev = 0, cur = -1;   // empty interval by default
+        if (k <= n) {
+            prev = k > 0 ? keys[k - 1] : -1;
+            cur = k < n ? keys[k] : num_src;
+        }
+        const bool big = cur - prev > 4;
+        if (!big)
+            for (int64_t v = prev + 1; v <= cur; ++v) indptr_T[v] = (int32_t)k;
+        unsigned long long m = __ballot(big);
+        while (m) {
+            const int leader = __ffsll((long long)m) - 1;
+            const int64_t p = __shfl(prev, leader, kWave), c = __shfl(cur, leader, kWave);
+            const int64_t kk = __shfl(k, leader, kWave);
+            for (int64_t v = p + 1 + lane; v <= c; v += kWave) indptr_T[v] = (int32_t)kk;
+            m &= m - 1;
+        }
+    }
+}
+
+// --------------------------------------- forward-only GCN: out-degree histogram ----
 __global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t *p, int64_t n, int32_t v)
 {
     for (int64_t i = blockIdx.x * (int64_t)kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock)
@@ -63,198 +349,12 @@ __global__ __launch_bounds__(kBlock) void k_hist(const int32_t *__restrict__ idx
         atomicAdd(&cnt[idx[i]], 1);
 }
 
-// Block b owns elements [b*per, min(n,(b+1)*per)).
-__global__ __launch_bounds__(kBlock) void k_scan_partials(const int32_t *__restrict__ in, int64_t n,
-                                                          int64_t per, int32_t *__restrict__ bsum)
+__global__ __launch_bounds__(kBlock) void k_rsqrt_deg(const int32_t *__restrict__ deg, int64_t n,
+                                                      float *__restrict__ rsq)
 {
-    __shared__ int lds[kBlock / kWave];
-    int64_t beg = blockIdx.x * per, end = beg + per < n ? beg + per : n;
-    int s = 0;
-    for (int64_t i = beg + threadIdx.x; i < end; i += kBlock) s += in[i];
-    s = block_sum(s, lds);
-    if (threadIdx.x == 0) bsum[blockIdx.x] = s;
-}
-
-// out[i] = sum of in[0..i) for i in [0,n]; optionally rsq[i] = 1/sqrt(max(in[i],1)).
-// in and out may alias.
-__global__ __launch_bounds__(kBlock) void k_scan_final(const int32_t *in, int64_t n, int64_t per,
-                                                       const int32_t *__restrict__ bsum,
-                                                       int32_t *out, float *__restrict__ rsq)
-{
-    __shared__ int lds[kBlock / kWave];
-    const int b = blockIdx.x;
-    int pre = 0;
-    for (int i = threadIdx.x; i < b; i += kBlock) pre += bsum[i];
-    int carry = block_sum(pre, lds);
-    int64_t beg = b * per, end = beg + per < n ? beg + per : n;
-    for (int64_t base = beg; base < end; base += kBlock) {
-        int64_t i = base + threadIdx.x;
-        int v = i < end ? in[i] : 0;
-        int tot;
-        int ex = block_excl_scan(v, &tot, lds);
-        if (i < end) {
-            out[i] = carry + ex;
-            if (rsq) rsq[i] = (float)(1.0 / sqrt((double)(v < 1 ? 1 : v)));
-        }
-        carry += tot;
-    }
-    if (b == (int)gridDim.x - 1 && threadIdx.x == 0) out[n] = carry;
-}
-
-// ------------------------------------------------ degrees + long-row buckets ----
-// Pass 1 over row pointers: row lengths, scale factors, and per-block counts of
-// long rows / their chunks.
-__global__ __launch_bounds__(kBlock) void k_rows_count(const int32_t *__restrict__ rowptr, int64_t n,
-                                                       int64_t per, int32_t *__restrict__ len_out,
-                                                       float *__restrict__ inv, float *__restrict__ rsq,
-                                                       int32_t *__restrict__ counts)
-{
-    __shared__ int lds[kBlock / kWave];
-    int64_t beg = blockIdx.x * per, end = beg + per < n ? beg + per : n;
-    int nl = 0, nc = 0;
-    for (int64_t r = beg + threadIdx.x; r < end; r += kBlock) {
-        int len = rowptr[r + 1] - rowptr[r];
-        if (len_out) len_out[r] = len;
-        double d = (double)(len < 1 ? 1 : len);
-        if (inv) inv[r] = (float)(1.0 / d);
-        if (rsq) rsq[r] = (float)(1.0 / sqrt(d));
-        if (len > kLongThreshold) {
-            nl += 1;
-            nc += (len + kLongChunk - 1) / kLongChunk;
-        }
-    }
-    nl = block_sum(nl, lds);
-    nc = block_sum(nc, lds);
-    if (threadIdx.x == 0) {
-        counts[2 * blockIdx.x] = nl;
-        counts[2 * blockIdx.x + 1] = nc;
-    }
-}
-
-// Pass 2: ordered compaction.  long_rows ascending; chunk_ptr[i] = first chunk of
-// the i-th long row; totals[0] = number of long rows, totals[1] = number of chunks.
-__global__ __launch_bounds__(kBlock) void k_rows_fill(const int32_t *__restrict__ rowptr, int64_t n,
-                                                      int64_t per, const int32_t *__restrict__ counts,
-                                                      int32_t *__restrict__ long_rows,
-                                                      int32_t *__restrict__ chunk_ptr,
-                                                      int32_t *__restrict__ totals)
-{
-    __shared__ int lds[kBlock / kWave];
-    const int b = blockIdx.x;
-    int pl = 0, pc = 0;
-    for (int i = threadIdx.x; i < b; i += kBlock) {
-        pl += counts[2 * i];
-        pc += counts[2 * i + 1];
-    }
-    int cl = block_sum(pl, lds);
-    int cc = block_sum(pc, lds);
-    int64_t beg = b * per, end = beg + per < n ? beg + per : n;
-    for (int64_t base = beg; base < end; base += kBlock) {
-        int64_t r = base + threadIdx.x;
-        int len = r < end ? rowptr[r + 1] - rowptr[r] : 0;
-        int isl = len > kLongThreshold ? 1 : 0;
-        int nch = isl ? (len + kLongChunk - 1) / kLongChunk : 0;
-        int tl, tc;
-        int el = block_excl_scan(isl, &tl, lds);
-        int ec = block_excl_scan(nch, &tc, lds);
-        if (isl) {
-            long_rows[cl + el] = (int32_t)r;
-            chunk_ptr[cl + el] = cc + ec;
-        }
-        cl += tl;
-        cc += tc;
-    }
-    if (b == (int)gridDim.x - 1 && threadIdx.x == 0) {
-        chunk_ptr[cl] = cc;
-        totals[0] = cl;
-        totals[1] = cc;
-    }
-}
-
-// ------------------------------------------------------------ radix sort ----
-__global__ __launch_bounds__(kBlock) void k_radix_hist(const int32_t *__restrict__ keys, int64_t n,
-                                                       int64_t per, int shift,
-                                                       int32_t *__restrict__ cnt)
-{
-    __shared__ int h[kRadixBins];
-    h[threadIdx.x] = 0;
-    __syncthreads();
-    int64_t beg = blockIdx.x * per, end = beg + per < n ? beg + per : n;
-    for (int64_t i = beg + threadIdx.x; i < end; i += kBlock)
-        atomicAdd(&h[(keys[i] >> shift) & (kRadixBins - 1)], 1);
-    __syncthreads();
-    cnt[(int64_t)threadIdx.x * gridDim.x + blockIdx.x] = h[threadIdx.x];
-}
-
-// largest u with indptr[u] <= e  (the destination row that owns edge e)
-__device__ __forceinline__ int32_t owner_row(const int32_t *__restrict__ indptr, int32_t num_rows, int32_t e)
-{
-    int32_t lo = 0, hi = num_rows;   // invariant: indptr[lo] <= e < indptr[hi]
-    while (hi - lo > 1) {
-        int32_t mid = lo + ((hi - lo) >> 1);
-        if (indptr[mid] <= e) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// Stable scatter of one digit.  base[d*nb + b] = first output slot of digit d for
-// block b.  vals_in == NULL means the identity (first pass).  LAST: write the
-// final permutation and the destination row of every edge instead of keys.
-template <bool LAST>
-__global__ __launch_bounds__(kBlock) void k_radix_scatter(
-    const int32_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in, int64_t n, int64_t per,
-    int shift, const int32_t *__restrict__ base, int32_t *__restrict__ keys_out,
-    int32_t *__restrict__ vals_out, const int32_t *__restrict__ indptr, int32_t num_dst,
-    int32_t *__restrict__ dst_out)
-{
-    __shared__ int running[kRadixBins];
-    __shared__ int wcnt[kBlock / kWave][kRadixBins];
-    const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
-    running[t] = base[(int64_t)t * gridDim.x + blockIdx.x];
-    int64_t beg = blockIdx.x * per, end = beg + per < n ? beg + per : n;
-    for (int64_t tile = beg; tile < end; tile += kSortTile) {
-        int64_t i = tile + t;
-        bool valid = i < end;
-        int32_t key = valid ? keys_in[i] : 0;
-        int32_t val = valid ? (vals_in ? vals_in[i] : (int32_t)i) : 0;
-        int d = (key >> shift) & (kRadixBins - 1);
-#pragma unroll
-        for (int k = 0; k < kBlock / kWave; ++k) wcnt[k][t] = 0;
-        __syncthreads();
-        unsigned long long mask = __ballot(valid);
-#pragma unroll
-        for (int bit = 0; bit < kRadixBits; ++bit) {
-            bool one = (d >> bit) & 1;
-            unsigned long long bl = __ballot(one);
-            mask &= one ? bl : ~bl;
-        }
-        int lower = __popcll(mask & ((1ull << lane) - 1ull));
-        if (valid && lower == 0) wcnt[w][d] = __popcll(mask);
-        __syncthreads();
-        int pos = 0;
-        if (valid) {
-            pos = running[d] + lower;
-            for (int k = 0; k < w; ++k) pos += wcnt[k][d];
-        }
-        __syncthreads();
-        {
-            int add = 0;
-#pragma unroll
-            for (int k = 0; k < kBlock / kWave; ++k) add += wcnt[k][t];
-            running[t] += add;
-        }
-        if (valid) {
-            if (LAST) {
-                vals_out[pos] = val;
-                dst_out[pos] = owner_row(indptr, num_dst, val);
-            } else {
-                keys_out[pos] = key;
-                vals_out[pos] = val;
-            }
-        }
-        // the zeroing of wcnt[*][t] at the top of the next step is done by the
-        // same thread that just read it; readers of running[] wait at the barrier
-        // that follows the zeroing.
+    for (int64_t i = blockIdx.x * (int64_t)kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock) {
+        int d = deg[i];
+        rsq[i] = (float)(1.0 / sqrt((double)(d < 1 ? 1 : d)));
     }
 }
 
@@ -288,13 +388,18 @@ static int grid_for(int64_t n, int per_thread)
     return (int)g;
 }
 
-static void scan_shape(int64_t n, int *nb, int64_t *per)
+static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, float *inv, float *rsq,
+                          int32_t *counts, int32_t *long_rows, int32_t *chunk_ptr, int32_t *totals)
 {
-    int64_t b = ceil_div(n, (int64_t)kBlock * 8);
+    RowsArgs A;
+    int64_t b = ceil_div(n, (int64_t)kSortThreads * 4);
     if (b < 1) b = 1;
     if (b > kMaxScanBlocks) b = kMaxScanBlocks;
-    *nb = (int)b;
-    *per = n > 0 ? ceil_div(n, b) : 1;
+    A.rowptr = rowptr; A.n = n; A.nb = (int)b;
+    A.per = n > 0 ? ceil_div(n, b) : 1;
+    A.len_out = len_out; A.inv = inv; A.rsq = rsq;
+    A.counts = counts; A.long_rows = long_rows; A.chunk_ptr = chunk_ptr; A.totals = totals;
+    return A;
 }
 
 size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges)
@@ -323,108 +428,82 @@ size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src,
     q->chunk_ptr_src = (int32_t *)take(4 * ((size_t)cl + 1));
     q->counters = (int32_t *)take(4 * 4);
     for (int i = 0; i < 4; ++i) q->sort_buf[i] = (int32_t *)take(4 * (size_t)num_edges);
-    q->radix_cnt = (int32_t *)take(4 * ((size_t)kRadixBins * kMaxScanBlocks + 1));
+    q->edge_dst = (int32_t *)take(4 * (size_t)num_edges);
+    q->radix_cnt = (int32_t *)take(4 * (size_t)kRadixBins * kMaxSortBlocks);
     q->block_sums = (int32_t *)take(4 * 2 * (size_t)kMaxScanBlocks);
+    q->block_sums2 = (int32_t *)take(4 * 2 * (size_t)kMaxScanBlocks);
     return off;
 }
 
-static fastgl_status exclusive_scan(const int32_t *in, int64_t n, int32_t *out, float *rsq,
-                                    int32_t *bsum, hipStream_t s)
+static fastgl_status bucket_rows(const RowsArgs &A, hipStream_t s)
 {
-    int nb;
-    int64_t per;
-    scan_shape(n, &nb, &per);
-    hipLaunchKernelGGL(k_scan_partials, dim3(nb), dim3(kBlock), 0, s, in, n, per, bsum);
-    FASTGL_LAUNCH_CHECK("k_scan_partials");
-    hipLaunchKernelGGL(k_scan_final, dim3(nb), dim3(kBlock), 0, s, in, n, per, bsum, out, rsq);
-    FASTGL_LAUNCH_CHECK("k_scan_final");
-    return FASTGL_OK;
-}
-
-static fastgl_status bucket_rows(const int32_t *rowptr, int64_t n, int32_t *len_out, float *inv,
-                                 float *rsq, int32_t *long_rows, int32_t *chunk_ptr, int32_t *totals,
-                                 int32_t *bsum, hipStream_t s)
-{
-    int nb;
-    int64_t per;
-    scan_shape(n, &nb, &per);
-    hipLaunchKernelGGL(k_rows_count, dim3(nb), dim3(kBlock), 0, s, rowptr, n, per, len_out, inv, rsq, bsum);
+    hipLaunchKernelGGL(k_rows_count, dim3(A.nb), dim3(kSortThreads), 0, s, A);
     FASTGL_LAUNCH_CHECK("k_rows_count");
-    hipLaunchKernelGGL(k_rows_fill, dim3(nb), dim3(kBlock), 0, s, rowptr, n, per, bsum, long_rows,
-                       chunk_ptr, totals);
+    hipLaunchKernelGGL(k_rows_fill, dim3(A.nb), dim3(kSortThreads), 0, s, A);
     FASTGL_LAUNCH_CHECK("k_rows_fill");
     return FASTGL_OK;
 }
 
-static fastgl_status stable_transpose(fastgl_plan *p, hipStream_t s)
+// Sort (source id, edge id) pairs, ride the destination-side bucket kernels along
+// with the first pass, then derive indptr_T and the source-side buckets.
+static fastgl_status transpose_and_buckets(fastgl_plan *p, const RowsArgs &dstA, hipStream_t s)
 {
     const int64_t n = p->num_edges;
     int bits = 1;
     while (bits < 31 && ((int64_t)1 << bits) < p->num_src) ++bits;
     const int npass = (bits + kRadixBits - 1) / kRadixBits;
-    int64_t nb64 = ceil_div(n, (int64_t)kSortTile * 8);
-    if (nb64 < 1) nb64 = 1;
-    if (nb64 > kMaxScanBlocks) nb64 = kMaxScanBlocks;
-    const int nb = (int)nb64;
-    const int64_t per = n > 0 ? ceil_div(n, (int64_t)nb) : 1;
+    SortArgs S;
+    S.n = n;
+    int64_t per = ceil_div(ceil_div(n, (int64_t)kMaxSortBlocks), (int64_t)kSortStep) * kSortStep;
+    if (per < kSortStep) per = kSortStep;
+    S.per = per;
+    S.nb = n > 0 ? (int)ceil_div(n, per) : 1;
+    S.cnt = p->radix_cnt;
+    S.indptr = p->indptr; S.num_dst = (int32_t)p->num_dst;
+    S.edge_dst = p->edge_dst;
     const int32_t *kin = p->indices, *vin = nullptr;
     for (int pass = 0; pass < npass; ++pass) {
-        const int shift = pass * kRadixBits;
-        const bool last = pass == npass - 1;
-        int32_t *kout = p->sort_buf[(pass & 1) * 2], *vout = p->sort_buf[(pass & 1) * 2 + 1];
-        hipLaunchKernelGGL(k_radix_hist, dim3(nb), dim3(kBlock), 0, s, kin, n, per, shift, p->radix_cnt);
-        FASTGL_LAUNCH_CHECK("k_radix_hist");
-        fastgl_status st = exclusive_scan(p->radix_cnt, (int64_t)kRadixBins * nb, p->radix_cnt, nullptr,
-                                          p->block_sums, s);
-        if (st != FASTGL_OK) return st;
-        if (last) {
-            hipLaunchKernelGGL(k_radix_scatter<true>, dim3(nb), dim3(kBlock), 0, s, kin, vin, n, per, shift,
-                               p->radix_cnt, (int32_t *)nullptr, p->perm, p->indptr, (int32_t)p->num_dst,
-                               p->indices_T);
-        } else {
-            hipLaunchKernelGGL(k_radix_scatter<false>, dim3(nb), dim3(kBlock), 0, s, kin, vin, n, per, shift,
-                               p->radix_cnt, kout, vout, p->indptr, (int32_t)p->num_dst, (int32_t *)nullptr);
-        }
-        FASTGL_LAUNCH_CHECK("k_radix_scatter");
-        kin = kout;
-        vin = vout;
+        const bool first = pass == 0, last = pass == npass - 1;
+        S.keys_in = kin; S.vals_in = vin; S.shift = pass * kRadixBits;
+        S.keys_out = p->sort_buf[(pass & 1) * 2];
+        S.vals_out = last ? p->perm : p->sort_buf[(pass & 1) * 2 + 1];
+        S.dst_out = p->indices_T;
+        const int extra = first ? dstA.nb : 0;
+        if (first) hipLaunchKernelGGL(k_sort_hist<true>, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA);
+        else hipLaunchKernelGGL(k_sort_hist<false>, dim3(S.nb), dim3(kSortThreads), 0, s, S, dstA);
+        FASTGL_LAUNCH_CHECK("k_sort_hist");
+        if (last) hipLaunchKernelGGL(k_sort_scatter<true>, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA, extra ? 1 : 0);
+        else hipLaunchKernelGGL(k_sort_scatter<false>, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA, extra ? 1 : 0);
+        FASTGL_LAUNCH_CHECK("k_sort_scatter");
+        kin = S.keys_out;
+        vin = S.vals_out;
     }
-    return FASTGL_OK;
+    hipLaunchKernelGGL(k_row_starts, dim3(grid_for(n + 1, 1)), dim3(kBlock), 0, s, kin, n, p->num_src, p->indptr_T);
+    FASTGL_LAUNCH_CHECK("k_row_starts");
+    RowsArgs srcA = rows_args(p->indptr_T, p->num_src, p->dout, nullptr, p->src_rsqrt, p->block_sums2,
+                              p->long_src, p->chunk_ptr_src, p->counters + 2);
+    return bucket_rows(srcA, s);
 }
 
 // Enqueue the bookkeeping kernels for the requested parts.  need_src_degrees
 // asks for dout / src_rsqrt even when only the forward part is built (GCN).
 fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipStream_t s)
 {
-    fastgl_status st;
     p->parts = parts;
-    if (parts & FASTGL_PLAN_FWD) {
-        st = bucket_rows(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->long_dst,
-                         p->chunk_ptr_dst, p->counters, p->block_sums, s);
-        if (st != FASTGL_OK) return st;
-    }
-    if ((parts & FASTGL_PLAN_BWD) || need_src_degrees) {
-        hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout,
-                           p->num_src, 0);
+    RowsArgs dstA = rows_args(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->block_sums,
+                              p->long_dst, p->chunk_ptr_dst, p->counters);
+    if (parts & FASTGL_PLAN_BWD) return transpose_and_buckets(p, dstA, s);   // includes the forward part
+    fastgl_status st = bucket_rows(dstA, s);
+    if (st != FASTGL_OK) return st;
+    if (need_src_degrees) {
+        hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout, p->num_src, 0);
         FASTGL_LAUNCH_CHECK("k_fill_i32");
         hipLaunchKernelGGL(k_hist, dim3(grid_for(p->num_edges, 4)), dim3(kBlock), 0, s, p->indices,
                            p->num_edges, p->dout);
         FASTGL_LAUNCH_CHECK("k_hist");
-        st = exclusive_scan(p->dout, p->num_src, p->indptr_T, p->src_rsqrt, p->block_sums, s);
-        if (st != FASTGL_OK) return st;
-    }
-    if (parts & FASTGL_PLAN_BWD) {
-        if (!(parts & FASTGL_PLAN_FWD)) {
-            // backward gathers rows of grad_out scaled by the destination-side factors
-            st = bucket_rows(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->long_dst,
-                             p->chunk_ptr_dst, p->counters, p->block_sums, s);
-            if (st != FASTGL_OK) return st;
-        }
-        st = bucket_rows(p->indptr_T, p->num_src, nullptr, nullptr, nullptr, p->long_src,
-                         p->chunk_ptr_src, p->counters + 2, p->block_sums, s);
-        if (st != FASTGL_OK) return st;
-        st = stable_transpose(p, s);
-        if (st != FASTGL_OK) return st;
+        hipLaunchKernelGGL(k_rsqrt_deg, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout, p->num_src,
+                           p->src_rsqrt);
+        FASTGL_LAUNCH_CHECK("k_rsqrt_deg");
     }
     return FASTGL_OK;
 }

@@ -15,7 +15,6 @@ constexpr int kLongChunk = 128;        // edges per partial-sum chunk
 constexpr int kMaxScanBlocks = 1024;   // blocks of a two-kernel scan / compaction
 constexpr int kRadixBits = 8;
 constexpr int kRadixBins = 1 << kRadixBits;
-constexpr int kSortTile = 256;         // keys ranked per step by one sort block
 constexpr int kXcds = 8;               // workgroups are dealt round-robin to 8 L2 domains
 
 void set_error(const char *fmt, ...);
@@ -53,8 +52,10 @@ struct fastgl_plan {
     int32_t *counters;      // [4] n_long_dst, n_chunks_dst, n_long_src, n_chunks_src
     // scratch
     int32_t *sort_buf[4];   // ping-pong keys / values, num_edges each
-    int32_t *radix_cnt;     // kRadixBins * sort blocks
-    int32_t *block_sums;    // 2 * kMaxScanBlocks
+    int32_t *edge_dst;      // [num_edges] destination row of every edge
+    int32_t *radix_cnt;     // [sort blocks][kRadixBins]
+    int32_t *block_sums;    // 2 * kMaxScanBlocks (destination-side bucket counts)
+    int32_t *block_sums2;   // same for the source side
 };
 
 namespace fastgl {

@@ -123,6 +123,11 @@ def test_bookkeeping_bit_exact_small():
     check_bookkeeping(bg.random_block(rng, 70000, 300, 3.0), "few-sources")          # one radix pass... two
     check_bookkeeping(bg.random_block(rng, 300, 70000, 40.0, hub_rows=2, hub_deg=9000), "many-sources")
     check_bookkeeping(bg.make_config(1).blocks[0], "config1")
+    check_bookkeeping(bg.random_block(rng, 50, 200, 30.0), "one-radix-pass")
+    # four radix passes, long runs of sources without edges, a run longer than a wavefront
+    big = bg.random_block(rng, 4000, 17_000_000, 25.0, hub_rows=1, hub_deg=3000)
+    big.indices[big.indices > 9_000_000] = 16_999_999
+    check_bookkeeping(big, "sparse-id-space")
 
 
 def test_validate_counts_violations():
