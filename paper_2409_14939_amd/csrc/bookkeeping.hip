@@ -22,8 +22,7 @@ namespace fastgl {
 
 constexpr int kSortThreads = 1024;                   // 16 wavefronts per sort workgroup
 constexpr int kSortWaves = kSortThreads / kWave;
-constexpr int kSortItems = 4;                        // keys per thread and step
-constexpr int kSortStep = kSortThreads * kSortItems; // keys ranked per step by one workgroup
+constexpr int kMaxSortItems = 16;                    // keys per thread and step: 1, 2, 4, 8 or 16
 constexpr int kMaxSortBlocks = 256;
 
 // -------------------------------------------------- block-wide primitives ----
@@ -73,23 +72,45 @@ struct RowsArgs {
     float *inv, *rsq;        // [n] or NULL: 1/max(len,1), 1/sqrt(max(len,1))
     int32_t *counts;         // [2*nb] per-block (long rows, chunks)
     int32_t *long_rows, *chunk_ptr, *totals;
+    int32_t *edge_row;       // [nnz] or NULL: edge_row[e] = row that owns edge e
 };
 
-// Pass 1 over row pointers: row lengths, scale factors, and per-block counts of
-// long rows / their chunks.
+// Pass 1 over row pointers: row lengths, scale factors, per-block counts of long
+// rows / their chunks, and (optionally) the row id of every edge.  A thread
+// expands its own short rows; rows longer than a wavefront are expanded by the
+// whole wavefront, one after the other.
 __device__ __forceinline__ void rows_count(const RowsArgs &A, int b, int *lds)
 {
     int64_t beg = b * A.per, end = beg + A.per < A.n ? beg + A.per : A.n;
+    const int lane = threadIdx.x & (kWave - 1);
     int nl = 0, nc = 0;
-    for (int64_t r = beg + threadIdx.x; r < end; r += blockDim.x) {
-        int len = A.rowptr[r + 1] - A.rowptr[r];
-        if (A.len_out) A.len_out[r] = len;
-        double d = (double)(len < 1 ? 1 : len);
-        if (A.inv) A.inv[r] = (float)(1.0 / d);
-        if (A.rsq) A.rsq[r] = (float)(1.0 / sqrt(d));
-        if (len > kLongThreshold) {
-            nl += 1;
-            nc += (len + kLongChunk - 1) / kLongChunk;
+    for (int64_t base = beg; base < end; base += blockDim.x) {
+        const int64_t r = base + threadIdx.x;
+        int e0 = 0, len = 0;
+        if (r < end) {
+            e0 = A.rowptr[r];
+            len = A.rowptr[r + 1] - e0;
+            if (A.len_out) A.len_out[r] = len;
+            double d = (double)(len < 1 ? 1 : len);
+            if (A.inv) A.inv[r] = (float)(1.0 / d);
+            if (A.rsq) A.rsq[r] = (float)(1.0 / sqrt(d));
+            if (len > kLongThreshold) {
+                nl += 1;
+                nc += (len + kLongChunk - 1) / kLongChunk;
+            }
+        }
+        if (A.edge_row) {
+            const bool big = len > kWave;
+            if (!big)
+                for (int k = 0; k < len; ++k) A.edge_row[e0 + k] = (int32_t)r;
+            unsigned long long m = __ballot(big);
+            while (m) {
+                const int leader = __ffsll((long long)m) - 1;
+                const int le0 = __shfl(e0, leader, kWave), ll = __shfl(len, leader, kWave);
+                const int lr = (int)(base - beg) + (threadIdx.x - lane) + leader;   // row offset in block
+                for (int k = lane; k < ll; k += kWave) A.edge_row[le0 + k] = (int32_t)(beg + lr);
+                m &= m - 1;
+            }
         }
     }
     nl = block_sum(nl, lds);
@@ -156,27 +177,12 @@ struct SortArgs {
     int64_t n, per;                     // block b owns keys [b*per, min(n,(b+1)*per))
     int nb, shift;
     int32_t *cnt;                       // [nb][256] digit counts per block
-    // first pass: also record the destination row of every edge
-    const int32_t *indptr;
-    int32_t num_dst;
-    int32_t *edge_dst;                  // [n]; written by the first pass, read by the last
+    const int32_t *edge_dst;            // [n] destination row of every edge (read by the last pass)
     int32_t *dst_out;                   // last pass: [n] destination row in sorted order
 };
 
-// largest u in [lo, hi) with indptr[u] <= e  (the destination row that owns edge e)
-__device__ __forceinline__ int32_t owner_row(const int32_t *__restrict__ indptr, int32_t lo, int32_t hi, int32_t e)
-{
-    while (hi - lo > 1) {   // invariant: indptr[lo] <= e < indptr[hi]
-        int32_t mid = lo + ((hi - lo) >> 1);
-        if (indptr[mid] <= e) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// Digit histogram of the block's key range.  FIRST: also expand the CSR row ids
-// (edge_dst[e] = row owning e), searching only the rows this block's edges touch.
-// Workgroups beyond S.nb run the destination-side row count.
-template <bool FIRST>
+// Digit histogram of the block's key range.  Workgroups beyond S.nb run the
+// destination-side row count (first pass only).
 __global__ __launch_bounds__(kSortThreads) void k_sort_hist(SortArgs S, RowsArgs R)
 {
     __shared__ int h[kRadixBins];
@@ -188,15 +194,8 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(SortArgs S, RowsArgs
     if (threadIdx.x < kRadixBins) h[threadIdx.x] = 0;
     __syncthreads();
     const int64_t beg = blockIdx.x * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
-    int32_t rlo = 0, rhi = 1;
-    if (FIRST && beg < end) {
-        rlo = owner_row(S.indptr, 0, S.num_dst, (int32_t)beg);
-        rhi = owner_row(S.indptr, rlo, S.num_dst, (int32_t)(end - 1)) + 1;
-    }
-    for (int64_t i = beg + threadIdx.x; i < end; i += kSortThreads) {
+    for (int64_t i = beg + threadIdx.x; i < end; i += kSortThreads)
         atomicAdd(&h[(S.keys_in[i] >> S.shift) & (kRadixBins - 1)], 1);
-        if (FIRST) S.edge_dst[i] = owner_row(S.indptr, rlo, rhi, (int32_t)i);
-    }
     __syncthreads();
     if (threadIdx.x < kRadixBins) S.cnt[(int64_t)blockIdx.x * kRadixBins + threadIdx.x] = h[threadIdx.x];
 }
@@ -204,13 +203,13 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(SortArgs S, RowsArgs
 // Stable scatter of one digit.  Every workgroup derives its own output offsets
 // from the [nb][256] count table (no separate scan launch): for digit d,
 //   base = sum_{d' < d} total[d'] + sum_{b' < b} cnt[b'][d].
-// Within a step of 4096 keys each wavefront owns 256 consecutive keys and ranks
+// Within a step of 1024*ITEMS keys each wavefront owns 64*ITEMS consecutive keys and ranks
 // them 64 at a time: lanes with equal digits find each other with 8 ballots, the
 // running per-wavefront digit counts live in LDS, and a column scan over the 16
 // wavefronts turns them into absolute positions.
 // LAST: write sorted keys, the permutation, and the destination row of each edge.
 // Workgroups beyond S.nb run the destination-side row fill (first pass only).
-template <bool LAST>
+template <bool LAST, int ITEMS>
 __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsArgs R, int rows_role)
 {
     __shared__ int running[kRadixBins];
@@ -225,10 +224,19 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsA
     {   // offsets of this block's digits
         const int d = t & (kRadixBins - 1), part = t / kRadixBins;   // 4 parts share the blocks
         int below = 0, total = 0;
-        for (int bb = part; bb < S.nb; bb += kSortThreads / kRadixBins) {
-            int c = S.cnt[(int64_t)bb * kRadixBins + d];
-            total += c;
-            if (bb < b) below += c;
+        constexpr int kParts = kSortThreads / kRadixBins, kBatch = 16;
+        for (int b0 = part; b0 < S.nb; b0 += kParts * kBatch) {
+            int c[kBatch];
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {   // independent loads first
+                const int bb = b0 + k * kParts;
+                c[k] = bb < S.nb ? S.cnt[(int64_t)bb * kRadixBins + d] : 0;
+            }
+#pragma unroll
+            for (int k = 0; k < kBatch; ++k) {
+                total += c[k];
+                if (b0 + k * kParts < b) below += c[k];
+            }
         }
         wcnt[part][d] = below;
         wcnt[4 + part][d] = total;
@@ -247,24 +255,24 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsA
         __syncthreads();
     }
     const int64_t beg = b * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
-    for (int64_t step = beg; step < end; step += kSortStep) {
+    for (int64_t step = beg; step < end; step += kSortThreads * ITEMS) {
 #pragma unroll
         for (int k = 0; k < kSortWaves * kRadixBins / kSortThreads; ++k)
             (&wcnt[0][0])[k * kSortThreads + t] = 0;
         __syncthreads();
-        int32_t key[kSortItems], val[kSortItems];
-        int rank[kSortItems], dig[kSortItems];
-        bool ok[kSortItems];
+        int32_t key[ITEMS], val[ITEMS];
+        int rank[ITEMS], dig[ITEMS];
+        bool ok[ITEMS];
 #pragma unroll
-        for (int i = 0; i < kSortItems; ++i) {
-            const int64_t idx = step + (int64_t)w * (kWave * kSortItems) + i * kWave + lane;
+        for (int i = 0; i < ITEMS; ++i) {
+            const int64_t idx = step + (int64_t)w * (kWave * ITEMS) + i * kWave + lane;
             ok[i] = idx < end;
             key[i] = ok[i] ? S.keys_in[idx] : 0;
             val[i] = ok[i] ? (S.vals_in ? S.vals_in[idx] : (int32_t)idx) : 0;
             dig[i] = (key[i] >> S.shift) & (kRadixBins - 1);
         }
 #pragma unroll
-        for (int i = 0; i < kSortItems; ++i) {
+        for (int i = 0; i < ITEMS; ++i) {
             unsigned long long mask = __ballot(ok[i]);
 #pragma unroll
             for (int bit = 0; bit < kRadixBits; ++bit) {
@@ -291,7 +299,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsA
         }
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < kSortItems; ++i) {
+        for (int i = 0; i < ITEMS; ++i) {
             if (!ok[i]) continue;
             const int pos = wcnt[w][dig[i]] + rank[i];
             if (LAST) {
@@ -389,7 +397,8 @@ static int grid_for(int64_t n, int per_thread)
 }
 
 static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, float *inv, float *rsq,
-                          int32_t *counts, int32_t *long_rows, int32_t *chunk_ptr, int32_t *totals)
+                          int32_t *counts, int32_t *long_rows, int32_t *chunk_ptr, int32_t *totals,
+                          int32_t *edge_row = nullptr)
 {
     RowsArgs A;
     int64_t b = ceil_div(n, (int64_t)kSortThreads * 4);
@@ -399,6 +408,7 @@ static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, fl
     A.per = n > 0 ? ceil_div(n, b) : 1;
     A.len_out = len_out; A.inv = inv; A.rsq = rsq;
     A.counts = counts; A.long_rows = long_rows; A.chunk_ptr = chunk_ptr; A.totals = totals;
+    A.edge_row = edge_row;
     return A;
 }
 
@@ -454,12 +464,15 @@ static fastgl_status transpose_and_buckets(fastgl_plan *p, const RowsArgs &dstA,
     const int npass = (bits + kRadixBits - 1) / kRadixBits;
     SortArgs S;
     S.n = n;
-    int64_t per = ceil_div(ceil_div(n, (int64_t)kMaxSortBlocks), (int64_t)kSortStep) * kSortStep;
-    if (per < kSortStep) per = kSortStep;
+    // one step per workgroup when the keys fit 256 workgroups x 16 keys per thread
+    int items = 1;
+    while (items < kMaxSortItems && (int64_t)items * kSortThreads * kMaxSortBlocks < n) items <<= 1;
+    const int64_t step = (int64_t)items * kSortThreads;
+    int64_t per = ceil_div(ceil_div(n, (int64_t)kMaxSortBlocks), step) * step;
+    if (per < step) per = step;
     S.per = per;
     S.nb = n > 0 ? (int)ceil_div(n, per) : 1;
     S.cnt = p->radix_cnt;
-    S.indptr = p->indptr; S.num_dst = (int32_t)p->num_dst;
     S.edge_dst = p->edge_dst;
     const int32_t *kin = p->indices, *vin = nullptr;
     for (int pass = 0; pass < npass; ++pass) {
@@ -469,11 +482,21 @@ static fastgl_status transpose_and_buckets(fastgl_plan *p, const RowsArgs &dstA,
         S.vals_out = last ? p->perm : p->sort_buf[(pass & 1) * 2 + 1];
         S.dst_out = p->indices_T;
         const int extra = first ? dstA.nb : 0;
-        if (first) hipLaunchKernelGGL(k_sort_hist<true>, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA);
-        else hipLaunchKernelGGL(k_sort_hist<false>, dim3(S.nb), dim3(kSortThreads), 0, s, S, dstA);
+        hipLaunchKernelGGL(k_sort_hist, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA);
         FASTGL_LAUNCH_CHECK("k_sort_hist");
-        if (last) hipLaunchKernelGGL(k_sort_scatter<true>, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA, extra ? 1 : 0);
-        else hipLaunchKernelGGL(k_sort_scatter<false>, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA, extra ? 1 : 0);
+        const dim3 grid(S.nb + extra), blk(kSortThreads);
+        const int role = extra ? 1 : 0;
+#define FASTGL_SCATTER(IT)                                                                        \
+    if (last) hipLaunchKernelGGL((k_sort_scatter<true, IT>), grid, blk, 0, s, S, dstA, role);     \
+    else hipLaunchKernelGGL((k_sort_scatter<false, IT>), grid, blk, 0, s, S, dstA, role)
+        switch (items) {
+            case 1: FASTGL_SCATTER(1); break;
+            case 2: FASTGL_SCATTER(2); break;
+            case 4: FASTGL_SCATTER(4); break;
+            case 8: FASTGL_SCATTER(8); break;
+            default: FASTGL_SCATTER(16); break;
+        }
+#undef FASTGL_SCATTER
         FASTGL_LAUNCH_CHECK("k_sort_scatter");
         kin = S.keys_out;
         vin = S.vals_out;
@@ -491,7 +514,8 @@ fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipSt
 {
     p->parts = parts;
     RowsArgs dstA = rows_args(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->block_sums,
-                              p->long_dst, p->chunk_ptr_dst, p->counters);
+                              p->long_dst, p->chunk_ptr_dst, p->counters,
+                              (parts & FASTGL_PLAN_BWD) ? p->edge_dst : nullptr);
     if (parts & FASTGL_PLAN_BWD) return transpose_and_buckets(p, dstA, s);   // includes the forward part
     fastgl_status st = bucket_rows(dstA, s);
     if (st != FASTGL_OK) return st;
