@@ -22,7 +22,7 @@ namespace fastgl {
 
 constexpr int kSortThreads = 1024;                   // 16 wavefronts per sort workgroup
 constexpr int kSortWaves = kSortThreads / kWave;
-constexpr int kMaxSortItems = 16;                    // keys per thread and step: 1, 2, 4, 8 or 16
+constexpr int kMaxSortItems = 4;                     // keys per thread and step: 1, 2 or 4
 constexpr int kMaxSortBlocks = 256;
 
 // -------------------------------------------------- block-wide primitives ----
@@ -206,14 +206,16 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(SortArgs S, RowsArgs
 // Within a step of 1024*ITEMS keys each wavefront owns 64*ITEMS consecutive keys and ranks
 // them 64 at a time: lanes with equal digits find each other with 8 ballots, the
 // running per-wavefront digit counts live in LDS, and a column scan over the 16
-// wavefronts turns them into absolute positions.
+// wavefronts plus a scan over the digits give each key its place in the step's
+// sorted order.  The step is sorted into LDS first and written out from there.
 // LAST: write sorted keys, the permutation, and the destination row of each edge.
 // Workgroups beyond S.nb run the destination-side row fill (first pass only).
 template <bool LAST, int ITEMS>
 __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsArgs R, int rows_role)
 {
-    __shared__ int running[kRadixBins];
+    __shared__ int running[kRadixBins], lbase[kRadixBins], gdelta[kRadixBins];
     __shared__ int wcnt[kSortWaves][kRadixBins];
+    __shared__ int32_t skey[kSortThreads * ITEMS], sval[kSortThreads * ITEMS];
     __shared__ int lds[16];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
     if ((int)blockIdx.x >= S.nb) {
@@ -287,31 +289,46 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsA
             if (ok[i] && lower == 0) wcnt[w][dig[i]] = prior + __popcll(mask);
         }
         __syncthreads();
-        if (t < kRadixBins) {   // column scan over the wavefronts -> absolute bases
-            int run = running[t];
+        // column scan over the wavefronts, then a scan over the digits: position of
+        // every key inside this step's sorted order
+        int tot_t = 0;
+        if (t < kRadixBins) {
 #pragma unroll
             for (int k = 0; k < kSortWaves; ++k) {
                 int c = wcnt[k][t];
-                wcnt[k][t] = run;
-                run += c;
+                wcnt[k][t] = tot_t;
+                tot_t += c;
             }
-            running[t] = run;
+        }
+        int nvalid;
+        const int lb = block_excl_scan(tot_t, &nvalid, lds);
+        if (t < kRadixBins) {
+            lbase[t] = lb;
+            gdelta[t] = running[t] - lb;   // global position = gdelta[digit] + position in the step
+            running[t] += tot_t;
         }
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             if (!ok[i]) continue;
-            const int pos = wcnt[w][dig[i]] + rank[i];
-            if (LAST) {
-                S.keys_out[pos] = key[i];
-                S.vals_out[pos] = val[i];
-                S.dst_out[pos] = S.edge_dst[val[i]];
-            } else {
-                S.keys_out[pos] = key[i];
-                S.vals_out[pos] = val[i];
-            }
+            const int lpos = lbase[dig[i]] + wcnt[w][dig[i]] + rank[i];
+            skey[lpos] = key[i];
+            sval[lpos] = val[i];
         }
-        __syncthreads();   // wcnt is cleared at the top of the next step
+        __syncthreads();
+        // keys of one digit are now consecutive in LDS and go to consecutive global
+        // slots: neighbouring threads write neighbouring addresses
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int j = i * kSortThreads + t;
+            if (j >= nvalid) continue;
+            const int32_t k = skey[j], v = sval[j];
+            const int pos = gdelta[(k >> S.shift) & (kRadixBins - 1)] + j;
+            S.keys_out[pos] = k;
+            S.vals_out[pos] = v;
+            if (LAST) S.dst_out[pos] = S.edge_dst[v];
+        }
+        __syncthreads();   // wcnt and the staging arrays are reused by the next step
     }
 }
 
@@ -464,7 +481,7 @@ static fastgl_status transpose_and_buckets(fastgl_plan *p, const RowsArgs &dstA,
     const int npass = (bits + kRadixBits - 1) / kRadixBits;
     SortArgs S;
     S.n = n;
-    // one step per workgroup when the keys fit 256 workgroups x 16 keys per thread
+    // one step per workgroup when the keys fit 256 workgroups x 4 keys per thread
     int items = 1;
     while (items < kMaxSortItems && (int64_t)items * kSortThreads * kMaxSortBlocks < n) items <<= 1;
     const int64_t step = (int64_t)items * kSortThreads;
@@ -492,9 +509,7 @@ static fastgl_status transpose_and_buckets(fastgl_plan *p, const RowsArgs &dstA,
         switch (items) {
             case 1: FASTGL_SCATTER(1); break;
             case 2: FASTGL_SCATTER(2); break;
-            case 4: FASTGL_SCATTER(4); break;
-            case 8: FASTGL_SCATTER(8); break;
-            default: FASTGL_SCATTER(16); break;
+            default: FASTGL_SCATTER(4); break;
         }
 #undef FASTGL_SCATTER
         FASTGL_LAUNCH_CHECK("k_sort_scatter");
