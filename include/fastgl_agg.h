@@ -62,8 +62,13 @@ typedef enum { FASTGL_F32 = 0, FASTGL_BF16 = 1 } fastgl_dtype;
 /* Which parts of the per-block bookkeeping a plan holds. */
 enum {
     FASTGL_PLAN_FWD = 1, /* in-degrees, scale factors, destination-side degree buckets */
-    FASTGL_PLAN_BWD = 2, /* out-degrees, stable transpose CSR, source-side degree buckets */
-    FASTGL_PLAN_ALL = 3
+    FASTGL_PLAN_BWD = 2, /* out-degrees, stable transpose CSR, source-side degree buckets;
+                            implies FASTGL_PLAN_FWD */
+    FASTGL_PLAN_ALL = 3,
+    FASTGL_PLAN_SRC_DEG = 4 /* with FASTGL_PLAN_FWD only: out-degrees and their scale factors by a
+                               histogram, which is all a GCN-normalised FORWARD pass needs beyond
+                               FASTGL_PLAN_FWD.  Lets the forward pass start before the transpose
+                               (built in another plan, possibly on another stream) is ready. */
 };
 
 /* Opaque host-side handle; points into the caller's device buffer. */
@@ -92,7 +97,8 @@ typedef struct {
  *  indptr[num_dst+1], indices[num_edges]: CSR by destination row.
  *  edge_w[num_edges] float or NULL.  X[num_src,feat] in, out[num_dst,feat] out.
  *  plan: NULL, or a plan built for exactly these indptr/indices with
- *        FASTGL_PLAN_FWD.  With NULL the bookkeeping is rebuilt inside
+ *        FASTGL_PLAN_FWD (mode GCN also needs FASTGL_PLAN_SRC_DEG or
+ *        FASTGL_PLAN_BWD).  With NULL the bookkeeping is rebuilt inside
  *        `workspace` on every call.
  *  workspace: at least fastgl_block_workspace_bytes(...) bytes, 256-byte
  *        aligned; contents are scratch.  Calls that share a workspace or a
@@ -123,7 +129,8 @@ size_t fastgl_block_plan_bytes(int64_t num_dst, int64_t num_src, int64_t num_edg
 /* Build the per-block bookkeeping on `stream` inside plan_mem (device,
  * 256-byte aligned, >= fastgl_block_plan_bytes): degrees, scale factors, the
  * stable transpose CSR (transposed rows keep ascending original edge id) and
- * the degree buckets.  `parts` is a mask of FASTGL_PLAN_*.  The plan keeps
+ * the degree buckets.  `parts` is FASTGL_PLAN_FWD, FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG,
+ * FASTGL_PLAN_BWD or FASTGL_PLAN_ALL.  The plan keeps
  * pointers to indptr/indices and plan_mem: they must outlive it and stay
  * unchanged.  *out receives a host handle to free with
  * fastgl_block_plan_destroy.  No host synchronisation. */

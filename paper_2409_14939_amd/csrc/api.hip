@@ -131,8 +131,8 @@ static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32
         if (st != FASTGL_OK) return st;
         pl = &local;
     }
-    if (mode == FASTGL_AGG_GCN && !backward && !(pl->parts & FASTGL_PLAN_BWD) && plan) {
-        set_error("GCN forward needs a plan with source degrees (FASTGL_PLAN_ALL)");
+    if (mode == FASTGL_AGG_GCN && !backward && !(pl->parts & (FASTGL_PLAN_BWD | FASTGL_PLAN_SRC_DEG)) && plan) {
+        set_error("GCN forward needs a plan with source degrees (FASTGL_PLAN_SRC_DEG or FASTGL_PLAN_BWD)");
         return FASTGL_ERR_INVALID_ARG;
     }
 
@@ -205,8 +205,9 @@ fastgl_status fastgl_block_plan_create(const int32_t *indptr, const int32_t *ind
     *out = nullptr;
     fastgl_status st = check_block(indptr, indices, num_dst, num_src, num_edges);
     if (st != FASTGL_OK) return st;
-    if (parts != FASTGL_PLAN_FWD && parts != FASTGL_PLAN_BWD && parts != FASTGL_PLAN_ALL) {
-        set_error("parts must be a mask of FASTGL_PLAN_FWD / FASTGL_PLAN_BWD (got %d)", parts);
+    if (parts != FASTGL_PLAN_FWD && parts != FASTGL_PLAN_BWD && parts != FASTGL_PLAN_ALL &&
+        parts != (FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG)) {
+        set_error("parts must be FWD, FWD|SRC_DEG, BWD or ALL (got %d)", parts);
         return FASTGL_ERR_INVALID_ARG;
     }
     if (!plan_mem || ((uintptr_t)plan_mem & 255)) {
@@ -227,7 +228,8 @@ fastgl_status fastgl_block_plan_create(const int32_t *indptr, const int32_t *ind
     p->indptr = indptr; p->indices = indices;
     plan_layout(p, plan_mem, num_dst, num_src, num_edges);
     // a backward plan also carries what the forward pass of the same block needs
-    st = plan_build(p, parts == FASTGL_PLAN_BWD ? FASTGL_PLAN_ALL : parts, false, (hipStream_t)stream);
+    st = plan_build(p, (parts & FASTGL_PLAN_BWD) ? FASTGL_PLAN_ALL : FASTGL_PLAN_FWD,
+                    (parts & FASTGL_PLAN_SRC_DEG) != 0, (hipStream_t)stream);
     if (st != FASTGL_OK) {
         delete p;
         return st;
@@ -243,16 +245,17 @@ fastgl_status fastgl_block_plan_export(const fastgl_plan *p, fastgl_plan_view *v
         return FASTGL_ERR_INVALID_ARG;
     }
     const bool f = p->parts & FASTGL_PLAN_FWD, b = p->parts & FASTGL_PLAN_BWD;
+    const bool sd = b || (p->parts & FASTGL_PLAN_SRC_DEG);
     v->din = f ? p->din : nullptr;
     v->dst_inv = f ? p->dst_inv : nullptr;
     v->dst_rsqrt = f ? p->dst_rsqrt : nullptr;
     v->long_dst = f ? p->long_dst : nullptr;
     v->chunk_ptr_dst = f ? p->chunk_ptr_dst : nullptr;
-    v->dout = b ? p->dout : nullptr;
+    v->dout = sd ? p->dout : nullptr;
     v->indptr_T = b ? p->indptr_T : nullptr;
     v->indices_T = b ? p->indices_T : nullptr;
     v->perm = b ? p->perm : nullptr;
-    v->src_rsqrt = b ? p->src_rsqrt : nullptr;
+    v->src_rsqrt = sd ? p->src_rsqrt : nullptr;
     v->long_src = b ? p->long_src : nullptr;
     v->chunk_ptr_src = b ? p->chunk_ptr_src : nullptr;
     v->counters = p->counters;

@@ -535,6 +535,7 @@ fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipSt
     fastgl_status st = bucket_rows(dstA, s);
     if (st != FASTGL_OK) return st;
     if (need_src_degrees) {
+        p->parts |= FASTGL_PLAN_SRC_DEG;
         hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout, p->num_src, 0);
         FASTGL_LAUNCH_CHECK("k_fill_i32");
         hipLaunchKernelGGL(k_hist, dim3(grid_for(p->num_edges, 4)), dim3(kBlock), 0, s, p->indices,
