@@ -1,9 +1,9 @@
 """Benchmark of the block-aggregation hot path on one MI355X.
 
 One "step" = one pass of the whole hot path over one sampled mini-batch of the
-products-shaped 3-layer GCN workload: for every layer, build the block's
-bookkeeping (plan) and run the forward aggregation; then run the backward
-aggregation of every layer in reverse order.  All inputs are synthetic, seeded
+products-shaped 3-layer GCN workload: build the bookkeeping (plans) of the
+mini-batch's blocks, run the forward aggregation of every layer, then the
+backward aggregation of every layer in reverse order.  All inputs are synthetic, seeded
 and already resident in HBM when the timed region starts.
 
 Prints ONE JSON line:
@@ -108,18 +108,11 @@ def main() -> int:
     total_edges = w.total_edges()
     bytes_step = sum(L["bytes_fwd"] + L["bytes_bwd"] for L in layers) + gather_bytes
 
-    gcn = w.mode == "gcn"
-    for L in layers:
-        L["plan_mem_f"] = torch.empty_like(L["plan_mem"])
-
-    def make_plan(L):
-        """Full bookkeeping (transpose CSR, both bucket sides): what the backward pass needs."""
-        return B.fastgl_block_plan_create(L["indptr"], L["indices"], L["blk"].num_src, B.PLAN_ALL, L["plan_mem"])
-
-    def make_plan_f(L):
-        """What the forward pass needs: row buckets and scales (+ out-degrees for GCN)."""
-        parts = B.PLAN_FWD | (B.PLAN_SRC_DEG if gcn else 0)
-        return B.fastgl_block_plan_create(L["indptr"], L["indices"], L["blk"].num_src, parts, L["plan_mem_f"])
+    def make_plans():
+        """Bookkeeping of every block of the mini-batch (transpose CSR, degrees, scale
+        factors, degree buckets), built together: each stage is one launch for all layers."""
+        return B.fastgl_block_plan_create_many([(L["indptr"], L["indices"], L["blk"].num_src) for L in layers],
+                                               B.PLAN_ALL, [L["plan_mem"] for L in layers])
 
     def fwd(L, plan):
         B.fastgl_block_aggregate_fwd(L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, L["X"],
@@ -132,48 +125,23 @@ def main() -> int:
     # the dominant kernel: forward pull over the input-layer block
     dom = max(range(len(layers)), key=lambda i: layers[i]["bytes_fwd"])
     dom_ev = []
-    main = torch.cuda.current_stream()
-    side_b, side_f = torch.cuda.Stream(), torch.cuda.Stream()   # default priority
 
     def step(timed_dom=False):
-        """One mini-batch.  The aggregation kernels run on the main stream; the
-        bookkeeping of a fresh block is latency-bound integer work, so the transposes
-        (needed only by the backward pass) and the forward plans of the later layers
-        are built on two side streams underneath the forward aggregations."""
-        start = torch.cuda.Event()
-        start.record(main)
-        side_b.wait_event(start)
-        side_f.wait_event(start)
-        plans_b, ev_b = [None] * len(layers), [None] * len(layers)
-        with torch.cuda.stream(side_b):
-            for i in reversed(range(len(layers))):      # the backward pass starts at the last layer
-                plans_b[i] = make_plan(layers[i])
-                ev_b[i] = torch.cuda.Event()
-                ev_b[i].record(side_b)
-        plans_f, ev_f = [None] * len(layers), [None] * len(layers)
-        with torch.cuda.stream(side_f):
-            for i in range(1, len(layers)):
-                plans_f[i] = make_plan_f(layers[i])
-                ev_f[i] = torch.cuda.Event()
-                ev_f[i].record(side_f)
         if table is not None:
             B.fastgl_gather_rows(table, gid, out=layers[0]["X"])
-        plans_f[0] = make_plan_f(layers[0])
+        plans = make_plans()
         for i, L in enumerate(layers):
-            if i:
-                main.wait_event(ev_f[i])
             if timed_dom and i == dom:
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record()
-                fwd(L, plans_f[i])
+                fwd(L, plans[i])
                 e1.record()
                 dom_ev.append((e0, e1))
             else:
-                fwd(L, plans_f[i])
-        for i in reversed(range(len(layers))):
-            main.wait_event(ev_b[i])
-            bwd(layers[i], plans_b[i])
-        return plans_b
+                fwd(L, plans[i])
+        for L, p in zip(reversed(layers), reversed(plans)):
+            bwd(L, p)
+        return plans
 
     for _ in range(args.warmup):
         step()
@@ -199,9 +167,8 @@ def main() -> int:
         return e0.elapsed_time(e1) / reps
 
     reps = max(5, args.steps // 2)
-    plans = [make_plan(L) for L in layers]
-    plan_ms = timed(lambda: [make_plan(L) for L in layers], reps)
-    plan_f_ms = timed(lambda: [make_plan_f(L) for L in layers], reps)
+    plans = make_plans()
+    plan_ms = timed(make_plans, reps)
     fwd_ms = timed(lambda: [fwd(L, p) for L, p in zip(layers, plans)], reps)
     bwd_ms = timed(lambda: [bwd(L, p) for L, p in zip(reversed(layers), reversed(plans))], reps)
     per_layer = []
@@ -234,11 +201,11 @@ def main() -> int:
         "config": {"workload": w.name, "config_id": args.config, "seed": w.seed,
                    "fanout_order": args.fanout_order, "mode": w.mode, "widths": w.widths,
                    "total_edges": total_edges, "accumulate": "f64" if w.dtype == "f32" else "f32",
-                   "step": "per layer: forward plan + forward; full plans (transposes) built on side streams under the forward passes; then backward per layer (reverse)"},
+                   "step": "plans of all layers (one batched call); forward per layer; backward per layer (reverse)"},
         "hbm_gbps_compulsory": round(bytes_step / (ms_step * 1e-3) / 1e9, 1),
         "hbm_frac_of_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "compulsory_bytes_per_step": int(bytes_step),
-        "breakdown_ms": {"plan_full_serial": round(plan_ms, 4), "plan_fwd_serial": round(plan_f_ms, 4), "fwd": round(fwd_ms, 4), "bwd": round(bwd_ms, 4),
+        "breakdown_ms": {"plan": round(plan_ms, 4), "fwd": round(fwd_ms, 4), "bwd": round(bwd_ms, 4),
                          "cached_plan_step": round(fwd_ms + bwd_ms, 4)},
         "value_cached_plan": round(2.0 * total_edges / ((fwd_ms + bwd_ms) * 1e-3) / 1e9, 4),
         "hbm_frac_cached_plan": round(bytes_step / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),

@@ -139,6 +139,27 @@ fastgl_status fastgl_block_plan_create(
     int64_t num_dst, int64_t num_src, int64_t num_edges, int parts,
     void *plan_mem, size_t plan_bytes, void *stream, fastgl_plan **out);
 
+/* One block of a mini-batch, for fastgl_block_plan_create_many (host struct;
+ * the pointers inside are device pointers, as in fastgl_block_plan_create). */
+typedef struct {
+    const int32_t *indptr, *indices;
+    int64_t num_dst, num_src, num_edges;
+    int parts;
+    void *plan_mem;
+    size_t plan_bytes;
+} fastgl_block_desc;
+
+#define FASTGL_MAX_PLAN_BATCH 16
+
+/* Build the plans of all blocks of a mini-batch (the layers of a sampled GNN,
+ * paper Section 2.2) together: the same work as n calls of
+ * fastgl_block_plan_create, but each stage of the bookkeeping is one launch for
+ * all blocks, which matters because the stages are latency-bound.
+ * blocks: host array of n <= FASTGL_MAX_PLAN_BATCH descriptors; out: host array
+ * of n handles.  On any error no plan is created and every out[i] is NULL. */
+fastgl_status fastgl_block_plan_create_many(int n, const fastgl_block_desc *blocks, void *stream,
+                                            fastgl_plan **out);
+
 /* Fill *view (host struct) with the plan's device pointers. */
 fastgl_status fastgl_block_plan_export(const fastgl_plan *plan, fastgl_plan_view *view);
 

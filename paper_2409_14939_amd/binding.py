@@ -22,7 +22,7 @@ PLAN_FWD, PLAN_BWD, PLAN_ALL, PLAN_SRC_DEG = 1, 2, 3, 4
 
 EXPORTS = [
     "fastgl_block_aggregate_fwd", "fastgl_block_aggregate_bwd", "fastgl_block_plan_bytes",
-    "fastgl_block_plan_create", "fastgl_block_plan_export", "fastgl_block_plan_destroy",
+    "fastgl_block_plan_create", "fastgl_block_plan_create_many", "fastgl_block_plan_export", "fastgl_block_plan_destroy",
     "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk",
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
 ]
@@ -32,6 +32,12 @@ class FastglError(RuntimeError):
     def __init__(self, status: int, msg: str):
         super().__init__(f"fastgl status {status}: {msg}")
         self.status = status
+
+
+class BlockDesc(ctypes.Structure):
+    _fields_ = [("indptr", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("num_dst", ctypes.c_int64),
+                ("num_src", ctypes.c_int64), ("num_edges", ctypes.c_int64), ("parts", ctypes.c_int),
+                ("plan_mem", ctypes.c_void_p), ("plan_bytes", ctypes.c_size_t)]
 
 
 class PlanView(ctypes.Structure):
@@ -56,6 +62,7 @@ def lib() -> ctypes.CDLL:
         L.fastgl_block_plan_bytes.argtypes = [i64, i64, i64]
         L.fastgl_block_plan_bytes.restype = sz
         L.fastgl_block_plan_create.argtypes = [p, p, i64, i64, i64, i32, p, sz, p, ctypes.POINTER(p)]
+        L.fastgl_block_plan_create_many.argtypes = [i32, ctypes.POINTER(BlockDesc), p, ctypes.POINTER(p)]
         L.fastgl_block_plan_export.argtypes = [p, ctypes.POINTER(PlanView)]
         L.fastgl_block_plan_destroy.argtypes = [p]
         L.fastgl_block_plan_destroy.restype = None
@@ -150,6 +157,25 @@ def fastgl_block_plan_create(indptr: torch.Tensor, indices: torch.Tensor, num_sr
     _check(lib().fastgl_block_plan_create(_ptr(indptr), _ptr(indices), num_dst, num_src, num_edges, parts,
                                           _ptr(plan_mem), plan_mem.numel(), _stream(), ctypes.byref(out)))
     return Plan(out, plan_mem, indptr, indices, num_src)
+
+
+def fastgl_block_plan_create_many(blocks, parts: int = PLAN_ALL, plan_mems=None):
+    """blocks: list of (indptr, indices, num_src); returns one Plan per block, built together."""
+    n = len(blocks)
+    descs = (BlockDesc * n)()
+    mems = []
+    for i, (indptr, indices, num_src) in enumerate(blocks):
+        _dev(indptr, torch.int32, "indptr")
+        _dev(indices, torch.int32, "indices")
+        num_dst, num_edges = indptr.numel() - 1, indices.numel()
+        mem = plan_mems[i] if plan_mems is not None else torch.empty(
+            fastgl_block_plan_bytes(num_dst, num_src, num_edges), dtype=torch.uint8, device=indptr.device)
+        mems.append(mem)
+        descs[i] = BlockDesc(indptr.data_ptr(), indices.data_ptr(), num_dst, num_src, num_edges, parts,
+                             mem.data_ptr(), mem.numel())
+    out = (ctypes.c_void_p * n)()
+    _check(lib().fastgl_block_plan_create_many(n, descs, _stream(), out))
+    return [Plan(ctypes.c_void_p(out[i]), mems[i], blocks[i][0], blocks[i][1], blocks[i][2]) for i in range(n)]
 
 
 def _aggregate(fn, indptr, indices, edge_w, num_src, mode, inp, out, plan, workspace):

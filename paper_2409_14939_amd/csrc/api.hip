@@ -194,6 +194,63 @@ size_t fastgl_block_plan_bytes(int64_t num_dst, int64_t num_src, int64_t num_edg
     return plan_layout(nullptr, nullptr, num_dst, num_src, num_edges);
 }
 
+fastgl_status fastgl_block_plan_create_many(int n, const fastgl_block_desc *blocks, void *stream,
+                                            fastgl_plan **out)
+{
+    if (n < 0 || n > FASTGL_MAX_PLAN_BATCH || (n > 0 && (!blocks || !out))) {
+        set_error("n must be in [0, %d] and blocks / out must not be NULL", FASTGL_MAX_PLAN_BATCH);
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    for (int i = 0; i < n; ++i) out[i] = nullptr;
+    for (int i = 0; i < n; ++i) {
+        const fastgl_block_desc &d = blocks[i];
+        fastgl_status st = check_block(d.indptr, d.indices, d.num_dst, d.num_src, d.num_edges);
+        if (st != FASTGL_OK) return st;
+        if (d.parts != FASTGL_PLAN_FWD && d.parts != FASTGL_PLAN_BWD && d.parts != FASTGL_PLAN_ALL &&
+            d.parts != (FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG)) {
+            set_error("block %d: parts must be FWD, FWD|SRC_DEG, BWD or ALL (got %d)", i, d.parts);
+            return FASTGL_ERR_INVALID_ARG;
+        }
+        if (!d.plan_mem || ((uintptr_t)d.plan_mem & 255)) {
+            set_error("block %d: plan_mem must be a 256-byte aligned device buffer", i);
+            return FASTGL_ERR_INVALID_ARG;
+        }
+        const size_t need = plan_layout(nullptr, nullptr, d.num_dst, d.num_src, d.num_edges);
+        if (d.plan_bytes < need) {
+            set_error("block %d: plan buffer too small: %zu < %zu bytes", i, d.plan_bytes, need);
+            return FASTGL_ERR_WORKSPACE;
+        }
+    }
+    fastgl_plan *plans[FASTGL_MAX_PLAN_BATCH];
+    int parts[FASTGL_MAX_PLAN_BATCH];
+    bool src_deg[FASTGL_MAX_PLAN_BATCH];
+    fastgl_status st = FASTGL_OK;
+    int made = 0;
+    for (; made < n; ++made) {
+        const fastgl_block_desc &d = blocks[made];
+        fastgl_plan *p = new (std::nothrow) fastgl_plan;
+        if (!p) {
+            set_error("out of host memory");
+            st = FASTGL_ERR_INVALID_ARG;
+            break;
+        }
+        p->num_dst = d.num_dst; p->num_src = d.num_src; p->num_edges = d.num_edges;
+        p->indptr = d.indptr; p->indices = d.indices;
+        plan_layout(p, d.plan_mem, d.num_dst, d.num_src, d.num_edges);
+        plans[made] = p;
+        // a backward plan also carries what the forward pass of the same block needs
+        parts[made] = (d.parts & FASTGL_PLAN_BWD) ? FASTGL_PLAN_ALL : FASTGL_PLAN_FWD;
+        src_deg[made] = (d.parts & FASTGL_PLAN_SRC_DEG) != 0;
+    }
+    if (st == FASTGL_OK) st = plans_build(plans, parts, src_deg, n, (hipStream_t)stream);
+    if (st != FASTGL_OK) {
+        for (int i = 0; i < made; ++i) delete plans[i];
+        return st;
+    }
+    for (int i = 0; i < n; ++i) out[i] = plans[i];
+    return FASTGL_OK;
+}
+
 fastgl_status fastgl_block_plan_create(const int32_t *indptr, const int32_t *indices, int64_t num_dst,
                                        int64_t num_src, int64_t num_edges, int parts, void *plan_mem,
                                        size_t plan_bytes, void *stream, fastgl_plan **out)
@@ -202,40 +259,11 @@ fastgl_status fastgl_block_plan_create(const int32_t *indptr, const int32_t *ind
         set_error("out is NULL");
         return FASTGL_ERR_INVALID_ARG;
     }
-    *out = nullptr;
-    fastgl_status st = check_block(indptr, indices, num_dst, num_src, num_edges);
-    if (st != FASTGL_OK) return st;
-    if (parts != FASTGL_PLAN_FWD && parts != FASTGL_PLAN_BWD && parts != FASTGL_PLAN_ALL &&
-        parts != (FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG)) {
-        set_error("parts must be FWD, FWD|SRC_DEG, BWD or ALL (got %d)", parts);
-        return FASTGL_ERR_INVALID_ARG;
-    }
-    if (!plan_mem || ((uintptr_t)plan_mem & 255)) {
-        set_error("plan_mem must be a 256-byte aligned device buffer");
-        return FASTGL_ERR_INVALID_ARG;
-    }
-    const size_t need = plan_layout(nullptr, nullptr, num_dst, num_src, num_edges);
-    if (plan_bytes < need) {
-        set_error("plan buffer too small: %zu < %zu bytes", plan_bytes, need);
-        return FASTGL_ERR_WORKSPACE;
-    }
-    fastgl_plan *p = new (std::nothrow) fastgl_plan;
-    if (!p) {
-        set_error("out of host memory");
-        return FASTGL_ERR_INVALID_ARG;
-    }
-    p->num_dst = num_dst; p->num_src = num_src; p->num_edges = num_edges;
-    p->indptr = indptr; p->indices = indices;
-    plan_layout(p, plan_mem, num_dst, num_src, num_edges);
-    // a backward plan also carries what the forward pass of the same block needs
-    st = plan_build(p, (parts & FASTGL_PLAN_BWD) ? FASTGL_PLAN_ALL : FASTGL_PLAN_FWD,
-                    (parts & FASTGL_PLAN_SRC_DEG) != 0, (hipStream_t)stream);
-    if (st != FASTGL_OK) {
-        delete p;
-        return st;
-    }
-    *out = p;
-    return FASTGL_OK;
+    fastgl_block_desc d;
+    d.indptr = indptr; d.indices = indices;
+    d.num_dst = num_dst; d.num_src = num_src; d.num_edges = num_edges;
+    d.parts = parts; d.plan_mem = plan_mem; d.plan_bytes = plan_bytes;
+    return fastgl_block_plan_create_many(1, &d, stream, out);
 }
 
 fastgl_status fastgl_block_plan_export(const fastgl_plan *p, fastgl_plan_view *v)

@@ -8,14 +8,20 @@
 // the reversed edges; pulling along a transposed CSR keeps one writer per
 // output row, as the forward pass has (Section 4.2: a target's aggregation is
 // completed by one owner).  Every sampled block is new, so this work is part of
-// each iteration and is kept to a handful of launches:
+// each iteration and is kept to a handful of launches.  The work of a plan is a
+// sequence of STAGES; stage k of every plan built in one call shares one launch
+// of k_plan_stage, whose workgroups look up which job they belong to:
 //
-//   per radix pass (8-bit digit)   k_sort_hist, k_sort_scatter
-//   after the last pass            k_row_starts   (indptr_T from the sorted keys)
-//   degree buckets, per side       k_rows_count, k_rows_fill
+//   stage 0        digit histogram of pass 0    + destination-side row count
+//   stage 1        stable scatter of pass 0     + destination-side bucket fill
+//   stage 2p,2p+1  histogram / scatter of radix pass p (8-bit digits)
+//   then           row starts (indptr_T from the sorted keys),
+//                  source-side row count, source-side bucket fill
 //
-// The destination-side bucket kernels ride along in the first pass's two
-// launches as extra workgroups, so a full plan with a 3-pass sort is 9 launches.
+// A full plan with a 3-pass sort is 9 launches, and so are the plans of all
+// layers of a mini-batch when they are built together.
+#include <vector>
+
 #include "internal.h"
 
 namespace fastgl {
@@ -158,18 +164,6 @@ __device__ __forceinline__ void rows_fill(const RowsArgs &A, int b, int *lds)
     }
 }
 
-__global__ __launch_bounds__(kSortThreads) void k_rows_count(RowsArgs A)
-{
-    __shared__ int lds[16];
-    rows_count(A, blockIdx.x, lds);
-}
-
-__global__ __launch_bounds__(kSortThreads) void k_rows_fill(RowsArgs A)
-{
-    __shared__ int lds[16];
-    rows_fill(A, blockIdx.x, lds);
-}
-
 // ------------------------------------------------------------ radix sort ----
 struct SortArgs {
     const int32_t *keys_in, *vals_in;   // vals_in == NULL: the identity (first pass)
@@ -178,26 +172,20 @@ struct SortArgs {
     int nb, shift;
     int32_t *cnt;                       // [nb][256] digit counts per block
     const int32_t *edge_dst;            // [n] destination row of every edge (read by the last pass)
-    int32_t *dst_out;                   // last pass: [n] destination row in sorted order
+    int32_t *dst_out;                   // last pass: [n] destination row in sorted order, else NULL
+    int items;                          // keys per thread and step: 1, 2 or 4
 };
 
-// Digit histogram of the block's key range.  Workgroups beyond S.nb run the
-// destination-side row count (first pass only).
-__global__ __launch_bounds__(kSortThreads) void k_sort_hist(SortArgs S, RowsArgs R)
+// Digit histogram of the block's key range.
+__device__ __forceinline__ void sort_hist(const SortArgs &S, int b, int *h)
 {
-    __shared__ int h[kRadixBins];
-    __shared__ int lds[16];
-    if ((int)blockIdx.x >= S.nb) {
-        rows_count(R, blockIdx.x - S.nb, lds);
-        return;
-    }
     if (threadIdx.x < kRadixBins) h[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t beg = blockIdx.x * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
+    const int64_t beg = b * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
     for (int64_t i = beg + threadIdx.x; i < end; i += kSortThreads)
         atomicAdd(&h[(S.keys_in[i] >> S.shift) & (kRadixBins - 1)], 1);
     __syncthreads();
-    if (threadIdx.x < kRadixBins) S.cnt[(int64_t)blockIdx.x * kRadixBins + threadIdx.x] = h[threadIdx.x];
+    if (threadIdx.x < kRadixBins) S.cnt[(int64_t)b * kRadixBins + threadIdx.x] = h[threadIdx.x];
 }
 
 // Stable scatter of one digit.  Every workgroup derives its own output offsets
@@ -208,21 +196,21 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(SortArgs S, RowsArgs
 // running per-wavefront digit counts live in LDS, and a column scan over the 16
 // wavefronts plus a scan over the digits give each key its place in the step's
 // sorted order.  The step is sorted into LDS first and written out from there.
-// LAST: write sorted keys, the permutation, and the destination row of each edge.
-// Workgroups beyond S.nb run the destination-side row fill (first pass only).
-template <bool LAST, int ITEMS>
-__global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsArgs R, int rows_role)
+// The last pass (dst_out set) also writes the destination row of each edge.
+struct SortShared {
+    int running[kRadixBins], lbase[kRadixBins], gdelta[kRadixBins];
+    int wcnt[kSortWaves][kRadixBins];
+    int32_t skey[kSortThreads * kMaxSortItems], sval[kSortThreads * kMaxSortItems];
+};
+
+template <int ITEMS>
+__device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShared &M, int *lds)
 {
-    __shared__ int running[kRadixBins], lbase[kRadixBins], gdelta[kRadixBins];
-    __shared__ int wcnt[kSortWaves][kRadixBins];
-    __shared__ int32_t skey[kSortThreads * ITEMS], sval[kSortThreads * ITEMS];
-    __shared__ int lds[16];
+    int (&running)[kRadixBins] = M.running, (&lbase)[kRadixBins] = M.lbase, (&gdelta)[kRadixBins] = M.gdelta;
+    int (&wcnt)[kSortWaves][kRadixBins] = M.wcnt;
+    int32_t *skey = M.skey, *sval = M.sval;
+    const bool LAST = S.dst_out != nullptr;
     const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
-    if ((int)blockIdx.x >= S.nb) {
-        if (rows_role) rows_fill(R, blockIdx.x - S.nb, lds);
-        return;
-    }
-    const int b = blockIdx.x;
     {   // offsets of this block's digits
         const int d = t & (kRadixBins - 1), part = t / kRadixBins;   // 4 parts share the blocks
         int below = 0, total = 0;
@@ -335,28 +323,75 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(SortArgs S, RowsA
 // indptr_T from the sorted source ids: position k starts every source id in
 // (key[k-1], key[k]].  k == n closes the tail.  Gaps (sources without edges) are
 // short in practice; a long one is filled by the whole wavefront together.
-__global__ __launch_bounds__(kBlock) void k_row_starts(const int32_t *__restrict__ keys, int64_t n,
-                                                       int64_t num_src, int32_t *__restrict__ indptr_T)
+struct StartsArgs {
+    const int32_t *keys;     // [n] sorted source ids
+    int64_t n, num_src;
+    int32_t *indptr_T;       // [num_src+1]
+    int nb;
+};
+
+__device__ __forceinline__ void row_starts(const StartsArgs &A, int b)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    for (int64_t base = (int64_t)blockIdx.x * kBlock; base <= n; base += (int64_t)gridDim.x * kBlock) {
+    const int64_t n = A.n;
+    for (int64_t base = (int64_t)b * blockDim.x; base <= n; base += (int64_t)A.nb * blockDim.x) {
         const int64_t k = base + threadIdx.x;
         int64_t prev = 0, cur = -1;   // empty interval by default
         if (k <= n) {
-            prev = k > 0 ? keys[k - 1] : -1;
-            cur = k < n ? keys[k] : num_src;
+            prev = k > 0 ? A.keys[k - 1] : -1;
+            cur = k < n ? A.keys[k] : A.num_src;
         }
         const bool big = cur - prev > 4;
         if (!big)
-            for (int64_t v = prev + 1; v <= cur; ++v) indptr_T[v] = (int32_t)k;
+            for (int64_t v = prev + 1; v <= cur; ++v) A.indptr_T[v] = (int32_t)k;
         unsigned long long m = __ballot(big);
         while (m) {
             const int leader = __ffsll((long long)m) - 1;
             const int64_t p = __shfl(prev, leader, kWave), c = __shfl(cur, leader, kWave);
             const int64_t kk = __shfl(k, leader, kWave);
-            for (int64_t v = p + 1 + lane; v <= c; v += kWave) indptr_T[v] = (int32_t)kk;
+            for (int64_t v = p + 1 + lane; v <= c; v += kWave) A.indptr_T[v] = (int32_t)kk;
             m &= m - 1;
         }
+    }
+}
+
+// ------------------------------------------------------- the stage kernel ----
+enum { JOB_ROWS_COUNT = 0, JOB_ROWS_FILL = 1, JOB_SORT_HIST = 2, JOB_SORT_SCATTER = 3, JOB_ROW_STARTS = 4 };
+constexpr int kMaxJobs = 16;
+
+struct Job {
+    int kind, nblocks;
+    union {
+        RowsArgs rows;
+        SortArgs sort;
+        StartsArgs starts;
+    };
+};
+
+struct StageArgs {
+    int njobs;
+    int first[kMaxJobs + 1];   // first workgroup of each job
+    Job job[kMaxJobs];
+};
+
+__global__ __launch_bounds__(kSortThreads) void k_plan_stage(StageArgs A)
+{
+    __shared__ SortShared M;
+    __shared__ int lds[16];
+    int j = 0;
+    while (j + 1 < A.njobs && (int)blockIdx.x >= A.first[j + 1]) ++j;
+    const int b = blockIdx.x - A.first[j];
+    const Job &J = A.job[j];
+    switch (J.kind) {
+        case JOB_ROWS_COUNT: rows_count(J.rows, b, lds); break;
+        case JOB_ROWS_FILL: rows_fill(J.rows, b, lds); break;
+        case JOB_SORT_HIST: sort_hist(J.sort, b, M.running); break;
+        case JOB_SORT_SCATTER:
+            if (J.sort.items == 1) sort_scatter<1>(J.sort, b, M, lds);
+            else if (J.sort.items == 2) sort_scatter<2>(J.sort, b, M, lds);
+            else sort_scatter<4>(J.sort, b, M, lds);
+            break;
+        default: row_starts(J.starts, b); break;
     }
 }
 
@@ -462,19 +497,34 @@ size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src,
     return off;
 }
 
-static fastgl_status bucket_rows(const RowsArgs &A, hipStream_t s)
+// ---- stages ----------------------------------------------------------------
+using Stages = std::vector<std::vector<Job>>;
+
+static void add_job(Stages &st, size_t k, const Job &j)
 {
-    hipLaunchKernelGGL(k_rows_count, dim3(A.nb), dim3(kSortThreads), 0, s, A);
-    FASTGL_LAUNCH_CHECK("k_rows_count");
-    hipLaunchKernelGGL(k_rows_fill, dim3(A.nb), dim3(kSortThreads), 0, s, A);
-    FASTGL_LAUNCH_CHECK("k_rows_fill");
-    return FASTGL_OK;
+    if (st.size() <= k) st.resize(k + 1);
+    st[k].push_back(j);
 }
 
-// Sort (source id, edge id) pairs, ride the destination-side bucket kernels along
-// with the first pass, then derive indptr_T and the source-side buckets.
-static fastgl_status transpose_and_buckets(fastgl_plan *p, const RowsArgs &dstA, hipStream_t s)
+static Job rows_job(int kind, const RowsArgs &A)
 {
+    Job j;
+    j.kind = kind; j.nblocks = A.nb; j.rows = A;
+    return j;
+}
+
+// Append the jobs of one plan.  Stage k of a plan only depends on its own
+// earlier stages, so plans of different depth can share launches.
+static void plan_stages(fastgl_plan *p, int parts, Stages &st)
+{
+    p->parts = parts;
+    const bool full = (parts & FASTGL_PLAN_BWD) != 0;
+    RowsArgs dstA = rows_args(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->block_sums,
+                              p->long_dst, p->chunk_ptr_dst, p->counters, full ? p->edge_dst : nullptr);
+    add_job(st, 0, rows_job(JOB_ROWS_COUNT, dstA));
+    add_job(st, 1, rows_job(JOB_ROWS_FILL, dstA));
+    if (!full) return;
+
     const int64_t n = p->num_edges;
     int bits = 1;
     while (bits < 31 && ((int64_t)1 << bits) < p->num_src) ++bits;
@@ -487,65 +537,95 @@ static fastgl_status transpose_and_buckets(fastgl_plan *p, const RowsArgs &dstA,
     const int64_t step = (int64_t)items * kSortThreads;
     int64_t per = ceil_div(ceil_div(n, (int64_t)kMaxSortBlocks), step) * step;
     if (per < step) per = step;
+    S.items = items;
     S.per = per;
     S.nb = n > 0 ? (int)ceil_div(n, per) : 1;
     S.cnt = p->radix_cnt;
     S.edge_dst = p->edge_dst;
     const int32_t *kin = p->indices, *vin = nullptr;
     for (int pass = 0; pass < npass; ++pass) {
-        const bool first = pass == 0, last = pass == npass - 1;
+        const bool last = pass == npass - 1;
         S.keys_in = kin; S.vals_in = vin; S.shift = pass * kRadixBits;
         S.keys_out = p->sort_buf[(pass & 1) * 2];
         S.vals_out = last ? p->perm : p->sort_buf[(pass & 1) * 2 + 1];
-        S.dst_out = p->indices_T;
-        const int extra = first ? dstA.nb : 0;
-        hipLaunchKernelGGL(k_sort_hist, dim3(S.nb + extra), dim3(kSortThreads), 0, s, S, dstA);
-        FASTGL_LAUNCH_CHECK("k_sort_hist");
-        const dim3 grid(S.nb + extra), blk(kSortThreads);
-        const int role = extra ? 1 : 0;
-#define FASTGL_SCATTER(IT)                                                                        \
-    if (last) hipLaunchKernelGGL((k_sort_scatter<true, IT>), grid, blk, 0, s, S, dstA, role);     \
-    else hipLaunchKernelGGL((k_sort_scatter<false, IT>), grid, blk, 0, s, S, dstA, role)
-        switch (items) {
-            case 1: FASTGL_SCATTER(1); break;
-            case 2: FASTGL_SCATTER(2); break;
-            default: FASTGL_SCATTER(4); break;
-        }
-#undef FASTGL_SCATTER
-        FASTGL_LAUNCH_CHECK("k_sort_scatter");
+        S.dst_out = last ? p->indices_T : nullptr;
+        Job j;
+        j.nblocks = S.nb; j.sort = S;
+        j.kind = JOB_SORT_HIST;
+        add_job(st, 2 * pass, j);
+        j.kind = JOB_SORT_SCATTER;
+        add_job(st, 2 * pass + 1, j);
         kin = S.keys_out;
         vin = S.vals_out;
     }
-    hipLaunchKernelGGL(k_row_starts, dim3(grid_for(n + 1, 1)), dim3(kBlock), 0, s, kin, n, p->num_src, p->indptr_T);
-    FASTGL_LAUNCH_CHECK("k_row_starts");
+    Job t;
+    t.kind = JOB_ROW_STARTS;
+    t.starts.keys = kin; t.starts.n = n; t.starts.num_src = p->num_src; t.starts.indptr_T = p->indptr_T;
+    int64_t nb = ceil_div(n + 1, (int64_t)kSortThreads);
+    if (nb > 1024) nb = 1024;
+    t.starts.nb = (int)nb; t.nblocks = (int)nb;
+    add_job(st, 2 * npass, t);
     RowsArgs srcA = rows_args(p->indptr_T, p->num_src, p->dout, nullptr, p->src_rsqrt, p->block_sums2,
                               p->long_src, p->chunk_ptr_src, p->counters + 2);
-    return bucket_rows(srcA, s);
+    add_job(st, 2 * npass + 1, rows_job(JOB_ROWS_COUNT, srcA));
+    add_job(st, 2 * npass + 2, rows_job(JOB_ROWS_FILL, srcA));
 }
 
-// Enqueue the bookkeeping kernels for the requested parts.  need_src_degrees
-// asks for dout / src_rsqrt even when only the forward part is built (GCN).
-fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipStream_t s)
+static fastgl_status run_stages(const Stages &st, hipStream_t s)
 {
-    p->parts = parts;
-    RowsArgs dstA = rows_args(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->block_sums,
-                              p->long_dst, p->chunk_ptr_dst, p->counters,
-                              (parts & FASTGL_PLAN_BWD) ? p->edge_dst : nullptr);
-    if (parts & FASTGL_PLAN_BWD) return transpose_and_buckets(p, dstA, s);   // includes the forward part
-    fastgl_status st = bucket_rows(dstA, s);
-    if (st != FASTGL_OK) return st;
-    if (need_src_degrees) {
-        p->parts |= FASTGL_PLAN_SRC_DEG;
-        hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout, p->num_src, 0);
-        FASTGL_LAUNCH_CHECK("k_fill_i32");
-        hipLaunchKernelGGL(k_hist, dim3(grid_for(p->num_edges, 4)), dim3(kBlock), 0, s, p->indices,
-                           p->num_edges, p->dout);
-        FASTGL_LAUNCH_CHECK("k_hist");
-        hipLaunchKernelGGL(k_rsqrt_deg, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout, p->num_src,
-                           p->src_rsqrt);
-        FASTGL_LAUNCH_CHECK("k_rsqrt_deg");
+    for (const auto &jobs : st) {
+        for (size_t at = 0; at < jobs.size(); at += kMaxJobs) {
+            StageArgs A;
+            A.njobs = (int)(jobs.size() - at < (size_t)kMaxJobs ? jobs.size() - at : kMaxJobs);
+            int blocks = 0;
+            for (int i = 0; i < A.njobs; ++i) {
+                A.first[i] = blocks;
+                A.job[i] = jobs[at + i];
+                blocks += A.job[i].nblocks;
+            }
+            A.first[A.njobs] = blocks;
+            hipLaunchKernelGGL(k_plan_stage, dim3(blocks), dim3(kSortThreads), 0, s, A);
+            FASTGL_LAUNCH_CHECK("k_plan_stage");
+        }
     }
     return FASTGL_OK;
+}
+
+// Out-degrees by histogram for a forward-only plan of a GCN-normalised pass.
+static fastgl_status src_degrees(fastgl_plan *p, hipStream_t s)
+{
+    p->parts |= FASTGL_PLAN_SRC_DEG;
+    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout, p->num_src, 0);
+    FASTGL_LAUNCH_CHECK("k_fill_i32");
+    hipLaunchKernelGGL(k_hist, dim3(grid_for(p->num_edges, 4)), dim3(kBlock), 0, s, p->indices, p->num_edges,
+                       p->dout);
+    FASTGL_LAUNCH_CHECK("k_hist");
+    hipLaunchKernelGGL(k_rsqrt_deg, dim3(grid_for(p->num_src, 4)), dim3(kBlock), 0, s, p->dout, p->num_src,
+                       p->src_rsqrt);
+    FASTGL_LAUNCH_CHECK("k_rsqrt_deg");
+    return FASTGL_OK;
+}
+
+// Enqueue the bookkeeping of n plans; stage k of all of them shares a launch.
+// parts[i]: FASTGL_PLAN_FWD or FASTGL_PLAN_ALL; src_deg[i] asks a forward-only
+// plan for dout / src_rsqrt as well (GCN).
+fastgl_status plans_build(fastgl_plan *const *plans, const int *parts, const bool *src_deg, int n, hipStream_t s)
+{
+    Stages st;
+    for (int i = 0; i < n; ++i) plan_stages(plans[i], parts[i], st);
+    fastgl_status rc = run_stages(st, s);
+    if (rc != FASTGL_OK) return rc;
+    for (int i = 0; i < n; ++i)
+        if (src_deg[i] && !(parts[i] & FASTGL_PLAN_BWD)) {
+            rc = src_degrees(plans[i], s);
+            if (rc != FASTGL_OK) return rc;
+        }
+    return FASTGL_OK;
+}
+
+fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipStream_t s)
+{
+    return plans_build(&p, &parts, &need_src_degrees, 1, s);
 }
 
 fastgl_status validate_block(const int32_t *indptr, const int32_t *indices, int64_t num_dst,

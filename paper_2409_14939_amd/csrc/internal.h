@@ -62,6 +62,7 @@ namespace fastgl {
 
 size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges);
 fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipStream_t s);
+fastgl_status plans_build(fastgl_plan *const *plans, const int *parts, const bool *src_deg, int n, hipStream_t s);
 
 struct PullDesc {
     const int32_t *rowptr;     // [num_rows+1]

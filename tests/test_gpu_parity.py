@@ -130,6 +130,40 @@ def test_bookkeeping_bit_exact_small():
     check_bookkeeping(big, "sparse-id-space")
 
 
+def test_batched_plans_match_single_plans():
+    """Plans built together (one launch per stage for all blocks) equal plans built alone."""
+    rng = np.random.default_rng(41)
+    blocks = [ragged_block(), bg.random_block(rng, 40, 200, 3.0), bg.make_config(1).blocks[0],
+              bg.random_block(rng, 300, 70000, 40.0, hub_rows=2, hub_deg=9000),
+              bg.random_block(rng, 9, 17, 0.0, empty_frac=1.0)]
+    dev = [(dev_i32(b.indptr), dev_i32(b.indices), b.num_src) for b in blocks]
+    plans = B.fastgl_block_plan_create_many(dev)
+    for blk, plan in zip(blocks, plans):
+        v = plan.export()
+        pT, iT, perm = oracle.transpose(blk.indptr, blk.indices, blk.num_src)
+        din, dout = oracle.degrees(blk.indptr, blk.indices, blk.num_src)
+        assert np.array_equal(read_i32(plan, v.indptr_T, blk.num_src + 1), pT)
+        assert np.array_equal(read_i32(plan, v.perm, blk.num_edges), perm)
+        assert np.array_equal(read_i32(plan, v.indices_T, blk.num_edges), iT)
+        assert np.array_equal(read_i32(plan, v.din, blk.num_dst), din)
+        assert np.array_equal(read_i32(plan, v.dout, blk.num_src), dout)
+        rows, cptr = oracle.long_rows(pT, B.fastgl_long_row_threshold(), B.fastgl_long_row_chunk())
+        cnt = read_i32(plan, v.counters, 4)
+        assert cnt[2] == rows.shape[0] and cnt[3] == cptr[-1]
+        assert np.array_equal(read_i32(plan, v.long_src, rows.shape[0]), rows)
+    # a forward-only plan with histogram degrees serves a GCN forward pass
+    blk = blocks[0]
+    ip, ix, _ = dev[0]
+    pf = B.fastgl_block_plan_create(ip, ix, blk.num_src, B.PLAN_FWD | B.PLAN_SRC_DEG)
+    X = make_inputs(rng, blk.num_src, 48, "f32")
+    out = B.fastgl_block_aggregate_fwd(ip, ix, None, blk.num_src, "gcn", dev_feat(X, "f32"), plan=pf)
+    torch.cuda.synchronize()
+    assert_close(host_feat(out, "f32"), oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, "gcn",
+                                                             "f32", X), "f32", "forward-only plan")
+    with pytest.raises(B.FastglError):
+        B.fastgl_block_aggregate_bwd(ip, ix, None, blk.num_src, "gcn", dev_feat(make_inputs(rng, blk.num_dst, 48, "f32"), "f32"), plan=pf)
+
+
 def test_validate_counts_violations():
     blk = ragged_block()
     bad = blk.indices.copy()
