@@ -27,10 +27,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 METRIC = "aggregated GEdges/s (fwd+bwd) and achieved HBM GB/s vs peak, 1 MI355X"
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs
-# (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); the
-# summaries live under profiles/.  None until measured for the current kernel.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM-side bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs
+# of this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
+# reads for a plain 1 GiB copy (`--calibrate`): FETCH_SIZE counts 2 KiB units,
+# WRITE_SIZE 1 KiB units on this stack.  Summary: profiles/pull_rows_config2_traffic.md.
+# Key: (config, direction, layer).  Re-measure when the kernel's access pattern changes.
+MEASURED_TRAFFIC_BYTES = {(2, "fwd", 0): int(652526.1 * 2048 + 215011.3 * 1024)}
 
 
 def compulsory_bytes(rowptr_rows, nnz, used_in_rows, out_rows, feat, elem):
@@ -48,6 +50,8 @@ def main() -> int:
     ap.add_argument("--fanout-order", default="A", choices=["A", "B"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
@@ -65,6 +69,15 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+
+    if args.calibrate:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)                                             # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate": "4 device copies of 1 GiB (1073741824 bytes read and written each)"}))
+        return 0
 
     t0 = time.time()
     w = bg.make_config(args.config, fanout_order=args.fanout_order, width=args.width)
@@ -219,30 +232,31 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         import oracle
-        # bounded sample: the same workload, the layers in order until ~20 s of CPU work
-        budget, spent, edges_done, reps_done = 20.0, 0.0, 0, 0
-        sample = []
-        for i, L in enumerate(layers):
-            blk = L["blk"]
+        # bounded sample: whole passes over the same workload, layer by layer, repeated
+        # until about 12 s of CPU work (at least one full pass over every layer)
+        budget, spent, edges_done, passes = 12.0, 0.0, 0, 0
+        host = []
+        for L in layers:
             if w.dtype == "f32":
-                Xh, Gh = L["X"].cpu().numpy(), L["G"].cpu().numpy()
+                host.append((L["X"].cpu().numpy(), L["G"].cpu().numpy()))
             else:
-                Xh = L["X"].view(torch.int16).cpu().numpy().view(np.uint16)
-                Gh = L["G"].view(torch.int16).cpu().numpy().view(np.uint16)
-            t0 = time.perf_counter()
-            oracle.par_aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Xh)
-            oracle.par_aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Gh)
-            dt = time.perf_counter() - t0
-            spent += dt
-            edges_done += 2 * blk.num_edges
-            sample.append(i)
-            if spent > budget:
-                break
+                host.append((L["X"].view(torch.int16).cpu().numpy().view(np.uint16),
+                             L["G"].view(torch.int16).cpu().numpy().view(np.uint16)))
+        while spent < budget:
+            for L, (Xh, Gh) in zip(layers, host):
+                blk = L["blk"]
+                t0 = time.perf_counter()
+                oracle.par_aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Xh)
+                oracle.par_aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Gh)
+                spent += time.perf_counter() - t0
+                edges_done += 2 * blk.num_edges
+            passes += 1
+        sample = f"{passes} full fwd+bwd passes over all {len(layers)} layers"
         result["cpu_baseline"] = {
             "value": round(edges_done / spent / 1e9, 5), "unit": "GEdges/s",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"parallel oracle variant (fp32 accumulate, OpenMP rows), fwd+bwd once over layers "
-                      f"{sample} of the same workload ({edges_done // 2} edges), {spent:.2f} s",
+            "sample": f"parallel oracle variant (fp32 accumulate, OpenMP over rows, backward through its own "
+                      f"transpose): {sample} of the same workload, {spent:.1f} s of CPU time",
         }
     if args.verbose:
         print(json.dumps(result, indent=1), file=sys.stderr)
