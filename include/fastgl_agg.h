@@ -91,6 +91,9 @@ typedef struct {
     const int32_t *long_src;     /* same for transpose rows                                   */
     const int32_t *chunk_ptr_src;
     const int32_t *counters;     /* [4] n_long_dst, n_chunks_dst, n_long_src, n_chunks_src    */
+    const int32_t *split_dst;    /* [S+1], S = ceil((num_dst+E)/fastgl_work_per_group()): first row of
+                                    every equal-work row set: min r with indptr[r] + r >= g * work  */
+    const int32_t *split_src;    /* same over the transpose rows                              */
 } fastgl_plan_view;
 
 /* Forward aggregation of one block (Eq. 1).
@@ -175,6 +178,11 @@ size_t fastgl_block_workspace_bytes(int64_t num_dst, int64_t num_src, int64_t nu
  * fastgl_long_row_chunk() edges whose partial sums are reduced in a fixed order. */
 int32_t fastgl_long_row_threshold(void);
 int32_t fastgl_long_row_chunk(void);
+
+/* The plan cuts the rows into consecutive sets of this much work (edges + rows)
+ * each; a lane group of the aggregation kernels takes 1-8 consecutive sets, so no
+ * group is overloaded however skewed the degrees are. */
+int32_t fastgl_work_per_group(void);
 
 /* Row gather from a device-resident feature table, the device-side tail of the
  * memory-IO phase (Section 2.2): out[i,:] = table[ids[i],:], ids int64[n] in

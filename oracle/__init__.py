@@ -52,6 +52,8 @@ def lib():
         L.fastgl_oracle_transpose.restype = i32
         L.fastgl_oracle_long_rows.argtypes = [p, i64, ctypes.c_int32, ctypes.c_int32, p, p]
         L.fastgl_oracle_long_rows.restype = i64
+        L.fastgl_oracle_work_split.argtypes = [p, i64, ctypes.c_int32, p]
+        L.fastgl_oracle_work_split.restype = i64
         L.fastgl_oracle_gather_rows.argtypes = [p, p, i64, i64, i32, p]
         L.fastgl_oracle_gather_rows.restype = i32
         L.fastgl_oracle_double_to_bf16.argtypes = [ctypes.c_double]
@@ -146,6 +148,14 @@ def long_rows(rowptr, threshold, chunk):
     cptr = np.empty(n + 2, np.int32)
     k = lib().fastgl_oracle_long_rows(_ptr(rowptr), n, threshold, chunk, _ptr(rows), _ptr(cptr))
     return rows[:k].copy(), cptr[:k + 1].copy()
+
+
+def work_split(rowptr, work):
+    rowptr = _i32(rowptr)
+    n = rowptr.shape[0] - 1
+    out = np.empty((int(rowptr[-1]) + n) // work + 3, np.int32)
+    g = lib().fastgl_oracle_work_split(_ptr(rowptr), n, work, _ptr(out))
+    return out[:g + 1].copy()
 
 
 def gather_rows(table, ids, dtype):

@@ -158,6 +158,21 @@ int64_t fastgl_oracle_long_rows(const int32_t *indptr, int64_t num_rows,
     return n;
 }
 
+/* Equal-work row sets: set g starts at the first row r with rowptr[r] + r >= g*work
+ * (a row's work = its edges + 1).  split has ngroups+1 entries, ngroups =
+ * ceil((num_rows + nnz) / work).  Returns ngroups. */
+int64_t fastgl_oracle_work_split(const int32_t *rowptr, int64_t num_rows, int32_t work, int32_t *split)
+{
+    int64_t total = (int64_t)rowptr[num_rows] + num_rows;
+    int64_t ngroups = (total + work - 1) / work;
+    int64_t r = 0;
+    for (int64_t g = 0; g <= ngroups; ++g) {
+        while (r < num_rows && (int64_t)rowptr[r] + r < g * (int64_t)work) ++r;
+        split[g] = (int32_t)r;
+    }
+    return ngroups;
+}
+
 /* ---- definitional aggregation (fp64, single thread) ------------------------ */
 static double dst_scale(int mode, int32_t din)
 {

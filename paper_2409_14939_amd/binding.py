@@ -23,7 +23,7 @@ PLAN_FWD, PLAN_BWD, PLAN_ALL, PLAN_SRC_DEG = 1, 2, 3, 4
 EXPORTS = [
     "fastgl_block_aggregate_fwd", "fastgl_block_aggregate_bwd", "fastgl_block_plan_bytes",
     "fastgl_block_plan_create", "fastgl_block_plan_create_many", "fastgl_block_plan_export", "fastgl_block_plan_destroy",
-    "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk",
+    "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk", "fastgl_work_per_group",
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
 ]
 
@@ -43,7 +43,7 @@ class BlockDesc(ctypes.Structure):
 class PlanView(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in (
         "din", "dout", "indptr_T", "indices_T", "perm", "dst_inv", "dst_rsqrt", "src_rsqrt",
-        "long_dst", "chunk_ptr_dst", "long_src", "chunk_ptr_src", "counters")]
+        "long_dst", "chunk_ptr_dst", "long_src", "chunk_ptr_src", "counters", "split_dst", "split_src")]
 
 
 _lib = None
@@ -70,6 +70,7 @@ def lib() -> ctypes.CDLL:
         L.fastgl_block_workspace_bytes.restype = sz
         L.fastgl_long_row_threshold.restype = ctypes.c_int32
         L.fastgl_long_row_chunk.restype = ctypes.c_int32
+        L.fastgl_work_per_group.restype = ctypes.c_int32
         L.fastgl_gather_rows.argtypes = [p, i64, p, i64, i64, i32, p, p]
         L.fastgl_block_validate.argtypes = [p, p, i64, i64, i64, p, ctypes.POINTER(i64), p]
         L.fastgl_last_error.restype = ctypes.c_char_p
@@ -114,6 +115,10 @@ def fastgl_long_row_threshold() -> int:
 
 def fastgl_long_row_chunk() -> int:
     return int(lib().fastgl_long_row_chunk())
+
+
+def fastgl_work_per_group() -> int:
+    return int(lib().fastgl_work_per_group())
 
 
 def fastgl_block_plan_bytes(num_dst: int, num_src: int, num_edges: int) -> int:

@@ -26,8 +26,7 @@
 
 namespace fastgl {
 
-constexpr int kUnroll = 8;
-constexpr int kRowsPerGroup = 8;
+constexpr int kUnroll = 6;
 constexpr int kXcdRun = 16;
 
 template <int DT> struct AccT { using type = double; };
@@ -107,17 +106,19 @@ struct PullParams {
     const float *edge_w, *col_scale;
     const char *in;
     char *out;
-    int64_t num_units;        // row sets * ntiles
+    const int32_t *split;     // [nsets+1] first row of every fine row set (equal work each)
+    int64_t nsets;            // fine row sets
+    int64_t ngroups;          // groups per column tile = ceil(nsets / sets_per_group)
     int32_t ntiles;           // column tiles per row
     int32_t G;                // lanes per group (power of two)
-    int32_t rpg;              // consecutive rows owned by one group (<= G)
+    int32_t sets_per_group;   // consecutive fine row sets one group takes (1, 2, 4 or 8)
     int64_t num_rows;
     int32_t row_mode;
     int32_t long_thr;         // rows longer than this are left to the chunk kernels
     int64_t row_bytes;        // bytes of one feature row
     int64_t feat;
     int32_t xcd_run;          // consecutive logical blocks handed to one L2 domain
-    int64_t num_blocks;       // launched blocks (multiple of kXcds * xcd_run)
+    int64_t num_blocks;       // launched blocks (multiple of kXcds)
     const int32_t *long_rows, *chunk_ptr, *n_long, *n_chunks;
     char *partials;
 };
@@ -135,15 +136,32 @@ template <typename T> __device__ __forceinline__ T shfl_t(T v, int src);
 template <> __device__ __forceinline__ float shfl_t<float>(float v, int src) { return __shfl(v, src, kWave); }
 template <> __device__ __forceinline__ double shfl_t<double>(double v, int src) { return __shfl(v, src, kWave); }
 
-// Workgroup ids are dealt round-robin to the 8 L2 domains.  Logical blocks (and
-// with them rows) are handed out in runs of P.xcd_run consecutive blocks per
-// domain: neighbouring rows share one L2 (they touch neighbouring source rows and
-// the same output cache lines), while every domain still gets a sample of the
-// whole row range, so skewed blocks (all hubs at low ids) stay balanced.
-__device__ __forceinline__ int64_t logical_block(int run)
+// Which (row set, column tile) a lane group works on.
+//
+// Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.
+// Consecutive logical workgroups are handed to an XCD in runs of P.xcd_run, so
+// that neighbouring rows (which share output cache lines and first-touch source
+// rows) share an L2, while every XCD still samples the whole row range: blocks
+// whose hubs all sit at low ids stay balanced.  The column tiles of a row set
+// (rows wider than 64 slices) sit in neighbouring groups.
+struct GroupId {
+    int64_t g;        // index of the group's first fine row set / P.sets_per_group
+    int tile;         // column tile
+    int64_t count;    // launched groups per tile (chunk stride)
+};
+
+__device__ __forceinline__ GroupId map_group(const PullParams &P)
 {
+    const int gpb = kBlock / P.G;
     const int64_t x = blockIdx.x % kXcds, q = blockIdx.x / kXcds;
-    return ((q / run) * kXcds + x) * run + q % run;
+    const int64_t lb = ((q / P.xcd_run) * kXcds + x) * P.xcd_run + q % P.xcd_run;
+    const int64_t vg = lb * gpb + threadIdx.x / P.G;
+    const int64_t launched = P.num_blocks * gpb;
+    GroupId r;
+    r.tile = (int)(vg % P.ntiles);
+    r.g = vg / P.ntiles;
+    r.count = (launched - r.tile + P.ntiles - 1) / P.ntiles;
+    return r;
 }
 
 // Column ids and weights of up to G consecutive edges, one per lane of a group.
@@ -238,18 +256,16 @@ __device__ __forceinline__ void walk_run(const PullParams &P, int64_t r0, int ia
     while (row < ib) close_row();
 }
 
-// Chunks of long rows: one unit = (chunk, column tile).  The number of chunks
-// lives in device memory, so the host never needs to know the degrees; groups
-// stride over the units and write fp64 / fp32 partial sums to the workspace.
+// Chunks of long rows.  The number of chunks lives in device memory, so the host
+// never needs to know the degrees; the groups of a column tile stride over the
+// chunks and write fp64 / fp32 partial sums of their tile to the workspace.
 template <int DT, int VB, bool HASW>
-__device__ __forceinline__ void pull_chunks(const PullParams &P, int64_t first_unit, int64_t stride, int sub,
-                                            int gbase)
+__device__ __forceinline__ void pull_chunks(const PullParams &P, const GroupId &id, int sub, int gbase)
 {
     const int n_long = *P.n_long;
-    const int64_t total = (int64_t)(*P.n_chunks) * P.ntiles;
-    for (int64_t unit = first_unit; unit < total; unit += stride) {
-        const int chunk = (int)(unit / P.ntiles);
-        const int tile = (int)(unit - (int64_t)chunk * P.ntiles);
+    const int64_t total = *P.n_chunks;
+    const int64_t lane_off = ((int64_t)id.tile * P.G + sub) * VB;
+    for (int64_t chunk = id.g; chunk < total; chunk += id.count) {
         int lo = 0, hi = n_long;   // chunk_ptr[lo] <= chunk < chunk_ptr[hi]
         while (hi - lo > 1) {
             int mid = lo + ((hi - lo) >> 1);
@@ -257,48 +273,50 @@ __device__ __forceinline__ void pull_chunks(const PullParams &P, int64_t first_u
         }
         const int row = P.long_rows[lo];
         const int rbeg = P.rowptr[row], rend = P.rowptr[row + 1];
-        const int beg = rbeg + (chunk - P.chunk_ptr[lo]) * kLongChunk;
+        const int beg = rbeg + ((int)chunk - P.chunk_ptr[lo]) * kLongChunk;
         const int end = beg + kLongChunk < rend ? beg + kLongChunk : rend;
-        const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
         walk_run<DT, VB, HASW, true>(P, chunk, 0, 1, beg, end, sub, gbase, lane_off, lane_off < P.row_bytes);
     }
 }
 
 // One launch covers every row.  Each group first takes its share of the long-row
-// chunks (usually none), then its own set of P.rpg consecutive rows (x one column
-// tile), skipping rows that are long.  k_reduce_chunks finishes the long rows.
+// chunks (usually none), then its own row set: the consecutive rows
+// of a few fine row sets, which the plan cut so that every set carries the same
+// work (edges + rows), whatever the degree distribution is.  Rows that are long
+// are skipped here; k_reduce_chunks finishes them.
 template <int DT, int VB, bool HASW>
 __global__ __launch_bounds__(kBlock) void k_pull_rows(PullParams P)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
-    const int64_t unit = (logical_block(P.xcd_run) * kBlock + tid) / P.G;
-    if (P.long_rows)
-        pull_chunks<DT, VB, HASW>(P, unit, (int64_t)gridDim.x * kBlock / P.G, sub, gbase);
-    if (unit >= P.num_units) return;
-    const int64_t rg = unit / P.ntiles;
-    const int tile = (int)(unit - rg * P.ntiles);
-    const int64_t lane_off = ((int64_t)tile * P.G + sub) * VB;
+    const GroupId id = map_group(P);
+    if (P.long_rows) pull_chunks<DT, VB, HASW>(P, id, sub, gbase);
+    if (id.g >= P.ngroups) return;
+    const int64_t lane_off = ((int64_t)id.tile * P.G + sub) * VB;
     const bool active = lane_off < P.row_bytes;
-    const int64_t r0 = rg * P.rpg;
-    const int nrows = P.num_rows - r0 < P.rpg ? (int)(P.num_rows - r0) : P.rpg;
-    int pb = 0, pe = 0;
-    if (sub < nrows) {
-        pb = P.rowptr[r0 + sub];
-        pe = P.rowptr[r0 + sub + 1];
-    }
+    const int64_t s0 = id.g * P.sets_per_group;
+    const int64_t s1 = s0 + P.sets_per_group < P.nsets ? s0 + P.sets_per_group : P.nsets;
+    const int64_t rbeg = P.split[s0], rend = P.split[s1];
     const unsigned long long gmask = P.G == kWave ? ~0ull : ((1ull << P.G) - 1ull);
-    unsigned long long lm = (__ballot(sub < nrows && pe - pb > P.long_thr) >> gbase) & gmask;
-    int i = 0;
-    while (i < nrows) {
-        if ((lm >> i) & 1ull) {   // a long row: its chunks were handled above
-            ++i;
-            continue;
+    for (int64_t r0 = rbeg; r0 < rend; r0 += P.G) {
+        const int nrows = rend - r0 < P.G ? (int)(rend - r0) : P.G;
+        int pb = 0, pe = 0;
+        if (sub < nrows) {
+            pb = P.rowptr[r0 + sub];
+            pe = P.rowptr[r0 + sub + 1];
         }
-        const unsigned long long rest = lm >> i;
-        const int j = rest ? i + (__ffsll((long long)rest) - 1) : nrows;
-        walk_run<DT, VB, HASW, false>(P, r0, i, j, pb, pe, sub, gbase, lane_off, active);
-        i = j;
+        unsigned long long lm = (__ballot(sub < nrows && pe - pb > P.long_thr) >> gbase) & gmask;
+        int i = 0;
+        while (i < nrows) {
+            if ((lm >> i) & 1ull) {   // a long row: its chunks were handled above
+                ++i;
+                continue;
+            }
+            const unsigned long long rest = lm >> i;
+            const int j = rest ? i + (__ffsll((long long)rest) - 1) : nrows;
+            walk_run<DT, VB, HASW, false>(P, r0, i, j, pb, pe, sub, gbase, lane_off, active);
+            i = j;
+        }
     }
 }
 
@@ -410,22 +428,22 @@ fastgl_status launch_pull(const PullDesc &d, hipStream_t s)
     group_shape(P.row_bytes, vb, &G, &ntiles);
     P.G = G; P.ntiles = ntiles;
     P.num_rows = d.num_rows;
-    // rows per group: enough to amortise the row-pointer / column-id latency over
-    // many gathers, few enough to keep >= ~8K wavefronts in the launch
-    int64_t rpg = d.num_rows * G / ((int64_t)kWave * 8192);
-    const int maxrpg = tune("FASTGL_RPG", kRowsPerGroup);
-    if (rpg > maxrpg) rpg = maxrpg;
-    if (rpg > G) rpg = G;
-    if (rpg < 1) rpg = 1;
-    P.rpg = (int)rpg;
-    P.num_units = ceil_div(d.num_rows, rpg) * ntiles;
+    P.split = d.split;
+    P.nsets = d.nsets;
+    // several fine sets per group when there are plenty: amortises the row-pointer /
+    // column-id latency over more gathers while keeping >= ~16K groups in flight
+    int spg = 1;
+    while (spg < 8 && (d.nsets / (spg * 2)) * G * ntiles / kWave >= 16384) spg *= 2;
+    P.sets_per_group = tune("FASTGL_SPG", spg);
+    P.ngroups = ceil_div(d.nsets, P.sets_per_group);
     const bool with_long = d.long_rows != nullptr;
     P.long_thr = with_long ? kLongThreshold : INT32_MAX;
     P.long_rows = d.long_rows; P.chunk_ptr = d.chunk_ptr; P.n_long = d.n_long; P.n_chunks = d.n_chunks;
     P.partials = (char *)d.partials;
-    const int64_t nblocks = ceil_div(P.num_units * G, kBlock);
+    const int gpb = kBlock / G;
     P.xcd_run = tune("FASTGL_XCD_RUN", kXcdRun);
-    P.num_blocks = ceil_div(nblocks, (int64_t)kXcds * P.xcd_run) * kXcds * P.xcd_run;
+    P.num_blocks = ceil_div(ceil_div(P.ngroups * ntiles, gpb), (int64_t)kXcds * P.xcd_run) * P.xcd_run * kXcds;
+    const int64_t nblocks = P.num_blocks;
     if (P.num_blocks > 0x7FFFFFFFLL) {
         set_error("block too large for one launch (%lld workgroups)", (long long)nblocks);
         return FASTGL_ERR_UNSUPPORTED;

@@ -151,6 +151,7 @@ static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32
         d.num_rows = num_dst; d.num_cols = num_src;
         d.long_rows = pl->long_dst; d.chunk_ptr = pl->chunk_ptr_dst;
         d.n_long = pl->counters; d.n_chunks = pl->counters + 1;
+        d.split = pl->split_dst; d.nsets = num_row_sets(num_dst, num_edges);
     } else {
         d.rowptr = pl->indptr_T; d.col = pl->indices_T; d.eid = pl->perm;
         d.col_scale = mode == FASTGL_AGG_MEAN ? pl->dst_inv : mode == FASTGL_AGG_GCN ? pl->dst_rsqrt : nullptr;
@@ -158,6 +159,7 @@ static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32
         d.num_rows = num_src; d.num_cols = num_dst;
         d.long_rows = pl->long_src; d.chunk_ptr = pl->chunk_ptr_src;
         d.n_long = pl->counters + 2; d.n_chunks = pl->counters + 3;
+        d.split = pl->split_src; d.nsets = num_row_sets(num_src, num_edges);
     }
     return launch_pull(d, s);
 }
@@ -279,6 +281,8 @@ fastgl_status fastgl_block_plan_export(const fastgl_plan *p, fastgl_plan_view *v
     v->dst_rsqrt = f ? p->dst_rsqrt : nullptr;
     v->long_dst = f ? p->long_dst : nullptr;
     v->chunk_ptr_dst = f ? p->chunk_ptr_dst : nullptr;
+    v->split_dst = f ? p->split_dst : nullptr;
+    v->split_src = b ? p->split_src : nullptr;
     v->dout = sd ? p->dout : nullptr;
     v->indptr_T = b ? p->indptr_T : nullptr;
     v->indices_T = b ? p->indices_T : nullptr;
@@ -301,6 +305,7 @@ size_t fastgl_block_workspace_bytes(int64_t num_dst, int64_t num_src, int64_t nu
 
 int32_t fastgl_long_row_threshold(void) { return kLongThreshold; }
 int32_t fastgl_long_row_chunk(void) { return kLongChunk; }
+int32_t fastgl_work_per_group(void) { return kWorkPerGroup; }
 
 fastgl_status fastgl_gather_rows(const void *table, int64_t table_rows, const int64_t *ids, int64_t n,
                                  int64_t feat, fastgl_dtype dtype, void *out, void *stream)

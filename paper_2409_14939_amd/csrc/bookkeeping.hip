@@ -355,8 +355,32 @@ __device__ __forceinline__ void row_starts(const StartsArgs &A, int b)
     }
 }
 
+// Equal-work row sets: set g starts at the first row r with rowptr[r] + r >= g * kWorkPerGroup
+// (work of a row = its edges + 1), so no lane group of the aggregation kernel gets
+// more than kWorkPerGroup units plus one row, however skewed the degrees are.
+struct SplitArgs {
+    const int32_t *rowptr;   // [n+1]
+    int64_t n, ngroups;
+    int32_t *split;          // [ngroups+1]
+    int nb;
+};
+
+__device__ __forceinline__ void work_split(const SplitArgs &A, int b)
+{
+    for (int64_t g = (int64_t)b * blockDim.x + threadIdx.x; g <= A.ngroups; g += (int64_t)A.nb * blockDim.x) {
+        const int64_t target = g * kWorkPerGroup;
+        int64_t lo = 0, hi = A.n;   // answer in [lo, hi]; rowptr[n] + n >= any target <= ngroups * work
+        while (lo < hi) {
+            const int64_t mid = lo + ((hi - lo) >> 1);
+            if ((int64_t)A.rowptr[mid] + mid >= target) hi = mid; else lo = mid + 1;
+        }
+        A.split[g] = (int32_t)lo;
+    }
+}
+
 // ------------------------------------------------------- the stage kernel ----
-enum { JOB_ROWS_COUNT = 0, JOB_ROWS_FILL = 1, JOB_SORT_HIST = 2, JOB_SORT_SCATTER = 3, JOB_ROW_STARTS = 4 };
+enum { JOB_ROWS_COUNT = 0, JOB_ROWS_FILL = 1, JOB_SORT_HIST = 2, JOB_SORT_SCATTER = 3, JOB_ROW_STARTS = 4,
+       JOB_SPLIT = 5 };
 constexpr int kMaxJobs = 16;
 
 struct Job {
@@ -365,6 +389,7 @@ struct Job {
         RowsArgs rows;
         SortArgs sort;
         StartsArgs starts;
+        SplitArgs split;
     };
 };
 
@@ -391,7 +416,8 @@ __global__ __launch_bounds__(kSortThreads) void k_plan_stage(StageArgs A)
             else if (J.sort.items == 2) sort_scatter<2>(J.sort, b, M, lds);
             else sort_scatter<4>(J.sort, b, M, lds);
             break;
-        default: row_starts(J.starts, b); break;
+        case JOB_ROW_STARTS: row_starts(J.starts, b); break;
+        default: work_split(J.split, b); break;
     }
 }
 
@@ -488,6 +514,8 @@ size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src,
     q->chunk_ptr_dst = (int32_t *)take(4 * ((size_t)cl + 1));
     q->long_src = (int32_t *)take(4 * (size_t)cl);
     q->chunk_ptr_src = (int32_t *)take(4 * ((size_t)cl + 1));
+    q->split_dst = (int32_t *)take(4 * ((size_t)num_row_sets(num_dst, num_edges) + 1));
+    q->split_src = (int32_t *)take(4 * ((size_t)num_row_sets(num_src, num_edges) + 1));
     q->counters = (int32_t *)take(4 * 4);
     for (int i = 0; i < 4; ++i) q->sort_buf[i] = (int32_t *)take(4 * (size_t)num_edges);
     q->edge_dst = (int32_t *)take(4 * (size_t)num_edges);
@@ -506,6 +534,17 @@ static void add_job(Stages &st, size_t k, const Job &j)
     st[k].push_back(j);
 }
 
+static Job split_job(const int32_t *rowptr, int64_t n, int64_t nnz, int32_t *out)
+{
+    Job j;
+    j.kind = JOB_SPLIT;
+    j.split.rowptr = rowptr; j.split.n = n; j.split.ngroups = num_row_sets(n, nnz); j.split.split = out;
+    int64_t nb = ceil_div(j.split.ngroups + 1, (int64_t)kSortThreads);
+    if (nb > 256) nb = 256;
+    j.split.nb = (int)nb; j.nblocks = (int)nb;
+    return j;
+}
+
 static Job rows_job(int kind, const RowsArgs &A)
 {
     Job j;
@@ -522,6 +561,7 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
     RowsArgs dstA = rows_args(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->block_sums,
                               p->long_dst, p->chunk_ptr_dst, p->counters, full ? p->edge_dst : nullptr);
     add_job(st, 0, rows_job(JOB_ROWS_COUNT, dstA));
+    add_job(st, 0, split_job(p->indptr, p->num_dst, p->num_edges, p->split_dst));
     add_job(st, 1, rows_job(JOB_ROWS_FILL, dstA));
     if (!full) return;
 
@@ -568,6 +608,7 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
     RowsArgs srcA = rows_args(p->indptr_T, p->num_src, p->dout, nullptr, p->src_rsqrt, p->block_sums2,
                               p->long_src, p->chunk_ptr_src, p->counters + 2);
     add_job(st, 2 * npass + 1, rows_job(JOB_ROWS_COUNT, srcA));
+    add_job(st, 2 * npass + 1, split_job(p->indptr_T, p->num_src, p->num_edges, p->split_src));
     add_job(st, 2 * npass + 2, rows_job(JOB_ROWS_FILL, srcA));
 }
 

@@ -12,6 +12,7 @@ constexpr int kWave = 64;
 constexpr int kBlock = 256;            // threads per workgroup (4 wavefronts)
 constexpr int kLongThreshold = 256;    // rows longer than this go through the chunked path
 constexpr int kLongChunk = 128;        // edges per partial-sum chunk
+constexpr int kWorkPerGroup = 16;      // edges + rows per fine row set (a lane group takes 1-8 sets)
 constexpr int kMaxScanBlocks = 1024;   // blocks of a two-kernel scan / compaction
 constexpr int kRadixBits = 8;
 constexpr int kRadixBins = 1 << kRadixBits;
@@ -37,6 +38,7 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Upper bounds used to size the bucket arrays without knowing the degrees.
 inline int64_t cap_long_rows(int64_t num_edges) { return num_edges / (kLongThreshold + 1) + 1; }
+inline int64_t num_row_sets(int64_t rows, int64_t nnz) { return ceil_div(rows + nnz, kWorkPerGroup); }
 inline int64_t cap_chunks(int64_t num_edges) { return num_edges / kLongChunk + cap_long_rows(num_edges) + 1; }
 
 }  // namespace fastgl
@@ -49,6 +51,7 @@ struct fastgl_plan {
     int32_t *din, *dout, *indptr_T, *indices_T, *perm;
     float *dst_inv, *dst_rsqrt, *src_rsqrt;
     int32_t *long_dst, *chunk_ptr_dst, *long_src, *chunk_ptr_src;
+    int32_t *split_dst, *split_src;   // [row sets + 1] first row of each equal-work row set
     int32_t *counters;      // [4] n_long_dst, n_chunks_dst, n_long_src, n_chunks_src
     // scratch
     int32_t *sort_buf[4];   // ping-pong keys / values, num_edges each
@@ -81,6 +84,9 @@ struct PullDesc {
     // long-row bucket (device-resident counts)
     const int32_t *long_rows, *chunk_ptr, *n_long, *n_chunks;
     void *partials;            // cap_chunks * feat accumulators
+    // equal-work row sets
+    const int32_t *split;      // [nsets+1]
+    int64_t nsets;
 };
 
 fastgl_status launch_pull(const PullDesc &d, hipStream_t s);

@@ -109,6 +109,10 @@ def check_bookkeeping(blk, what):
         assert c[0] == rows.shape[0] and c[1] == cptr[-1]
         assert np.array_equal(read_i32(plan, lr, rows.shape[0]), rows)
         assert np.array_equal(read_i32(plan, cp, rows.shape[0] + 1), cptr)
+    work = B.fastgl_work_per_group()
+    for rowptr, ptr in ((blk.indptr, v.split_dst), (pT, v.split_src)):
+        sp = oracle.work_split(rowptr, work)
+        assert np.array_equal(read_i32(plan, ptr, sp.shape[0]), sp)
     # scale factors: correctly rounded fp32 of the fp64 value
     np.testing.assert_allclose(read_f32(plan, v.dst_inv, nd), 1.0 / np.maximum(din, 1), rtol=1e-6)
     np.testing.assert_allclose(read_f32(plan, v.dst_rsqrt, nd), 1.0 / np.sqrt(np.maximum(din, 1)), rtol=1e-6)

@@ -177,6 +177,23 @@ def test_long_row_buckets():
     assert rows.size == 0 and cptr.tolist() == [0]
 
 
+def test_work_split_covers_rows_with_bounded_work():
+    rng = np.random.default_rng(14)
+    for blk in small_blocks() + [bg.random_block(rng, 700, 300, 9.0, hub_rows=3, hub_deg=500)]:
+        ptr = blk.indptr.astype(np.int64)
+        n, work = blk.num_dst, 64
+        sp = oracle.work_split(blk.indptr, work)
+        assert sp[0] == 0 and sp[-1] == n and np.all(np.diff(sp) >= 0)
+        assert sp.shape[0] == -(-(n + blk.num_edges) // work) + 1
+        w = ptr + np.arange(n + 1)          # work before row r
+        for g in range(sp.shape[0] - 1):
+            a, b = sp[g], sp[g + 1]
+            if a < b:                        # all rows of the set start inside its work window
+                assert g * work <= w[a] and w[b - 1] < (g + 1) * work
+        # independent definition: searchsorted on the work prefix
+        assert np.array_equal(sp, np.searchsorted(w, np.arange(sp.shape[0]) * work, side="left").clip(max=n))
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_p9_metamorphic(mode):
     rng = np.random.default_rng(10)
