@@ -65,6 +65,8 @@ enum {
     FASTGL_PLAN_BWD = 2, /* out-degrees, stable transpose CSR, source-side degree buckets;
                             implies FASTGL_PLAN_FWD */
     FASTGL_PLAN_ALL = 3,
+    FASTGL_PLAN_PERM = 8,   /* with FASTGL_PLAN_BWD: also keep `perm`, the original edge id of every
+                               transposed edge.  Only a backward pass WITH edge_w reads it. */
     FASTGL_PLAN_SRC_DEG = 4 /* with FASTGL_PLAN_FWD only: out-degrees and their scale factors by a
                                histogram, which is all a GCN-normalised FORWARD pass needs beyond
                                FASTGL_PLAN_FWD.  Lets the forward pass start before the transpose
@@ -82,7 +84,7 @@ typedef struct {
     const int32_t *dout;         /* [num_src]   edges per source                              */
     const int32_t *indptr_T;     /* [num_src+1] transpose row pointers                        */
     const int32_t *indices_T;    /* [E] destination of the k-th edge in (source, edge id) order */
-    const int32_t *perm;         /* [E] original edge id of that edge                         */
+    const int32_t *perm;         /* [E] original edge id of that edge (FASTGL_PLAN_PERM only) */
     const float *dst_inv;        /* [num_dst]   1/max(din,1)                                  */
     const float *dst_rsqrt;      /* [num_dst]   1/sqrt(max(din,1))                            */
     const float *src_rsqrt;      /* [num_src]   1/sqrt(max(dout,1))                           */
@@ -118,7 +120,8 @@ fastgl_status fastgl_block_aggregate_fwd(
  * same edge weights as the forward pass.  grad_out[num_dst,feat] in,
  * grad_X[num_src,feat] out (every row written).  The pass pulls along a
  * stable transpose of the CSR, so results are deterministic (no atomics on
- * floating point).  plan needs FASTGL_PLAN_ALL; otherwise as forward. */
+ * floating point).  plan needs FASTGL_PLAN_ALL, and FASTGL_PLAN_PERM as well when
+ * edge_w is given; otherwise as forward. */
 fastgl_status fastgl_block_aggregate_bwd(
     const int32_t *indptr, const int32_t *indices, const float *edge_w,
     int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
@@ -133,7 +136,7 @@ size_t fastgl_block_plan_bytes(int64_t num_dst, int64_t num_src, int64_t num_edg
  * 256-byte aligned, >= fastgl_block_plan_bytes): degrees, scale factors, the
  * stable transpose CSR (transposed rows keep ascending original edge id) and
  * the degree buckets.  `parts` is FASTGL_PLAN_FWD, FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG,
- * FASTGL_PLAN_BWD or FASTGL_PLAN_ALL.  The plan keeps
+ * FASTGL_PLAN_BWD or FASTGL_PLAN_ALL, the last two optionally | FASTGL_PLAN_PERM.  The plan keeps
  * pointers to indptr/indices and plan_mem: they must outlive it and stay
  * unchanged.  *out receives a host handle to free with
  * fastgl_block_plan_destroy.  No host synchronisation. */

@@ -426,6 +426,10 @@ fastgl_status launch_pull(const PullDesc &d, hipStream_t s)
     const int vb = pick_slice_bytes(P.row_bytes, d.in, d.out, elem);
     int G, ntiles;
     group_shape(P.row_bytes, vb, &G, &ntiles);
+    if (tune("FASTGL_G", 0) > 0 && tune("FASTGL_G", 0) < G) {   // development knob: narrower groups, more tiles
+        ntiles = ntiles * G / tune("FASTGL_G", 0);
+        G = tune("FASTGL_G", 0);
+    }
     P.G = G; P.ntiles = ntiles;
     P.num_rows = d.num_rows;
     P.split = d.split;

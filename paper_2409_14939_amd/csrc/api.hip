@@ -100,7 +100,7 @@ static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32
         return FASTGL_ERR_INVALID_ARG;
     }
     const size_t pbytes = partial_bytes(num_edges, feat, dtype);
-    const int need_parts = backward ? FASTGL_PLAN_ALL : FASTGL_PLAN_FWD;
+    const int need_parts = backward ? (FASTGL_PLAN_ALL | (edge_w ? FASTGL_PLAN_PERM : 0)) : FASTGL_PLAN_FWD;
     hipStream_t s = (hipStream_t)stream;
     fastgl_plan local;
     const fastgl_plan *pl = plan;
@@ -208,9 +208,11 @@ fastgl_status fastgl_block_plan_create_many(int n, const fastgl_block_desc *bloc
         const fastgl_block_desc &d = blocks[i];
         fastgl_status st = check_block(d.indptr, d.indices, d.num_dst, d.num_src, d.num_edges);
         if (st != FASTGL_OK) return st;
-        if (d.parts != FASTGL_PLAN_FWD && d.parts != FASTGL_PLAN_BWD && d.parts != FASTGL_PLAN_ALL &&
-            d.parts != (FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG)) {
-            set_error("block %d: parts must be FWD, FWD|SRC_DEG, BWD or ALL (got %d)", i, d.parts);
+        const int base = d.parts & ~FASTGL_PLAN_PERM;
+        const bool ok = d.parts == FASTGL_PLAN_FWD || d.parts == (FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG) ||
+                        base == FASTGL_PLAN_BWD || base == FASTGL_PLAN_ALL;
+        if (!ok || d.parts < 0 || d.parts > 15) {
+            set_error("block %d: parts must be FWD, FWD|SRC_DEG, BWD[|PERM] or ALL[|PERM] (got %d)", i, d.parts);
             return FASTGL_ERR_INVALID_ARG;
         }
         if (!d.plan_mem || ((uintptr_t)d.plan_mem & 255)) {
@@ -241,7 +243,7 @@ fastgl_status fastgl_block_plan_create_many(int n, const fastgl_block_desc *bloc
         plan_layout(p, d.plan_mem, d.num_dst, d.num_src, d.num_edges);
         plans[made] = p;
         // a backward plan also carries what the forward pass of the same block needs
-        parts[made] = (d.parts & FASTGL_PLAN_BWD) ? FASTGL_PLAN_ALL : FASTGL_PLAN_FWD;
+        parts[made] = (d.parts & FASTGL_PLAN_BWD) ? (FASTGL_PLAN_ALL | (d.parts & FASTGL_PLAN_PERM)) : FASTGL_PLAN_FWD;
         src_deg[made] = (d.parts & FASTGL_PLAN_SRC_DEG) != 0;
     }
     if (st == FASTGL_OK) st = plans_build(plans, parts, src_deg, n, (hipStream_t)stream);
@@ -286,7 +288,7 @@ fastgl_status fastgl_block_plan_export(const fastgl_plan *p, fastgl_plan_view *v
     v->dout = sd ? p->dout : nullptr;
     v->indptr_T = b ? p->indptr_T : nullptr;
     v->indices_T = b ? p->indices_T : nullptr;
-    v->perm = b ? p->perm : nullptr;
+    v->perm = (b && (p->parts & FASTGL_PLAN_PERM)) ? p->perm : nullptr;
     v->src_rsqrt = sd ? p->src_rsqrt : nullptr;
     v->long_src = b ? p->long_src : nullptr;
     v->chunk_ptr_src = b ? p->chunk_ptr_src : nullptr;

@@ -166,13 +166,13 @@ __device__ __forceinline__ void rows_fill(const RowsArgs &A, int b, int *lds)
 
 // ------------------------------------------------------------ radix sort ----
 struct SortArgs {
-    const int32_t *keys_in, *vals_in;   // vals_in == NULL: the identity (first pass)
-    int32_t *keys_out, *vals_out;
+    const int32_t *keys_in, *vals_in;   // vals: the destination row of the edge
+    int32_t *keys_out, *vals_out;       // keys_out == NULL: not needed (never on this path: row starts read them)
+    const int32_t *eid_in;              // second payload, the original edge id; NULL on the first pass = identity
+    int32_t *eid_out;                   // NULL: the plan carries no edge permutation
     int64_t n, per;                     // block b owns keys [b*per, min(n,(b+1)*per))
     int nb, shift;
     int32_t *cnt;                       // [nb][256] digit counts per block
-    const int32_t *edge_dst;            // [n] destination row of every edge (read by the last pass)
-    int32_t *dst_out;                   // last pass: [n] destination row in sorted order, else NULL
     int items;                          // keys per thread and step: 1, 2 or 4
 };
 
@@ -196,11 +196,12 @@ __device__ __forceinline__ void sort_hist(const SortArgs &S, int b, int *h)
 // running per-wavefront digit counts live in LDS, and a column scan over the 16
 // wavefronts plus a scan over the digits give each key its place in the step's
 // sorted order.  The step is sorted into LDS first and written out from there.
-// The last pass (dst_out set) also writes the destination row of each edge.
+// The payload is the edge's destination row and, if asked for, its original id.
 struct SortShared {
     int running[kRadixBins], lbase[kRadixBins], gdelta[kRadixBins];
     int wcnt[kSortWaves][kRadixBins];
     int32_t skey[kSortThreads * kMaxSortItems], sval[kSortThreads * kMaxSortItems];
+    int32_t seid[kSortThreads * kMaxSortItems];
 };
 
 template <int ITEMS>
@@ -208,8 +209,8 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
 {
     int (&running)[kRadixBins] = M.running, (&lbase)[kRadixBins] = M.lbase, (&gdelta)[kRadixBins] = M.gdelta;
     int (&wcnt)[kSortWaves][kRadixBins] = M.wcnt;
-    int32_t *skey = M.skey, *sval = M.sval;
-    const bool LAST = S.dst_out != nullptr;
+    int32_t *skey = M.skey, *sval = M.sval, *seid = M.seid;
+    const bool EID = S.eid_out != nullptr;
     const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
     {   // offsets of this block's digits
         const int d = t & (kRadixBins - 1), part = t / kRadixBins;   // 4 parts share the blocks
@@ -250,7 +251,7 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
         for (int k = 0; k < kSortWaves * kRadixBins / kSortThreads; ++k)
             (&wcnt[0][0])[k * kSortThreads + t] = 0;
         __syncthreads();
-        int32_t key[ITEMS], val[ITEMS];
+        int32_t key[ITEMS], val[ITEMS], eid[ITEMS];
         int rank[ITEMS], dig[ITEMS];
         bool ok[ITEMS];
 #pragma unroll
@@ -258,7 +259,8 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
             const int64_t idx = step + (int64_t)w * (kWave * ITEMS) + i * kWave + lane;
             ok[i] = idx < end;
             key[i] = ok[i] ? S.keys_in[idx] : 0;
-            val[i] = ok[i] ? (S.vals_in ? S.vals_in[idx] : (int32_t)idx) : 0;
+            val[i] = ok[i] ? S.vals_in[idx] : 0;
+            eid[i] = EID && ok[i] ? (S.eid_in ? S.eid_in[idx] : (int32_t)idx) : 0;
             dig[i] = (key[i] >> S.shift) & (kRadixBins - 1);
         }
 #pragma unroll
@@ -302,6 +304,7 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
             const int lpos = lbase[dig[i]] + wcnt[w][dig[i]] + rank[i];
             skey[lpos] = key[i];
             sval[lpos] = val[i];
+            if (EID) seid[lpos] = eid[i];
         }
         __syncthreads();
         // keys of one digit are now consecutive in LDS and go to consecutive global
@@ -314,7 +317,7 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
             const int pos = gdelta[(k >> S.shift) & (kRadixBins - 1)] + j;
             S.keys_out[pos] = k;
             S.vals_out[pos] = v;
-            if (LAST) S.dst_out[pos] = S.edge_dst[v];
+            if (EID) S.eid_out[pos] = seid[j];
         }
         __syncthreads();   // wcnt and the staging arrays are reused by the next step
     }
@@ -517,7 +520,7 @@ size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src,
     q->split_dst = (int32_t *)take(4 * ((size_t)num_row_sets(num_dst, num_edges) + 1));
     q->split_src = (int32_t *)take(4 * ((size_t)num_row_sets(num_src, num_edges) + 1));
     q->counters = (int32_t *)take(4 * 4);
-    for (int i = 0; i < 4; ++i) q->sort_buf[i] = (int32_t *)take(4 * (size_t)num_edges);
+    for (int i = 0; i < 6; ++i) q->sort_buf[i] = (int32_t *)take(4 * (size_t)num_edges);
     q->edge_dst = (int32_t *)take(4 * (size_t)num_edges);
     q->radix_cnt = (int32_t *)take(4 * (size_t)kRadixBins * kMaxSortBlocks);
     q->block_sums = (int32_t *)take(4 * 2 * (size_t)kMaxScanBlocks);
@@ -558,6 +561,8 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
 {
     p->parts = parts;
     const bool full = (parts & FASTGL_PLAN_BWD) != 0;
+    if (!full) parts &= ~FASTGL_PLAN_PERM;
+    p->parts = parts;
     RowsArgs dstA = rows_args(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->block_sums,
                               p->long_dst, p->chunk_ptr_dst, p->counters, full ? p->edge_dst : nullptr);
     add_job(st, 0, rows_job(JOB_ROWS_COUNT, dstA));
@@ -581,14 +586,14 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
     S.per = per;
     S.nb = n > 0 ? (int)ceil_div(n, per) : 1;
     S.cnt = p->radix_cnt;
-    S.edge_dst = p->edge_dst;
-    const int32_t *kin = p->indices, *vin = nullptr;
+    const bool want_perm = (parts & FASTGL_PLAN_PERM) != 0;
+    const int32_t *kin = p->indices, *vin = p->edge_dst, *ein = nullptr;
     for (int pass = 0; pass < npass; ++pass) {
         const bool last = pass == npass - 1;
-        S.keys_in = kin; S.vals_in = vin; S.shift = pass * kRadixBits;
-        S.keys_out = p->sort_buf[(pass & 1) * 2];
-        S.vals_out = last ? p->perm : p->sort_buf[(pass & 1) * 2 + 1];
-        S.dst_out = last ? p->indices_T : nullptr;
+        S.keys_in = kin; S.vals_in = vin; S.eid_in = ein; S.shift = pass * kRadixBits;
+        S.keys_out = p->sort_buf[(pass & 1) * 3];
+        S.vals_out = last ? p->indices_T : p->sort_buf[(pass & 1) * 3 + 1];
+        S.eid_out = !want_perm ? nullptr : last ? p->perm : p->sort_buf[(pass & 1) * 3 + 2];
         Job j;
         j.nblocks = S.nb; j.sort = S;
         j.kind = JOB_SORT_HIST;
@@ -597,6 +602,7 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
         add_job(st, 2 * pass + 1, j);
         kin = S.keys_out;
         vin = S.vals_out;
+        ein = S.eid_out;
     }
     Job t;
     t.kind = JOB_ROW_STARTS;

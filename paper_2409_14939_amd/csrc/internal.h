@@ -54,7 +54,7 @@ struct fastgl_plan {
     int32_t *split_dst, *split_src;   // [row sets + 1] first row of each equal-work row set
     int32_t *counters;      // [4] n_long_dst, n_chunks_dst, n_long_src, n_chunks_src
     // scratch
-    int32_t *sort_buf[4];   // ping-pong keys / values, num_edges each
+    int32_t *sort_buf[6];   // ping-pong keys / destination rows / edge ids, num_edges each
     int32_t *edge_dst;      // [num_edges] destination row of every edge
     int32_t *radix_cnt;     // [sort blocks][kRadixBins]
     int32_t *block_sums;    // 2 * kMaxScanBlocks (destination-side bucket counts)

@@ -67,7 +67,8 @@ def test_bad_arguments_are_refused_before_launch(kw, status, text):
 def test_plan_and_gather_argument_checks():
     L = B.lib()
     out = ctypes.c_void_p()
-    assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 7, FAKE, 1 << 30, None, ctypes.byref(out)) == B.FASTGL_ERR_INVALID_ARG
+    for bad in (0, 4, 6, 7, 9, 13, 16, -1):
+        assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, bad, FAKE, 1 << 30, None, ctypes.byref(out)) == B.FASTGL_ERR_INVALID_ARG, bad
     assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 3, FAKE, 8, None, ctypes.byref(out)) == B.FASTGL_ERR_WORKSPACE
     assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 3, None, 1 << 30, None, ctypes.byref(out)) == B.FASTGL_ERR_INVALID_ARG
     assert out.value is None

@@ -17,7 +17,8 @@ MODES = ["sum", "mean", "gcn"]
 def run_both(blk, w, mode, dtype, X, G, use_plan):
     ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
     wd = None if w is None else torch.from_numpy(w).cuda()
-    plan = B.fastgl_block_plan_create(ip, ix, blk.num_src) if use_plan else None
+    plan = B.fastgl_block_plan_create(ip, ix, blk.num_src, B.PLAN_ALL | (B.PLAN_PERM if w is not None else 0)) \
+        if use_plan else None
     out = B.fastgl_block_aggregate_fwd(ip, ix, wd, blk.num_src, mode, dev_feat(X, dtype), plan=plan)
     dX = B.fastgl_block_aggregate_bwd(ip, ix, wd, blk.num_src, mode, dev_feat(G, dtype), plan=plan)
     torch.cuda.synchronize()
@@ -91,7 +92,7 @@ def check_bookkeeping(blk, what):
     print(f"bookkeeping {what} dst={blk.num_dst} src={blk.num_src} E={blk.num_edges}", flush=True)
     ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
     assert B.fastgl_block_validate(ip, ix, blk.num_src) == 0
-    plan = B.fastgl_block_plan_create(ip, ix, blk.num_src)
+    plan = B.fastgl_block_plan_create(ip, ix, blk.num_src, B.PLAN_ALL | B.PLAN_PERM)
     v = plan.export()
     e, nd, ns = blk.num_edges, blk.num_dst, blk.num_src
     din, dout = oracle.degrees(blk.indptr, blk.indices, ns)
@@ -141,7 +142,7 @@ def test_batched_plans_match_single_plans():
               bg.random_block(rng, 300, 70000, 40.0, hub_rows=2, hub_deg=9000),
               bg.random_block(rng, 9, 17, 0.0, empty_frac=1.0)]
     dev = [(dev_i32(b.indptr), dev_i32(b.indices), b.num_src) for b in blocks]
-    plans = B.fastgl_block_plan_create_many(dev)
+    plans = B.fastgl_block_plan_create_many(dev, B.PLAN_ALL | B.PLAN_PERM)
     for blk, plan in zip(blocks, plans):
         v = plan.export()
         pT, iT, perm = oracle.transpose(blk.indptr, blk.indices, blk.num_src)
@@ -164,8 +165,20 @@ def test_batched_plans_match_single_plans():
     torch.cuda.synchronize()
     assert_close(host_feat(out, "f32"), oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, "gcn",
                                                              "f32", X), "f32", "forward-only plan")
+    G = dev_feat(make_inputs(rng, blk.num_dst, 48, "f32"), "f32")
+    with pytest.raises(B.FastglError):     # a forward-only plan cannot serve the backward pass
+        B.fastgl_block_aggregate_bwd(ip, ix, None, blk.num_src, "gcn", G, plan=pf)
+    # a plan without the edge permutation serves an unweighted backward pass but not a weighted one,
+    # and does not export perm
+    pa = B.fastgl_block_plan_create(ip, ix, blk.num_src, B.PLAN_ALL)
+    assert pa.export().perm is None
+    wts = torch.ones(blk.num_edges, device="cuda")
     with pytest.raises(B.FastglError):
-        B.fastgl_block_aggregate_bwd(ip, ix, None, blk.num_src, "gcn", dev_feat(make_inputs(rng, blk.num_dst, 48, "f32"), "f32"), plan=pf)
+        B.fastgl_block_aggregate_bwd(ip, ix, wts, blk.num_src, "sum", G, plan=pa)
+    dX = B.fastgl_block_aggregate_bwd(ip, ix, None, blk.num_src, "sum", G, plan=pa)
+    torch.cuda.synchronize()
+    assert_close(host_feat(dX, "f32"), oracle.aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, "sum",
+                                                            "f32", host_feat(G, "f32")), "f32", "plan without perm")
 
 
 def test_validate_counts_violations():
