@@ -26,7 +26,8 @@
 
 namespace fastgl {
 
-constexpr int kUnroll = 6;
+constexpr int kUnroll = 6;        // row gathers in flight per lane (wide groups)
+constexpr int kUnrollNarrow = 4;  // groups of <= 16 lanes fetch <= 16 column ids at a time: 4 divides that
 constexpr int kXcdRun = 16;
 
 template <int DT> struct AccT { using type = double; };
@@ -190,7 +191,7 @@ __device__ __forceinline__ acc_t load_weight(const PullParams &P, int k, int ken
 // Column ids are fetched two chunks ahead and weights one chunk ahead of use.
 // PARTIAL: the "row" is a chunk of a long row; its unscaled sum goes to slot r0 of
 // the partial-sum buffer instead of the output.
-template <int DT, int VB, bool HASW, bool PARTIAL>
+template <int DT, int VB, bool HASW, bool PARTIAL, int U>
 __device__ __forceinline__ void walk_run(const PullParams &P, int64_t r0, int ia, int ib, int pb, int pe,
                                          int sub, int gbase, int64_t lane_off, bool active)
 {
@@ -229,16 +230,16 @@ __device__ __forceinline__ void walk_run(const PullParams &P, int64_t r0, int ia
         const int n = eend - k0 < G ? eend - k0 : G;
         const int nn_c = load_cols<HASW, acc_t>(P, k0 + 2 * G + sub, eend);
         const acc_t nxt_w = load_weight<HASW, acc_t>(P, k0 + G + sub, eend, nxt_c);
-        for (int j0 = 0; j0 < n; j0 += kUnroll) {
-            uint32_t raw[kUnroll][S::NW];
+        for (int j0 = 0; j0 < n; j0 += U) {
+            uint32_t raw[U][S::NW];
 #pragma unroll
-            for (int t = 0; t < kUnroll; ++t) {
+            for (int t = 0; t < U; ++t) {
                 const int j = j0 + t;
                 const int c = __shfl(cur_c, gbase + (j & (G - 1)), kWave);
                 if (j < n && active) S::load(P.in + (int64_t)c * P.row_bytes + lane_off, raw[t]);
             }
 #pragma unroll
-            for (int t = 0; t < kUnroll; ++t) {
+            for (int t = 0; t < U; ++t) {
                 const int j = j0 + t;
                 acc_t w = (acc_t)1;
                 if (HASW) w = shfl_t<acc_t>(cur_w, gbase + (j & (G - 1)));
@@ -259,7 +260,7 @@ __device__ __forceinline__ void walk_run(const PullParams &P, int64_t r0, int ia
 // Chunks of long rows.  The number of chunks lives in device memory, so the host
 // never needs to know the degrees; the groups of a column tile stride over the
 // chunks and write fp64 / fp32 partial sums of their tile to the workspace.
-template <int DT, int VB, bool HASW>
+template <int DT, int VB, bool HASW, int U>
 __device__ __forceinline__ void pull_chunks(const PullParams &P, const GroupId &id, int sub, int gbase)
 {
     const int n_long = *P.n_long;
@@ -275,7 +276,7 @@ __device__ __forceinline__ void pull_chunks(const PullParams &P, const GroupId &
         const int rbeg = P.rowptr[row], rend = P.rowptr[row + 1];
         const int beg = rbeg + ((int)chunk - P.chunk_ptr[lo]) * kLongChunk;
         const int end = beg + kLongChunk < rend ? beg + kLongChunk : rend;
-        walk_run<DT, VB, HASW, true>(P, chunk, 0, 1, beg, end, sub, gbase, lane_off, lane_off < P.row_bytes);
+        walk_run<DT, VB, HASW, true, U>(P, chunk, 0, 1, beg, end, sub, gbase, lane_off, lane_off < P.row_bytes);
     }
 }
 
@@ -284,13 +285,13 @@ __device__ __forceinline__ void pull_chunks(const PullParams &P, const GroupId &
 // of a few fine row sets, which the plan cut so that every set carries the same
 // work (edges + rows), whatever the degree distribution is.  Rows that are long
 // are skipped here; k_reduce_chunks finishes them.
-template <int DT, int VB, bool HASW>
+template <int DT, int VB, bool HASW, int U>
 __global__ __launch_bounds__(kBlock) void k_pull_rows(PullParams P)
 {
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int sub = tid & (P.G - 1), gbase = lane & ~(P.G - 1);
     const GroupId id = map_group(P);
-    if (P.long_rows) pull_chunks<DT, VB, HASW>(P, id, sub, gbase);
+    if (P.long_rows) pull_chunks<DT, VB, HASW, U>(P, id, sub, gbase);
     if (id.g >= P.ngroups) return;
     const int64_t lane_off = ((int64_t)id.tile * P.G + sub) * VB;
     const bool active = lane_off < P.row_bytes;
@@ -314,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void k_pull_rows(PullParams P)
             }
             const unsigned long long rest = lm >> i;
             const int j = rest ? i + (__ffsll((long long)rest) - 1) : nrows;
-            walk_run<DT, VB, HASW, false>(P, r0, i, j, pb, pe, sub, gbase, lane_off, active);
+            walk_run<DT, VB, HASW, false, U>(P, r0, i, j, pb, pe, sub, gbase, lane_off, active);
             i = j;
         }
     }
@@ -339,9 +340,19 @@ __global__ __launch_bounds__(kBlock) void k_reduce_chunks(PullParams P)
 #pragma unroll
         for (int i = 0; i < S::NE; ++i) acc[i] = (acc_t)0;
         const acc_t *src = reinterpret_cast<const acc_t *>(P.partials) + ((int64_t)tile * P.G + sub) * S::NE;
-        for (int c = P.chunk_ptr[li]; c < P.chunk_ptr[li + 1]; ++c) {
+        // partial sums are added in chunk order (fixed result); 8 are fetched at a time
+        const int c1 = P.chunk_ptr[li + 1];
+        for (int c0 = P.chunk_ptr[li]; c0 < c1; c0 += 8) {
+            acc_t part[8][S::NE];
 #pragma unroll
-            for (int i = 0; i < S::NE; ++i) acc[i] += src[(int64_t)c * P.feat + i];
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int i = 0; i < S::NE; ++i)
+                    part[k][i] = c0 + k < c1 ? src[(int64_t)(c0 + k) * P.feat + i] : (acc_t)0;
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+#pragma unroll
+                for (int i = 0; i < S::NE; ++i) acc[i] += part[k][i];
         }
         const int len = P.rowptr[row + 1] - P.rowptr[row];
         S::store(P.out + (int64_t)row * P.row_bytes + lane_off, acc, row_scale<acc_t>(P.row_mode, len));
@@ -401,8 +412,11 @@ static fastgl_status launch_typed(const PullParams &P, bool hasw, bool with_long
 {
     if (nblocks > 0) {
         dim3 grid((unsigned)P.num_blocks);
-        if (hasw) hipLaunchKernelGGL((k_pull_rows<DT, VB, true>), grid, dim3(kBlock), 0, s, P);
-        else hipLaunchKernelGGL((k_pull_rows<DT, VB, false>), grid, dim3(kBlock), 0, s, P);
+        const bool narrow = P.G <= 16;
+        if (hasw && narrow) hipLaunchKernelGGL((k_pull_rows<DT, VB, true, kUnrollNarrow>), grid, dim3(kBlock), 0, s, P);
+        else if (hasw) hipLaunchKernelGGL((k_pull_rows<DT, VB, true, kUnroll>), grid, dim3(kBlock), 0, s, P);
+        else if (narrow) hipLaunchKernelGGL((k_pull_rows<DT, VB, false, kUnrollNarrow>), grid, dim3(kBlock), 0, s, P);
+        else hipLaunchKernelGGL((k_pull_rows<DT, VB, false, kUnroll>), grid, dim3(kBlock), 0, s, P);
         FASTGL_LAUNCH_CHECK("k_pull_rows");
     }
     if (with_long) {
