@@ -95,10 +95,21 @@ template <int DT, int VB> struct Slice {
         } else {
             r[0] = to_bf16(acc[0] * scale);
         }
-        if constexpr (VB == 16) *reinterpret_cast<uint4 *>(p) = make_uint4(r[0], r[1], r[2], r[3]);
-        else if constexpr (VB == 8) *reinterpret_cast<uint2 *>(p) = make_uint2(r[0], r[1]);
-        else if constexpr (VB == 4) *reinterpret_cast<uint32_t *>(p) = r[0];
-        else *reinterpret_cast<uint16_t *>(p) = (uint16_t)r[0];
+        // output rows are written once and never read back by this kernel: streaming
+        // stores keep them from displacing gathered rows in L2 / Infinity Cache
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        if constexpr (VB == 16) {
+            u32x4 v = {r[0], r[1], r[2], r[3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+        } else if constexpr (VB == 8) {
+            u32x2 v = {r[0], r[1]};
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(p));
+        } else if constexpr (VB == 4) {
+            __builtin_nontemporal_store(r[0], reinterpret_cast<uint32_t *>(p));
+        } else {
+            __builtin_nontemporal_store((uint16_t)r[0], reinterpret_cast<uint16_t *>(p));
+        }
     }
 };
 
