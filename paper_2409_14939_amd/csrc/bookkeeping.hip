@@ -79,6 +79,8 @@ struct RowsArgs {
     int32_t *counts;         // [2*nb] per-block (long rows, chunks)
     int32_t *long_rows, *chunk_ptr, *totals;
     int32_t *edge_row;       // [nnz] or NULL: edge_row[e] = row that owns edge e
+    int32_t *split;          // [nsets+1] or NULL: first row of every equal-work row set
+    int64_t nsets;
 };
 
 // Pass 1 over row pointers: row lengths, scale factors, per-block counts of long
@@ -115,6 +117,29 @@ __device__ __forceinline__ void rows_count(const RowsArgs &A, int b, int *lds)
                 const int le0 = __shfl(e0, leader, kWave), ll = __shfl(len, leader, kWave);
                 const int lr = (int)(base - beg) + (threadIdx.x - lane) + leader;   // row offset in block
                 for (int k = lane; k < ll; k += kWave) A.edge_row[le0 + k] = (int32_t)(beg + lr);
+                m &= m - 1;
+            }
+        }
+        if (A.split) {
+            // Equal-work row sets: set g starts at the first row whose work prefix
+            // W[r] = rowptr[r] + r reaches g * kWorkPerGroup.  Row r+1 is that row for
+            // every g in (W[r]/work, W[r+1]/work]; the thread of row r writes them.
+            int64_t g0 = 1, g1 = 0;   // empty
+            if (r < end) {
+                g0 = ((int64_t)e0 + r) / kWorkPerGroup + 1;
+                g1 = ((int64_t)e0 + len + r + 1) / kWorkPerGroup;
+                if (r == 0) A.split[0] = 0;
+                if (r == A.n - 1 && g1 < A.nsets) A.split[A.nsets] = (int32_t)A.n;   // partial last set
+            }
+            const bool big = g1 - g0 >= kWave;
+            if (!big)
+                for (int64_t g = g0; g <= g1; ++g) A.split[g] = (int32_t)(r + 1);
+            unsigned long long m = __ballot(big);
+            while (m) {
+                const int leader = __ffsll((long long)m) - 1;
+                const int64_t lg0 = __shfl(g0, leader, kWave), lg1 = __shfl(g1, leader, kWave);
+                const int64_t lr = __shfl(r, leader, kWave);
+                for (int64_t g = lg0 + lane; g <= lg1; g += kWave) A.split[g] = (int32_t)(lr + 1);
                 m &= m - 1;
             }
         }
@@ -358,32 +383,8 @@ __device__ __forceinline__ void row_starts(const StartsArgs &A, int b)
     }
 }
 
-// Equal-work row sets: set g starts at the first row r with rowptr[r] + r >= g * kWorkPerGroup
-// (work of a row = its edges + 1), so no lane group of the aggregation kernel gets
-// more than kWorkPerGroup units plus one row, however skewed the degrees are.
-struct SplitArgs {
-    const int32_t *rowptr;   // [n+1]
-    int64_t n, ngroups;
-    int32_t *split;          // [ngroups+1]
-    int nb;
-};
-
-__device__ __forceinline__ void work_split(const SplitArgs &A, int b)
-{
-    for (int64_t g = (int64_t)b * blockDim.x + threadIdx.x; g <= A.ngroups; g += (int64_t)A.nb * blockDim.x) {
-        const int64_t target = g * kWorkPerGroup;
-        int64_t lo = 0, hi = A.n;   // answer in [lo, hi]; rowptr[n] + n >= any target <= ngroups * work
-        while (lo < hi) {
-            const int64_t mid = lo + ((hi - lo) >> 1);
-            if ((int64_t)A.rowptr[mid] + mid >= target) hi = mid; else lo = mid + 1;
-        }
-        A.split[g] = (int32_t)lo;
-    }
-}
-
 // ------------------------------------------------------- the stage kernel ----
-enum { JOB_ROWS_COUNT = 0, JOB_ROWS_FILL = 1, JOB_SORT_HIST = 2, JOB_SORT_SCATTER = 3, JOB_ROW_STARTS = 4,
-       JOB_SPLIT = 5 };
+enum { JOB_ROWS_COUNT = 0, JOB_ROWS_FILL = 1, JOB_SORT_HIST = 2, JOB_SORT_SCATTER = 3, JOB_ROW_STARTS = 4 };
 constexpr int kMaxJobs = 16;
 
 struct Job {
@@ -392,7 +393,6 @@ struct Job {
         RowsArgs rows;
         SortArgs sort;
         StartsArgs starts;
-        SplitArgs split;
     };
 };
 
@@ -419,8 +419,7 @@ __global__ __launch_bounds__(kSortThreads) void k_plan_stage(StageArgs A)
             else if (J.sort.items == 2) sort_scatter<2>(J.sort, b, M, lds);
             else sort_scatter<4>(J.sort, b, M, lds);
             break;
-        case JOB_ROW_STARTS: row_starts(J.starts, b); break;
-        default: work_split(J.split, b); break;
+        default: row_starts(J.starts, b); break;
     }
 }
 
@@ -479,7 +478,7 @@ static int grid_for(int64_t n, int per_thread)
 
 static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, float *inv, float *rsq,
                           int32_t *counts, int32_t *long_rows, int32_t *chunk_ptr, int32_t *totals,
-                          int32_t *edge_row = nullptr)
+                          int32_t *edge_row, int32_t *split, int64_t nnz)
 {
     RowsArgs A;
     int64_t b = ceil_div(n, (int64_t)kSortThreads * 4);
@@ -490,6 +489,8 @@ static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, fl
     A.len_out = len_out; A.inv = inv; A.rsq = rsq;
     A.counts = counts; A.long_rows = long_rows; A.chunk_ptr = chunk_ptr; A.totals = totals;
     A.edge_row = edge_row;
+    A.split = split;
+    A.nsets = num_row_sets(n, nnz);
     return A;
 }
 
@@ -537,17 +538,6 @@ static void add_job(Stages &st, size_t k, const Job &j)
     st[k].push_back(j);
 }
 
-static Job split_job(const int32_t *rowptr, int64_t n, int64_t nnz, int32_t *out)
-{
-    Job j;
-    j.kind = JOB_SPLIT;
-    j.split.rowptr = rowptr; j.split.n = n; j.split.ngroups = num_row_sets(n, nnz); j.split.split = out;
-    int64_t nb = ceil_div(j.split.ngroups + 1, (int64_t)kSortThreads);
-    if (nb > 256) nb = 256;
-    j.split.nb = (int)nb; j.nblocks = (int)nb;
-    return j;
-}
-
 static Job rows_job(int kind, const RowsArgs &A)
 {
     Job j;
@@ -564,9 +554,9 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
     if (!full) parts &= ~FASTGL_PLAN_PERM;
     p->parts = parts;
     RowsArgs dstA = rows_args(p->indptr, p->num_dst, p->din, p->dst_inv, p->dst_rsqrt, p->block_sums,
-                              p->long_dst, p->chunk_ptr_dst, p->counters, full ? p->edge_dst : nullptr);
+                              p->long_dst, p->chunk_ptr_dst, p->counters, full ? p->edge_dst : nullptr,
+                              p->split_dst, p->num_edges);
     add_job(st, 0, rows_job(JOB_ROWS_COUNT, dstA));
-    add_job(st, 0, split_job(p->indptr, p->num_dst, p->num_edges, p->split_dst));
     add_job(st, 1, rows_job(JOB_ROWS_FILL, dstA));
     if (!full) return;
 
@@ -612,9 +602,9 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
     t.starts.nb = (int)nb; t.nblocks = (int)nb;
     add_job(st, 2 * npass, t);
     RowsArgs srcA = rows_args(p->indptr_T, p->num_src, p->dout, nullptr, p->src_rsqrt, p->block_sums2,
-                              p->long_src, p->chunk_ptr_src, p->counters + 2);
+                              p->long_src, p->chunk_ptr_src, p->counters + 2, nullptr, p->split_src,
+                              p->num_edges);
     add_job(st, 2 * npass + 1, rows_job(JOB_ROWS_COUNT, srcA));
-    add_job(st, 2 * npass + 1, split_job(p->indptr_T, p->num_src, p->num_edges, p->split_src));
     add_job(st, 2 * npass + 2, rows_job(JOB_ROWS_FILL, srcA));
 }
 
