@@ -32,7 +32,7 @@ METRIC = "aggregated GEdges/s (fwd+bwd) and achieved HBM GB/s vs peak, 1 MI355X"
 # reads for a plain 1 GiB copy (`--calibrate`): FETCH_SIZE counts 2 KiB units,
 # WRITE_SIZE 1 KiB units on this stack.  Summary: profiles/pull_rows_config2_traffic.md.
 # Key: (config, direction, layer).  Re-measure when the kernel's access pattern changes.
-MEASURED_TRAFFIC_BYTES = {(2, "fwd", 0): int(652526.1 * 2048 + 215011.3 * 1024)}
+MEASURED_TRAFFIC_BYTES = {(2, "fwd", 0): int(632334.8 * 2048 + 208647.1 * 1024)}
 
 
 def compulsory_bytes(rowptr_rows, nnz, used_in_rows, out_rows, feat, elem):
