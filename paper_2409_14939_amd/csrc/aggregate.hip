@@ -5,14 +5,16 @@
 //
 // Mapping to the machine.  A feature row is cut into slices of VB bytes (16 when
 // the row size allows, so one lane moves one dwordx4) and a "group" of G lanes
-// (a power of two, <= 64) covers G consecutive slices.  One group owns one
-// (row, column tile) unit from start to end, so each output element has a single
-// writer and the summation order is fixed: results do not depend on scheduling.
+// (a power of two, <= 64) covers G consecutive slices.  One group owns a set of
+// consecutive rows (x one column tile) from start to end, so each output element
+// has a single writer and the summation order is fixed: results do not depend on
+// scheduling.  The row sets come from the plan and carry equal work (edges +
+// rows), so skewed degree distributions do not overload a group.
 // The partial sum lives in registers (the paper keeps it in shared memory on its
 // GPU; with one lane per slice registers serve the same purpose at no traffic).
-// The lanes of a group fetch the row's column ids and weights with one coalesced
-// load and hand them round with cross-lane reads, then issue up to 8 independent
-// row gathers before the first use.
+// The lanes of a group fetch column ids and weights with one coalesced load and
+// hand them round with cross-lane reads, then issue up to 6 independent row
+// gathers before the first use.  Output rows leave with streaming stores.
 //
 // f32 rows accumulate in fp64, bf16 rows in fp32; one rounding at the store.
 //
@@ -20,8 +22,6 @@
 // cut into chunks of kLongChunk edges that any group can take (in the same
 // launch); the partial sums go to the workspace and are added in chunk order by
 // a second, small kernel, so the result is still deterministic.
-#include <stdlib.h>
-
 #include "internal.h"
 
 namespace fastgl {
@@ -394,12 +394,6 @@ __global__ __launch_bounds__(kBlock) void k_gather_rows(const char *__restrict__
 }
 
 // ------------------------------------------------------------- host side ----
-static int tune(const char *name, int dflt)   // development knob
-{
-    const char *v = getenv(name);
-    return v ? atoi(v) : dflt;
-}
-
 // Largest slice width (bytes) that divides the row size and the buffer alignment.
 static int pick_slice_bytes(int64_t row_bytes, const void *a, const void *b, int elem)
 {
@@ -451,10 +445,6 @@ fastgl_status launch_pull(const PullDesc &d, hipStream_t s)
     const int vb = pick_slice_bytes(P.row_bytes, d.in, d.out, elem);
     int G, ntiles;
     group_shape(P.row_bytes, vb, &G, &ntiles);
-    if (tune("FASTGL_G", 0) > 0 && tune("FASTGL_G", 0) < G) {   // development knob: narrower groups, more tiles
-        ntiles = ntiles * G / tune("FASTGL_G", 0);
-        G = tune("FASTGL_G", 0);
-    }
     P.G = G; P.ntiles = ntiles;
     P.num_rows = d.num_rows;
     P.split = d.split;
@@ -463,14 +453,14 @@ fastgl_status launch_pull(const PullDesc &d, hipStream_t s)
     // column-id latency over more gathers while keeping >= ~16K groups in flight
     int spg = 1;
     while (spg < 8 && (d.nsets / (spg * 2)) * G * ntiles / kWave >= 16384) spg *= 2;
-    P.sets_per_group = tune("FASTGL_SPG", spg);
+    P.sets_per_group = spg;
     P.ngroups = ceil_div(d.nsets, P.sets_per_group);
     const bool with_long = d.long_rows != nullptr;
     P.long_thr = with_long ? kLongThreshold : INT32_MAX;
     P.long_rows = d.long_rows; P.chunk_ptr = d.chunk_ptr; P.n_long = d.n_long; P.n_chunks = d.n_chunks;
     P.partials = (char *)d.partials;
     const int gpb = kBlock / G;
-    P.xcd_run = tune("FASTGL_XCD_RUN", kXcdRun);
+    P.xcd_run = kXcdRun;
     P.num_blocks = ceil_div(ceil_div(P.ngroups * ntiles, gpb), (int64_t)kXcds * P.xcd_run) * P.xcd_run * kXcds;
     const int64_t nblocks = P.num_blocks;
     if (P.num_blocks > 0x7FFFFFFFLL) {

@@ -1,6 +1,6 @@
 // Per-block integer bookkeeping on the GPU: degrees, scale factors, a stable
-// transpose of the CSR (LSD radix sort of (source id, edge id)), and degree
-// buckets (ordered compaction of long rows).  Everything is integer work with
+// transpose of the CSR (LSD radix sort of the edges by source id), equal-work row
+// sets and degree buckets (ordered compaction of long rows).  Everything is integer work with
 // a single valid answer: no float atomics, no order-dependent results, and (on
 // the full-plan path) no global atomics at all.
 //
@@ -12,11 +12,12 @@
 // sequence of STAGES; stage k of every plan built in one call shares one launch
 // of k_plan_stage, whose workgroups look up which job they belong to:
 //
-//   stage 0        digit histogram of pass 0    + destination-side row count
+//   stage 0        digit histogram of pass 0    + destination-side row pass (degrees,
+//                  scale factors, edge -> row expansion, equal-work split, bucket counts)
 //   stage 1        stable scatter of pass 0     + destination-side bucket fill
 //   stage 2p,2p+1  histogram / scatter of radix pass p (8-bit digits)
 //   then           row starts (indptr_T from the sorted keys),
-//                  source-side row count, source-side bucket fill
+//                  source-side row pass, source-side bucket fill
 //
 // A full plan with a 3-pass sort is 9 launches, and so are the plans of all
 // layers of a mini-batch when they are built together.
