@@ -214,6 +214,63 @@ def test_gather_rows():
         assert np.array_equal(host_feat(got, dtype), oracle.gather_rows(T, ids, dtype))
 
 
+def test_random_small_blocks():
+    """Seeded sweep over odd shapes: widths that force 2-, 4- and 8-byte slices, both dtypes,
+    all modes, weights on and off, with and without a plan, tiny to multi-workgroup blocks."""
+    rng = np.random.default_rng(2024)
+    for case in range(48):
+        nd = int(rng.integers(1, 400))
+        ns = int(rng.integers(1, 900))
+        feat = int(rng.choice([1, 2, 5, 7, 9, 17, 31, 33, 50, 66, 96, 130, 257]))
+        blk = bg.random_block(rng, nd, ns, float(rng.uniform(0.5, 12.0)), empty_frac=float(rng.uniform(0, 0.5)),
+                              hub_rows=int(rng.integers(0, 3)), hub_deg=int(rng.integers(200, 700)))
+        check_block(blk, MODES[case % 3], "f32" if case % 2 else "bf16", feat, bool(rng.integers(0, 2)),
+                    bool(rng.integers(0, 2)), 5000 + case, f"random-{case}")
+
+
+def test_capture_in_hip_graph_and_replay():
+    """Plan build + forward + backward allocate nothing and never synchronise, so the whole
+    step can be captured in a HIP graph; every replay must equal the eager result bit for bit."""
+    blk = ragged_block()
+    rng = np.random.default_rng(77)
+    feat = 100
+    ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
+    X = dev_feat(make_inputs(rng, blk.num_src, feat, "f32"), "f32")
+    G = dev_feat(make_inputs(rng, blk.num_dst, feat, "f32"), "f32")
+    out, dX = torch.empty(blk.num_dst, feat, device="cuda"), torch.empty(blk.num_src, feat, device="cuda")
+    pm = torch.empty(B.fastgl_block_plan_bytes(blk.num_dst, blk.num_src, blk.num_edges), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.fastgl_block_workspace_bytes(blk.num_dst, blk.num_src, blk.num_edges, feat, "f32"),
+                     dtype=torch.uint8, device="cuda")
+
+    def step():
+        plan = B.fastgl_block_plan_create(ip, ix, blk.num_src, B.PLAN_ALL, pm)
+        B.fastgl_block_aggregate_fwd(ip, ix, None, blk.num_src, "gcn", X, out=out, plan=plan, workspace=ws)
+        B.fastgl_block_aggregate_bwd(ip, ix, None, blk.num_src, "gcn", G, grad_X=dX, plan=plan, workspace=ws)
+        return plan
+
+    step()
+    torch.cuda.synchronize()
+    ref_out, ref_dX = out.clone(), dX.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            keep = step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        out.fill_(float("nan"))
+        dX.fill_(float("nan"))
+        pm.random_(0, 255)                       # eager work between replays; the plan is rebuilt by the graph
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref_out) and torch.equal(dX, ref_dX), f"replay {rep}"
+    del keep
+
+
 # ---- the five workloads at full size --------------------------------------------------
 def check_workload(w, layers=None):
     for li, (blk, feat) in enumerate(zip(w.blocks, w.widths)):

@@ -305,3 +305,18 @@ def test_parallel_variant_matches_definitional(mode, dtype):
     a = oracle.aggregate_bwd(blk.indptr, blk.indices, w, blk.num_src, mode, dtype, G)
     b = oracle.par_aggregate_bwd(blk.indptr, blk.indices, w, blk.num_src, mode, dtype, G)
     np.testing.assert_allclose(cv(b), cv(a), **tol)
+
+
+def test_paper_traffic_model_bytes():
+    """Eq. 3 / Eq. 4 numerators (Section 4.2): partial sums read |N|-1 times, weights, features."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "eq3_eq4_bytes.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        n, d, naive, ma_s, ma_g = map(int, line.split())
+        assert 4 * (n - 1) * d + 4 * n * d + 4 * n * d == naive
+        assert 4 * (n - 1) * d + 4 * n * (d - 1) == ma_s
+        assert 4 * n * d + 4 * n == ma_g
+        # the feature bytes alone are what this build calls "gathered bytes" for one row
+        assert 4 * n * d <= ma_g
