@@ -1,11 +1,12 @@
-"""ctypes front end of the CPU oracle (oracle/fastgl_oracle.c).
+"""ctypes front end of the CPU oracle (oracle/fastgl_oracle.c, oracle/update_oracle.c).
 
 TEST INFRASTRUCTURE ONLY.  Only tests/, the smoke check and the benchmark's
 cpu_baseline leg may import this package; the product path never does.  It
 works on host numpy arrays and imports nothing from the GPU package.
 
 Formulas: paper Section 2.1 Eq. 1 (forward) and Section 4.2 Eq. 5 (backward,
-read as the transpose of Eq. 1 applied to the upstream gradient).
+read as the transpose of Eq. 1 applied to the upstream gradient); Section 2.1
+Eq. 2 (update phase, read as the GCN dense transform act(H W + b)).
 """
 from __future__ import annotations
 
@@ -17,6 +18,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fastgl_oracle.c")
+_SRCS = [_SRC, os.path.join(_HERE, "update_oracle.c")]
 _LIB = os.path.join(_HERE, "libfastgl_oracle.so")
 
 MODES = {"sum": 0, "mean": 1, "gcn": 2}
@@ -25,9 +27,10 @@ DTYPES = {"f32": 0, "bf16": 1}
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (generic x86-64 so the .so runs on any host)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if (force or not os.path.exists(_LIB)
+            or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+               "-Wall", "-Wextra", "-o", _LIB, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -59,6 +62,10 @@ def lib():
         L.fastgl_oracle_double_to_bf16.argtypes = [ctypes.c_double]
         L.fastgl_oracle_double_to_bf16.restype = ctypes.c_uint16
         L.fastgl_oracle_num_threads.restype = i32
+        L.fastgl_oracle_update_fwd.argtypes = [p, p, p, i64, i64, i64, i32, p]
+        L.fastgl_oracle_update_fwd.restype = i32
+        L.fastgl_oracle_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p]
+        L.fastgl_oracle_update_bwd.restype = i32
         _lib = L
     return _lib
 
@@ -173,3 +180,39 @@ def double_to_bf16(x: float) -> int:
 
 def num_threads() -> int:
     return int(lib().fastgl_oracle_num_threads())
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def update_fwd(H, W, b, relu):
+    """Y = act(H W + b); H [M,K], W [K,N], b [N] or None (Section 2.1, Eq. 2)."""
+    H, W = _f32(H), _f32(W)
+    b = None if b is None else _f32(b)
+    M, K = H.shape
+    assert W.shape[0] == K and (b is None or b.shape == (W.shape[1],))
+    Y = np.empty((M, W.shape[1]), np.float32)
+    rc = lib().fastgl_oracle_update_fwd(_ptr(H), _ptr(W), _ptr(b), M, K, W.shape[1], int(bool(relu)), _ptr(Y))
+    if rc:
+        raise RuntimeError(f"oracle returned {rc}")
+    return Y
+
+
+def update_bwd(H, W, Y, dY, relu, want=("dH", "dW", "db")):
+    """Gradients of Eq. 2's dense transform; returns (dH, dW, db), None for parts not wanted.
+    Y is the forward output and gates dY where relu is set."""
+    H, W, dY = _f32(H), _f32(W), _f32(dY)
+    Y = None if Y is None else _f32(Y)
+    assert not relu or Y is not None
+    M, K = H.shape
+    N = W.shape[1]
+    assert dY.shape == (M, N) and W.shape[0] == K
+    dH = np.empty((M, K), np.float32) if "dH" in want else None
+    dW = np.empty((K, N), np.float32) if "dW" in want else None
+    db = np.empty(N, np.float32) if "db" in want else None
+    rc = lib().fastgl_oracle_update_bwd(_ptr(H), _ptr(W), _ptr(Y), _ptr(dY), M, K, N, int(bool(relu)),
+                                        _ptr(dH), _ptr(dW), _ptr(db))
+    if rc:
+        raise RuntimeError(f"oracle returned {rc}")
+    return dH, dW, db
