@@ -1,0 +1,63 @@
+/*
+ * fastgl_update.h - C ABI of the update phase of a sampled GCN layer on MI355X
+ * (gfx950), the dense step that follows neighbour aggregation.
+ *
+ * Paper Section 2.1, Eq. 2: the aggregated features h_u of every target node
+ * are transformed into the layer output x_u^{k+1} = Update(h_u).  For the GCN
+ * of the evaluation (Section 6.1) Update is the dense transform
+ *
+ *   forward   Y = act(H W + b)            act = identity or ReLU
+ *   backward  dZ = dY (.) [Y > 0]         (all of dY for the identity)
+ *             dH = dZ W^T,  dW = H^T dZ,  db = column sums of dZ
+ *
+ * H [M,K], W [K,N], Y/dY [M,N], dH [M,K], dW [K,N], b/db [N]: dense row-major
+ * fp32 with no padding between rows.  Products run on the fp32 matrix cores
+ * (v_mfma_f32_32x32x2_f32): fp32 multiply, fp32 accumulate.  dW and db are
+ * reduced over fixed slabs of rows whose partial results are summed in slab
+ * order in fp64, so results do not depend on scheduling.
+ *
+ * Conventions are those of fastgl_agg.h: every array is DEVICE memory owned by
+ * the caller, the library allocates nothing, work is enqueued on `stream`
+ * (hipStream_t as void*, NULL = default stream) without synchronising the host,
+ * outputs are overwritten in full and must not overlap inputs, and everything
+ * checkable on the host is checked before any launch (fastgl_last_error() has
+ * the text).  M, K, N >= 0 and < 2^31; M == 0 or N == 0 writes nothing; K == 0
+ * gives Y = act(b).
+ */
+#ifndef FASTGL_UPDATE_H
+#define FASTGL_UPDATE_H
+
+#include "fastgl_agg.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Eq. 2 forward: Y = act(H W + bias).  bias may be NULL (no bias term);
+ * relu != 0 selects ReLU, 0 the identity. */
+fastgl_status fastgl_update_fwd(const float *H, const float *W, const float *bias,
+                                int64_t M, int64_t K, int64_t N, int relu,
+                                float *Y, void *stream);
+
+/* Bytes of device workspace fastgl_update_bwd needs for the slab partials of
+ * dW and db (0 when neither is requested is not assumed: this is the bound for
+ * the full call). */
+size_t fastgl_update_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/* Eq. 2 backward.  Y is the forward OUTPUT and is read only when relu != 0
+ * (it may be NULL otherwise).  Any of dH, dW, db may be NULL to skip that
+ * result; dW and db need `workspace` (256-byte aligned, at least
+ * fastgl_update_bwd_workspace_bytes(M,K,N) bytes), dH alone does not. */
+fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, const float *dY,
+                                int64_t M, int64_t K, int64_t N, int relu,
+                                float *dH, float *dW, float *db,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Rows of H per dW/db slab (the length of the longest fp32 accumulation chain
+ * of the backward pass). */
+int32_t fastgl_update_slab_rows(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTGL_UPDATE_H */

@@ -25,6 +25,7 @@ EXPORTS = [
     "fastgl_block_plan_create", "fastgl_block_plan_create_many", "fastgl_block_plan_export", "fastgl_block_plan_destroy",
     "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk", "fastgl_work_per_group",
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
+    "fastgl_update_fwd", "fastgl_update_bwd", "fastgl_update_bwd_workspace_bytes", "fastgl_update_slab_rows",
 ]
 
 
@@ -74,6 +75,11 @@ def lib() -> ctypes.CDLL:
         L.fastgl_gather_rows.argtypes = [p, i64, p, i64, i64, i32, p, p]
         L.fastgl_block_validate.argtypes = [p, p, i64, i64, i64, p, ctypes.POINTER(i64), p]
         L.fastgl_last_error.restype = ctypes.c_char_p
+        L.fastgl_update_fwd.argtypes = [p, p, p, i64, i64, i64, i32, p, p]
+        L.fastgl_update_bwd_workspace_bytes.argtypes = [i64, i64, i64]
+        L.fastgl_update_bwd_workspace_bytes.restype = sz
+        L.fastgl_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p, p, sz, p]
+        L.fastgl_update_slab_rows.restype = ctypes.c_int32
         _lib = L
     return _lib
 
@@ -247,3 +253,60 @@ def fastgl_block_validate(indptr: torch.Tensor, indices: torch.Tensor, num_src: 
     _check(lib().fastgl_block_validate(_ptr(indptr), _ptr(indices), indptr.numel() - 1, num_src,
                                        indices.numel(), _ptr(scratch), ctypes.byref(n), _stream()))
     return int(n.value)
+
+
+def fastgl_update_slab_rows() -> int:
+    return int(lib().fastgl_update_slab_rows())
+
+
+def fastgl_update_bwd_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(lib().fastgl_update_bwd_workspace_bytes(M, K, N))
+
+
+def fastgl_update_fwd(H: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], relu: bool,
+                      Y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(H, torch.float32, "H")
+    _dev(W, torch.float32, "W")
+    (M, K), N = H.shape, W.shape[1]
+    if W.shape[0] != K or (bias is not None and bias.shape != (N,)):
+        raise ValueError("W must be [K,N] and bias [N]")
+    if bias is not None:
+        _dev(bias, torch.float32, "bias")
+    if Y is None:
+        Y = torch.empty((M, N), dtype=torch.float32, device=H.device)
+    elif Y.shape != (M, N):
+        raise ValueError("Y must be [M,N]")
+    _dev(Y, torch.float32, "Y")
+    _check(lib().fastgl_update_fwd(_ptr(H), _ptr(W), _ptr(bias), M, K, N, int(bool(relu)), _ptr(Y), _stream()))
+    return Y
+
+
+def fastgl_update_bwd(H: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor], dY: torch.Tensor, relu: bool,
+                      want=("dH", "dW", "db"), dH=None, dW=None, db=None,
+                      workspace: Optional[torch.Tensor] = None):
+    """Returns (dH, dW, db); parts not named in `want` (and not passed in) are None."""
+    _dev(H, torch.float32, "H")
+    _dev(W, torch.float32, "W")
+    _dev(dY, torch.float32, "dY")
+    if Y is not None:
+        _dev(Y, torch.float32, "Y")
+    (M, K), N = H.shape, W.shape[1]
+    if W.shape[0] != K or dY.shape != (M, N) or (Y is not None and Y.shape != (M, N)):
+        raise ValueError("shapes must be H [M,K], W [K,N], Y and dY [M,N]")
+    if dH is None and "dH" in want:
+        dH = torch.empty((M, K), dtype=torch.float32, device=H.device)
+    if dW is None and "dW" in want:
+        dW = torch.empty((K, N), dtype=torch.float32, device=H.device)
+    if db is None and "db" in want:
+        db = torch.empty((N,), dtype=torch.float32, device=H.device)
+    for t, shape, name in ((dH, (M, K), "dH"), (dW, (K, N), "dW"), (db, (N,), "db")):
+        if t is not None:
+            _dev(t, torch.float32, name)
+            if tuple(t.shape) != shape:
+                raise ValueError(f"{name} must have shape {shape}")
+    if workspace is None:
+        workspace = torch.empty(max(fastgl_update_bwd_workspace_bytes(M, K, N), 256), dtype=torch.uint8,
+                                device=H.device)
+    _check(lib().fastgl_update_bwd(_ptr(H), _ptr(W), _ptr(Y), _ptr(dY), M, K, N, int(bool(relu)), _ptr(dH),
+                                   _ptr(dW), _ptr(db), _ptr(workspace), workspace.numel(), _stream()))
+    return dH, dW, db

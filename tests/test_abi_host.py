@@ -12,7 +12,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "fastgl_agg.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read()
+                   for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(fastgl_[a-z_]+)\s*\(", text)))
 
@@ -78,3 +79,26 @@ def test_plan_and_gather_argument_checks():
     assert L.fastgl_gather_rows(None, 10, FAKE, 3, 8, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
     n = ctypes.c_int64()
     assert L.fastgl_block_validate(FAKE, FAKE, 4, 4, 4, None, ctypes.byref(n), None) == B.FASTGL_ERR_INVALID_ARG
+
+
+def test_update_argument_checks():
+    L = B.lib()
+    assert B.fastgl_update_slab_rows() > 0
+    assert B.fastgl_update_bwd_workspace_bytes(-1, 4, 4) == 0
+    one = B.fastgl_update_bwd_workspace_bytes(B.fastgl_update_slab_rows(), 100, 256)
+    assert one >= 4 * (100 * 256 + 256)
+    assert B.fastgl_update_bwd_workspace_bytes(B.fastgl_update_slab_rows() + 1, 100, 256) >= 2 * one - 256
+    assert L.fastgl_update_fwd(FAKE, FAKE, None, -1, 4, 4, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "negative" in B.fastgl_last_error()
+    assert L.fastgl_update_fwd(FAKE, FAKE, None, 2 ** 31, 4, 4, 0, FAKE, None) == B.FASTGL_ERR_UNSUPPORTED
+    assert L.fastgl_update_fwd(None, FAKE, None, 4, 4, 4, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert L.fastgl_update_fwd(FAKE, FAKE, None, 4, 4, 4, 0, ctypes.c_void_p(0x1002), None) == B.FASTGL_ERR_INVALID_ARG
+    assert L.fastgl_update_fwd(FAKE, FAKE, None, 0, 4, 4, 0, None, None) == B.FASTGL_OK      # nothing to do
+    bwd = L.fastgl_update_bwd
+    assert bwd(FAKE, FAKE, None, FAKE, 4, 4, 4, 1, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "relu" in B.fastgl_last_error()
+    assert bwd(FAKE, FAKE, FAKE, None, 4, 4, 4, 0, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert bwd(FAKE, FAKE, FAKE, FAKE, 4, 4, 4, 0, None, FAKE, None, None, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "workspace" in B.fastgl_last_error()
+    assert bwd(FAKE, FAKE, FAKE, FAKE, 4, 4, 4, 0, None, FAKE, None, FAKE, 8, None) == B.FASTGL_ERR_WORKSPACE
+    assert bwd(FAKE, FAKE, FAKE, FAKE, 4, 4, 4, 0, None, None, None, None, 0, None) == B.FASTGL_OK   # nothing asked

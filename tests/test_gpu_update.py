@@ -1,0 +1,165 @@
+"""GPU parity of the update phase (paper Section 2.1, Eq. 2: Y = act(H W + b) and its gradients)
+against the CPU oracle, through the C ABI.
+
+Tolerance (derived from the arithmetic, not tuned): the kernels multiply and accumulate in fp32 on
+the matrix cores; the oracle sums in fp64 and rounds once.  For a chain of L fp32 accumulations
+the textbook bound is |err| <= (L+2) u sum_k |a_k b_k| + u |ref| with u = 2^-24, whatever the
+order of the sum.  L is the contracted length (K for Y, N for dH) and the slab height for dW / db,
+whose slab partials are added in fp64.  That bound is checked element by element; because it is
+loose (it is a worst case), the root-mean-square error is also checked against the random-walk
+estimate 2 u sqrt(L) rms(ref), which a wrong or dropped term breaks by orders of magnitude."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2409_14939_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+U = 2.0 ** -24
+
+
+def dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def check(got, ref, absprod, L, what):
+    got, ref = got.astype(np.float64), ref.astype(np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    err = np.abs(got - ref)
+    lim = (L + 2) * U * absprod + U * np.abs(ref) + 1e-30
+    bad = err > lim
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - lim), err.shape)
+        raise AssertionError(f"{what}: {bad.sum()} of {bad.size} beyond the rounding bound; worst at {i}: "
+                             f"got {got[i]!r} ref {ref[i]!r} bound {lim[i]!r}")
+    rms_ref = np.sqrt(np.mean(ref ** 2))
+    rms_err = np.sqrt(np.mean(err ** 2))
+    assert rms_err <= 2 * U * np.sqrt(max(L, 1)) * rms_ref + 1e-30, (what, rms_err, rms_ref)
+
+
+def run_case(M, K, N, relu, bias, seed, what):
+    rng = np.random.default_rng(seed)
+    H = rng.standard_normal((M, K)).astype(np.float32)
+    W = (rng.standard_normal((K, N)) / np.sqrt(max(K, 1))).astype(np.float32)
+    b = rng.standard_normal(N).astype(np.float32) if bias else None
+    dY = rng.standard_normal((M, N)).astype(np.float32)
+    print(f"case {what} M={M} K={K} N={N} relu={relu} bias={bias}", flush=True)
+    Hd, Wd = dev(H), dev(W)
+    Yd = B.fastgl_update_fwd(Hd, Wd, dev(b), relu)
+    dHd, dWd, dbd = B.fastgl_update_bwd(Hd, Wd, Yd if relu else None, dev(dY), relu)
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+
+    aH, aW = np.abs(H).astype(np.float64), np.abs(W).astype(np.float64)
+    Yref = oracle.update_fwd(H, W, b, relu)
+    check(Y, Yref, aH @ aW + (0 if b is None else np.abs(b)), K + 1, what + " Y")
+    # The backward pass is gated by the forward OUTPUT.  Both sides get the oracle's Y where the two
+    # forward results disagree about the sign of an element (possible only within the rounding bound
+    # of zero); otherwise each side uses its own.
+    if relu:
+        flips = (Y > 0) != (Yref > 0)
+        assert flips.sum() <= 1e-4 * Y.size + 2, flips.sum()
+        if flips.any():
+            dHd, dWd, dbd = B.fastgl_update_bwd(Hd, Wd, dev(Yref), dev(dY), relu)
+            torch.cuda.synchronize()
+    dHr, dWr, dbr = oracle.update_bwd(H, W, Yref if relu else None, dY, relu)
+    dZ = np.abs(dY).astype(np.float64) * ((Yref > 0) if relu else 1.0)
+    slab = B.fastgl_update_slab_rows()
+    check(dHd.cpu().numpy(), dHr, dZ @ aW.T, N, what + " dH")
+    check(dWd.cpu().numpy(), dWr, aH.T @ dZ, min(M, slab), what + " dW")
+    check(dbd.cpu().numpy(), dbr, dZ.sum(axis=0), min(M, slab), what + " db")
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("M,K,N", [
+    (300, 100, 256),      # the input layer's widths, ragged row tail
+    (1500, 256, 256),     # two slabs, three row tiles
+    (2500, 256, 47),      # class scores: N not a multiple of 4 (scalar loads), three slabs
+    (257, 17, 130),       # nothing aligned
+    (129, 1, 1), (1, 40, 5), (64, 8, 128), (1024, 32, 32), (1025, 36, 260),
+])
+def test_update_parity(M, K, N, relu):
+    run_case(M, K, N, relu, bias=(N % 2 == 0), seed=M + 7 * K + 13 * N, what="update")
+
+
+def test_update_degenerate():
+    # K = 0: Y = act(b); M = 0: gradients of the weights are zero; N = 0: dH is zero
+    b = np.array([-1.0, 2.0, 0.5], np.float32)
+    H0 = torch.empty((5, 0), dtype=torch.float32, device="cuda")
+    W0 = torch.empty((0, 3), dtype=torch.float32, device="cuda")
+    print("case update degenerate K=0", flush=True)
+    Y = B.fastgl_update_fwd(H0, W0, dev(b), True)
+    torch.cuda.synchronize()
+    assert np.array_equal(Y.cpu().numpy(), np.tile(np.maximum(b, 0), (5, 1)))
+    dY = np.arange(15, dtype=np.float32).reshape(5, 3)
+    dH, dW, db = B.fastgl_update_bwd(H0, W0, Y, dev(dY), True)
+    torch.cuda.synchronize()
+    assert dH.shape == (5, 0) and dW.shape == (0, 3)
+    assert np.array_equal(db.cpu().numpy(), np.array([0, dY[:, 1].sum(), dY[:, 2].sum()], np.float32))
+    print("case update degenerate M=0", flush=True)
+    He = torch.empty((0, 4), dtype=torch.float32, device="cuda")
+    Wd = dev(np.ones((4, 3), np.float32))
+    Ye = B.fastgl_update_fwd(He, Wd, None, False)
+    dH, dW, db = B.fastgl_update_bwd(He, Wd, None, torch.empty((0, 3), dtype=torch.float32, device="cuda"), False)
+    torch.cuda.synchronize()
+    assert Ye.shape == (0, 3) and not dW.cpu().numpy().any() and not db.cpu().numpy().any()
+    print("case update degenerate N=0", flush=True)
+    Hn = dev(np.ones((6, 4), np.float32))
+    Wn = torch.empty((4, 0), dtype=torch.float32, device="cuda")
+    dH, dW, db = B.fastgl_update_bwd(Hn, Wn, None, torch.empty((6, 0), dtype=torch.float32, device="cuda"), False)
+    torch.cuda.synchronize()
+    assert dH.shape == (6, 4) and not dH.cpu().numpy().any()
+
+
+def test_update_partial_requests_and_determinism():
+    rng = np.random.default_rng(3)
+    M, K, N = 2100, 100, 256
+    H, W = dev(rng.standard_normal((M, K))), dev(rng.standard_normal((K, N)) / 10)
+    dY = dev(rng.standard_normal((M, N)))
+    print("case update partial requests", flush=True)
+    Y = B.fastgl_update_fwd(H, W, None, True)
+    full = B.fastgl_update_bwd(H, W, Y, dY, True)
+    only_h = B.fastgl_update_bwd(H, W, Y, dY, True, want=("dH",))
+    only_w = B.fastgl_update_bwd(H, W, Y, dY, True, want=("dW",))
+    only_b = B.fastgl_update_bwd(H, W, Y, dY, True, want=("db",))
+    again = B.fastgl_update_bwd(H, W, Y, dY, True)
+    torch.cuda.synchronize()
+    assert only_h[1] is None and only_h[2] is None and only_w[0] is None and only_b[1] is None
+    assert torch.equal(full[0], only_h[0]) and torch.equal(full[1], only_w[1]) and torch.equal(full[2], only_b[2])
+    for a, b in zip(full, again):          # fixed slabs, fixed order: bit-identical from run to run
+        assert torch.equal(a, b)
+
+
+def test_update_full_size_sampled():
+    """The products-shaped input layer (M = 512 345 rows, 100 -> 256) in the launch shape the
+    benchmark times; the oracle computes sampled rows of Y and dH and sampled columns of dW, db."""
+    rng = np.random.default_rng(11)
+    M, K, N = 512345, 100, 256
+    H = rng.standard_normal((M, K), dtype=np.float32)
+    W = (rng.standard_normal((K, N)) / 10).astype(np.float32)
+    b = rng.standard_normal(N).astype(np.float32)
+    dY = rng.standard_normal((M, N), dtype=np.float32)
+    print(f"case update full size M={M} K={K} N={N}", flush=True)
+    Hd, Wd, dYd = dev(H), dev(W), dev(dY)
+    Yd = B.fastgl_update_fwd(Hd, Wd, dev(b), True)
+    dHd, dWd, dbd = B.fastgl_update_bwd(Hd, Wd, Yd, dYd, True)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([rng.integers(0, M, 600), [0, 127, 128, M - 2, M - 1]]))
+    aW = np.abs(W).astype(np.float64)
+    Y = Yd.cpu().numpy()
+    Yref = oracle.update_fwd(H[rows], W, b, True)
+    check(Y[rows], Yref, np.abs(H[rows]).astype(np.float64) @ aW + np.abs(b), K + 1, "full Y")
+    Ygate = Y[rows]                        # gate the oracle with the GPU's own forward output
+    dHr, _, _ = oracle.update_bwd(H[rows], W, Ygate, dY[rows], True, want=("dH",))
+    dZ = np.abs(dY[rows]).astype(np.float64) * (Ygate > 0)
+    check(dHd.cpu().numpy()[rows], dHr, dZ @ aW.T, N, "full dH")
+    cols = np.array([0, 1, 63, 64, 127, 128, 200, 255])
+    Yc, dYc = np.ascontiguousarray(Y[:, cols]), np.ascontiguousarray(dY[:, cols])
+    _, dWr, dbr = oracle.update_bwd(H, np.ascontiguousarray(W[:, cols]), Yc, dYc, True, want=("dW", "db"))
+    dZc = np.abs(dYc).astype(np.float64) * (Yc > 0)
+    slab = B.fastgl_update_slab_rows()
+    check(dWd.cpu().numpy()[:, cols], dWr, np.abs(H).astype(np.float64).T @ dZc, slab, "full dW")
+    check(dbd.cpu().numpy()[cols], dbr, dZc.sum(axis=0), slab, "full db")
