@@ -21,8 +21,8 @@
  * (hipStream_t as void*, NULL = default stream) without synchronising the host,
  * outputs are overwritten in full and must not overlap inputs, and everything
  * checkable on the host is checked before any launch (fastgl_last_error() has
- * the text).  M, K, N >= 0 and < 2^31; M == 0 or N == 0 writes nothing; K == 0
- * gives Y = act(b).
+ * the text).  0 <= M < 2^31-1, 0 <= K, N < 2^24; M == 0 or N == 0 writes
+ * nothing in the forward pass; K == 0 gives Y = act(b).
  */
 #ifndef FASTGL_UPDATE_H
 #define FASTGL_UPDATE_H
@@ -53,9 +53,10 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
                                 float *dH, float *dW, float *db,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
-/* Rows of H per dW/db slab (the length of the longest fp32 accumulation chain
- * of the backward pass). */
-int32_t fastgl_update_slab_rows(void);
+/* Rows of H per dW/db slab for this shape (the length of the longest fp32
+ * accumulation chain of the backward pass): a function of M, K, N alone,
+ * between 128 and 1024; 0 for negative sizes. */
+int32_t fastgl_update_slab_rows(int64_t M, int64_t K, int64_t N);
 
 #ifdef __cplusplus
 }

@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
         L.fastgl_update_bwd_workspace_bytes.argtypes = [i64, i64, i64]
         L.fastgl_update_bwd_workspace_bytes.restype = sz
         L.fastgl_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p, p, sz, p]
+        L.fastgl_update_slab_rows.argtypes = [i64, i64, i64]
         L.fastgl_update_slab_rows.restype = ctypes.c_int32
         _lib = L
     return _lib
@@ -255,8 +256,8 @@ def fastgl_block_validate(indptr: torch.Tensor, indices: torch.Tensor, num_src: 
     return int(n.value)
 
 
-def fastgl_update_slab_rows() -> int:
-    return int(lib().fastgl_update_slab_rows())
+def fastgl_update_slab_rows(M: int, K: int, N: int) -> int:
+    return int(lib().fastgl_update_slab_rows(M, K, N))
 
 
 def fastgl_update_bwd_workspace_bytes(M: int, K: int, N: int) -> int:

@@ -19,11 +19,21 @@ namespace fastgl {
 namespace {
 
 constexpr int kTile = 128;              // rows and columns of a workgroup's result tile
-constexpr int kStep = 32;               // contracted indices per LDS stage
+#ifndef FASTGL_UPD_STEP
+#define FASTGL_UPD_STEP 32
+#endif
+#ifndef FASTGL_UPD_BUFFERS
+#define FASTGL_UPD_BUFFERS 1
+#endif
+constexpr int kStep = FASTGL_UPD_STEP;  // contracted indices per LDS stage
+constexpr int kBuffers = FASTGL_UPD_BUFFERS;
+constexpr int kLoads = kStep / 8;       // 16-byte loads per thread and operand tile
 constexpr int kRowStride = kStep + 4;   // floats between rows of a "row" operand in LDS
 constexpr int kColStride = kTile + 8;   // floats between contracted indices of a "col" operand
 constexpr int kOperandFloats = (kTile * kRowStride > kStep * kColStride) ? kTile * kRowStride : kStep * kColStride;
-constexpr int kSlabRows = 1024;         // rows of H per dW / db partial
+constexpr int kMaxSlabRows = 1024;      // most rows of H per dW / db partial
+constexpr int kMinSlabRows = 128;
+constexpr int kSlabFill = 640;          // workgroups wanted before slabs stop shrinking
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -31,7 +41,6 @@ struct Operand {
     const float *p;       // element (out o, contracted k) at p[o*ld + k] ("row") or p[k*ld + o] ("col")
     const float *gate;    // same layout, or NULL; where gate <= 0 the element reads as 0 (ReLU derivative)
     int64_t ld;
-    int vec;              // 16-byte loads allowed: ld % 4 == 0 and p, gate 16-byte aligned
 };
 
 struct GemmArgs {
@@ -49,75 +58,122 @@ struct GemmArgs {
     int64_t colsum_slab;
 };
 
-__device__ __forceinline__ float4 load4(const Operand &op, int64_t off, int nvalid)
+// A quad = four consecutive elements p[off..off+3] of which the first `nvalid` exist; the rest must
+// read as 0.  Loading and masking are split so that the loads of the next stage stay in flight
+// during the MFMAs of the current one: load_quad only issues loads (no control flow around them - a
+// load behind a branch is waited for at the join - and no arithmetic on the result); an element
+// that does not exist is loaded from offset 0, which the host guarantees to be readable.
+// mask_quad, called when the registers are written to LDS, zeroes what does not exist or is gated
+// off.  VEC: one 16-byte load; the host selects it only when every extent is a multiple of 4, so
+// nvalid is 0 or 4.
+template <bool GATE>
+struct Quad {
+    float4 v;
+    float4 g[GATE ? 1 : 0];
+};
+
+// `base` is uniform over the workgroup (the tile's origin), `off` a per-lane 32-bit element offset.
+template <bool VEC, bool GATE>
+__device__ __forceinline__ void load_quad(const float *__restrict__ base, const float *__restrict__ gate,
+                                          uint32_t off, int nvalid, Quad<GATE> &q)
 {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (nvalid <= 0) return v;
-    if (op.vec && nvalid >= 4) {
-        v = *reinterpret_cast<const float4 *>(op.p + off);
-        if (op.gate) {
-            const float4 g = *reinterpret_cast<const float4 *>(op.gate + off);
-            v.x = g.x > 0.f ? v.x : 0.f;
-            v.y = g.y > 0.f ? v.y : 0.f;
-            v.z = g.z > 0.f ? v.z : 0.f;
-            v.w = g.w > 0.f ? v.w : 0.f;
+    if (VEC) {
+        const uint32_t o = nvalid >= 4 ? off : 0u;
+        q.v = *reinterpret_cast<const float4 *>(base + o);
+        if (GATE) q.g[0] = *reinterpret_cast<const float4 *>(gate + o);
+    } else {
+        float e[4], f[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t o = i < nvalid ? off + i : 0u;
+            e[i] = base[o];
+            if (GATE) f[i] = gate[o];
         }
-        return v;
+        q.v = make_float4(e[0], e[1], e[2], e[3]);
+        if (GATE) q.g[0] = make_float4(f[0], f[1], f[2], f[3]);
     }
-    float e[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int i = 0; i < 4; ++i)
-        if (i < nvalid) {
-            e[i] = op.p[off + i];
-            if (op.gate && !(op.gate[off + i] > 0.f)) e[i] = 0.f;
-        }
-    return make_float4(e[0], e[1], e[2], e[3]);
+}
+
+template <bool GATE>
+__device__ __forceinline__ float4 mask_quad(const Quad<GATE> &q, int nvalid)
+{
+    float4 v = q.v;
+    if (GATE) {
+        v.x = q.g[0].x > 0.f ? v.x : 0.f;
+        v.y = q.g[0].y > 0.f ? v.y : 0.f;
+        v.z = q.g[0].z > 0.f ? v.z : 0.f;
+        v.w = q.g[0].w > 0.f ? v.w : 0.f;
+    }
+    v.x = nvalid > 0 ? v.x : 0.f;
+    v.y = nvalid > 1 ? v.y : 0.f;
+    v.z = nvalid > 2 ? v.z : 0.f;
+    v.w = nvalid > 3 ? v.w : 0.f;
+    return v;
 }
 
 __device__ __forceinline__ int clamp4(int64_t n) { return n >= 4 ? 4 : (n <= 0 ? 0 : (int)n); }
 
-// Global -> registers for one 128 (out) x 32 (contracted) operand tile.
-template <bool COL>
-__device__ __forceinline__ void fetch_tile(const Operand &op, int64_t o0, int64_t omax, int64_t k0, int64_t kend,
-                                           float4 (&r)[4])
-{
-    const int t = threadIdx.x;
-    if (!COL) {
-        const int kq = t & 7, rr = t >> 3;                 // 8 lanes cover the 32 contracted indices of a row
-        const int64_t k = k0 + 4 * kq;
-        const int nv = clamp4(kend - k);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int64_t o = o0 + rr + 32 * s;
-            r[s] = load4(op, o * op.ld + k, o < omax ? nv : 0);
-        }
-    } else {
-        const int oq = t & 31, kk = t >> 5;                // 32 lanes cover the 128 out indices of one k
-        const int64_t o = o0 + 4 * oq;
-        const int nv = clamp4(omax - o);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const int64_t k = k0 + kk + 8 * s;
-            r[s] = load4(op, k * op.ld + o, k < kend ? nv : 0);
-        }
-    }
-}
+// One 128 (out) x kStep (contracted) operand tile: global -> registers (fetch), registers -> LDS
+// (stage).  "row" operand: kStep/4 lanes cover the contracted indices of one out index and slot s
+// is out index t/(kStep/4) + s*(1024/kStep); "col" operand: 32 lanes cover the 128 out indices of
+// one contracted index and slot s is contracted index t/32 + 8s.  Lane offsets are relative to
+// the tile's origin and stay the same from stage to stage (the host keeps 160*ld below 2^32).
+template <bool COL, bool VEC, bool GATE>
+struct TileMover {
+    static constexpr int kq_n = kStep / 4, rows = 256 / kq_n;
+    Quad<GATE> r[kLoads];
+    uint32_t off[kLoads];   // element offset of slot s from the tile origin
+    int nv_out;             // row: bit s set if slot s is an existing out index; col: quad elements in range
+    int64_t ld, o0;
+    const float *p, *gate;
 
-template <bool COL>
-__device__ __forceinline__ void stage_tile(float *lds, const float4 (&r)[4])
-{
-    const int t = threadIdx.x;
-    if (!COL) {
-        const int kq = t & 7, rr = t >> 3;
+    __device__ __forceinline__ void init(const Operand &op, int64_t o0_, int64_t omax)
+    {
+        const int t = threadIdx.x;
+        ld = op.ld; o0 = o0_; p = op.p; gate = op.gate;
+        nv_out = 0;
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            *reinterpret_cast<float4 *>(lds + (rr + 32 * s) * kRowStride + 4 * kq) = r[s];
-    } else {
-        const int oq = t & 31, kk = t >> 5;
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-            *reinterpret_cast<float4 *>(lds + (kk + 8 * s) * kColStride + 4 * oq) = r[s];
+        for (int s = 0; s < kLoads; ++s) {
+            if (!COL) {
+                const int dr = t / kq_n + rows * s;
+                off[s] = (uint32_t)dr * (uint32_t)ld + 4u * (t % kq_n);
+                if (o0 + dr < omax) nv_out |= 1 << s;
+            } else {
+                off[s] = (uint32_t)((t >> 5) + 8 * s) * (uint32_t)ld + 4u * (t & 31);
+            }
+        }
+        if (COL) nv_out = clamp4(omax - (o0 + 4 * (t & 31)));
     }
-}
+
+    __device__ __forceinline__ int nvalid(int s, int64_t k0, int64_t kend) const
+    {
+        const int t = threadIdx.x;
+        if (!COL) return (nv_out >> s) & 1 ? clamp4(kend - (k0 + 4 * (t % kq_n))) : 0;
+        return k0 + (t >> 5) + 8 * s < kend ? nv_out : 0;
+    }
+
+    __device__ __forceinline__ void fetch(int64_t k0, int64_t kend)
+    {
+        const int64_t origin = COL ? k0 * ld + o0 : o0 * ld + k0;      // uniform
+#pragma unroll
+        for (int s = 0; s < kLoads; ++s)
+            load_quad<VEC, GATE>(p + origin, GATE ? gate + origin : nullptr, off[s], nvalid(s, k0, kend), r[s]);
+    }
+
+    // (k0, kend) must be those of the fetch that filled the registers.
+    __device__ __forceinline__ void stage(float *lds, int64_t k0, int64_t kend) const
+    {
+        const int t = threadIdx.x;
+#pragma unroll
+        for (int s = 0; s < kLoads; ++s) {
+            const float4 v = mask_quad<GATE>(r[s], nvalid(s, k0, kend));
+            if (!COL)
+                *reinterpret_cast<float4 *>(lds + (t / kq_n + rows * s) * kRowStride + 4 * (t % kq_n)) = v;
+            else
+                *reinterpret_cast<float4 *>(lds + ((t >> 5) + 8 * s) * kColStride + 4 * (t & 31)) = v;
+        }
+    }
+};
 
 // The four values (contracted indices 8c+4h .. 8c+4h+3) of out index o.
 template <bool COL>
@@ -128,11 +184,47 @@ __device__ __forceinline__ float4 read_frag(const float *lds, int o, int c, int 
     return make_float4(q[0], q[kColStride], q[2 * kColStride], q[3 * kColStride]);
 }
 
-template <bool A_COL, bool B_COL>
+// The MFMAs of one group of 8 contracted indices; consecutive MFMAs go to different accumulators.
+__device__ __forceinline__ void mma_group(const float4 (&fa)[2], const float4 (&fb)[2], f32x16 (&acc)[2][2])
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float av = t == 0 ? fa[i].x : t == 1 ? fa[i].y : t == 2 ? fa[i].z : fa[i].w;
+                const float bv = t == 0 ? fb[j].x : t == 1 ? fb[j].y : t == 2 ? fb[j].z : fb[j].w;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+            }
+}
+
+// All MFMAs of `nchunk` groups of 8 contracted indices of the staged tiles.
+template <bool A_COL, bool B_COL, bool COLSUM>
+__device__ __forceinline__ void mma_stage(const float *la, const float *lb, int nchunk, int wr, int wc, int l32,
+                                          int h, f32x16 (&acc)[2][2], float (&bsum)[2])
+{
+#pragma unroll 1
+    for (int c = 0; c < nchunk; ++c) {
+        float4 fa[2], fb[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            fa[i] = read_frag<A_COL>(la, wr * 64 + i * 32 + l32, c, h);
+            fb[i] = read_frag<B_COL>(lb, wc * 64 + i * 32 + l32, c, h);
+        }
+        if (COLSUM) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) bsum[j] += (fb[j].x + fb[j].y) + (fb[j].z + fb[j].w);
+        }
+        mma_group(fa, fb, acc);
+    }
+}
+
+template <bool A_COL, bool B_COL, bool COLSUM, bool VEC, bool GATE_A, bool GATE_B>
 __global__ __launch_bounds__(256) void k_update_gemm(const GemmArgs g)
 {
-    __shared__ __attribute__((aligned(16))) float lds_a[kOperandFloats];
-    __shared__ __attribute__((aligned(16))) float lds_b[kOperandFloats];
+    __shared__ __attribute__((aligned(16))) float lds_a[kBuffers][kOperandFloats];
+    __shared__ __attribute__((aligned(16))) float lds_b[kBuffers][kOperandFloats];
 
     // Workgroups are dealt round-robin to the 8 L2 domains; the ones that share an operand tile
     // (same outer index) are given consecutive slots of one domain.
@@ -173,62 +265,78 @@ __global__ __launch_bounds__(256) void k_update_gemm(const GemmArgs g)
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     float bsum[2] = {0.f, 0.f};
 
-    float4 ra[4], rb[4];
+    TileMover<A_COL, VEC, GATE_A> ma;
+    TileMover<B_COL, VEC, GATE_B> mb;
+    ma.init(g.a, r0, g.R);
+    mb.init(g.b, c0, g.C);
     if (kbeg < kend) {
-        fetch_tile<A_COL>(g.a, r0, g.R, kbeg, kend, ra);
-        fetch_tile<B_COL>(g.b, c0, g.C, kbeg, kend, rb);
-    }
-    for (int64_t k0 = kbeg; k0 < kend; k0 += kStep) {
-        stage_tile<A_COL>(lds_a, ra);
-        stage_tile<B_COL>(lds_b, rb);
+        ma.fetch(kbeg, kend);
+        mb.fetch(kbeg, kend);
+        ma.stage(lds_a[0], kbeg, kend);
+        mb.stage(lds_b[0], kbeg, kend);
         __syncthreads();
-        if (k0 + kStep < kend) {                   // next stage's global loads fly during the MFMAs
-            fetch_tile<A_COL>(g.a, r0, g.R, k0 + kStep, kend, ra);
-            fetch_tile<B_COL>(g.b, c0, g.C, k0 + kStep, kend, rb);
+    }
+    int buf = 0;
+    for (int64_t k0 = kbeg; k0 < kend; k0 += kStep) {
+        const bool more = k0 + kStep < kend;
+        if (more) {                                // next stage's global loads fly during the MFMAs
+            ma.fetch(k0 + kStep, kend);
+            mb.fetch(k0 + kStep, kend);
         }
         const int64_t left = kend - k0;
-        const int nchunk = left >= kStep ? kStep / 8 : (int)((left + 7) / 8);
-        for (int c = 0; c < nchunk; ++c) {
-            float4 fa[2], fb[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = read_frag<A_COL>(lds_a, wr * 64 + i * 32 + l32, c, h);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                fb[j] = read_frag<B_COL>(lds_b, wc * 64 + j * 32 + l32, c, h);
-                bsum[j] += (fb[j].x + fb[j].y) + (fb[j].z + fb[j].w);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i].x, fb[j].x, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i].y, fb[j].y, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i].z, fb[j].z, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i].w, fb[j].w, acc[i][j], 0, 0, 0);
-                }
+        mma_stage<A_COL, B_COL, COLSUM>(lds_a[buf], lds_b[buf], left >= kStep ? kStep / 8 : (int)((left + 7) / 8), wr,
+                                        wc, l32, h, acc, bsum);
+        if (kBuffers == 1) __syncthreads();
+        const int nb = kBuffers == 1 ? 0 : buf ^ 1;
+        if (more) {
+            ma.stage(lds_a[nb], k0 + kStep, kend);
+            mb.stage(lds_b[nb], k0 + kStep, kend);
         }
         __syncthreads();
+        buf = nb;
     }
 
     // Accumulator element e of lane (h, l32) is row 8*(e/4) + 4*h + e%4, column l32 of its 32 x 32 tile.
-    float *cbase = g.c + slab_id * g.c_slab;
+    const int64_t row0 = r0 + wr * 64 + 4 * h, col0 = c0 + wc * 64 + l32;
+    float *cb = g.c + slab_id * g.c_slab + row0 * g.ldc + col0;
+    const bool relu = g.relu != 0;
+    constexpr bool STREAM = !COLSUM;    // Y and dH leave with streaming stores; slab partials are re-read at once
+    if (r0 + kTile <= g.R && c0 + kTile <= g.C) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int64_t col = c0 + wc * 64 + j * 32 + l32;
-        if (col >= g.C) continue;
-        const float bj = g.bias ? g.bias[col] : 0.f;
+        for (int j = 0; j < 2; ++j) {
+            const float bj = g.bias ? g.bias[col0 + 32 * j] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int64_t row = r0 + wr * 64 + i * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-                if (row >= g.R) continue;
-                float v = acc[i][j][e] + bj;
-                if (g.relu) v = v > 0.f ? v : 0.f;
-                cbase[row * g.ldc + col] = v;
-            }
+                for (int e = 0; e < 16; ++e) {
+                    float v = acc[i][j][e] + bj;
+                    if (relu) v = v > 0.f ? v : 0.f;
+                    float *dst = &cb[(int64_t)(32 * i + 8 * (e >> 2) + (e & 3)) * g.ldc + 32 * j];
+                    if (STREAM)
+                        __builtin_nontemporal_store(v, dst);
+                    else
+                        *dst = v;
+                }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t col = col0 + 32 * j;
+            if (col >= g.C) continue;
+            const float bj = g.bias ? g.bias[col] : 0.f;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int dr = 32 * i + 8 * (e >> 2) + (e & 3);
+                    if (row0 + dr >= g.R) continue;
+                    float v = acc[i][j][e] + bj;
+                    if (relu) v = v > 0.f ? v : 0.f;
+                    cb[(int64_t)dr * g.ldc + 32 * j] = v;
+                }
+        }
     }
-    if (g.colsum && tile_r == 0 && wr == 0) {
+    if (COLSUM && tile_r == 0 && wr == 0) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const float s = bsum[j] + __shfl_xor(bsum[j], 32);
@@ -252,12 +360,27 @@ __global__ __launch_bounds__(256) void k_update_reduce(const float *part, int64_
     *dst = (float)s;
 }
 
-bool vec_ok(const float *p, const float *gate, int64_t ld)
+// 16-byte loads need every row of both operands to start 16-byte aligned and to hold whole quads.
+bool quad_ok(const Operand &op)
 {
-    return ld % 4 == 0 && (((uintptr_t)p | (uintptr_t)gate) & 15) == 0;
+    return op.p && op.ld % 4 == 0 && (((uintptr_t)op.p | (uintptr_t)op.gate) & 15) == 0;
 }
 
-template <bool A_COL, bool B_COL>
+// WHICH names the operand that may carry a gate: 0 none, 1 a, 2 b.
+template <bool A_COL, bool B_COL, bool COLSUM, int WHICH, bool VEC>
+void launch_gates(const GemmArgs &g, unsigned blocks, hipStream_t s)
+{
+    if (WHICH == 1 && g.a.gate)
+        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, WHICH == 1, false>), dim3(blocks), dim3(256), 0,
+                           s, g);
+    else if (WHICH == 2 && g.b.gate)
+        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, false, WHICH == 2>), dim3(blocks), dim3(256), 0,
+                           s, g);
+    else
+        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, false, false>), dim3(blocks), dim3(256), 0, s, g);
+}
+
+template <bool A_COL, bool B_COL, bool COLSUM, int WHICH>
 fastgl_status launch_gemm(GemmArgs &g, hipStream_t s, const char *what)
 {
     g.tiles_r = (int)ceil_div(g.R, kTile);
@@ -271,7 +394,16 @@ fastgl_status launch_gemm(GemmArgs &g, hipStream_t s, const char *what)
         set_error("%s: too many tiles (%lld)", what, (long long)blocks);
         return FASTGL_ERR_UNSUPPORTED;
     }
-    hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL>), dim3((unsigned)blocks), dim3(256), 0, s, g);
+    bool vec = quad_ok(g.a) && quad_ok(g.b);
+    if (g.R == 0) {            // operand a has no elements: give its (all masked) loads a readable address
+        g.a.p = g.b.p;
+        g.a.gate = nullptr;
+        vec = false;
+    }
+    if (vec)
+        launch_gates<A_COL, B_COL, COLSUM, WHICH, true>(g, (unsigned)blocks, s);
+    else
+        launch_gates<A_COL, B_COL, COLSUM, WHICH, false>(g, (unsigned)blocks, s);
     FASTGL_LAUNCH_CHECK(what);
     return FASTGL_OK;
 }
@@ -282,8 +414,8 @@ fastgl_status check_dims(int64_t M, int64_t K, int64_t N)
         set_error("negative size (M=%lld K=%lld N=%lld)", (long long)M, (long long)K, (long long)N);
         return FASTGL_ERR_INVALID_ARG;
     }
-    if (M >= INT32_MAX || K >= INT32_MAX || N >= INT32_MAX || K * N >= ((int64_t)1 << 38)) {
-        set_error("sizes must stay below 2^31-1 and K*N below 2^38");
+    if (M >= INT32_MAX || K >= ((int64_t)1 << 24) || N >= ((int64_t)1 << 24)) {
+        set_error("M must stay below 2^31-1, K and N below 2^24");
         return FASTGL_ERR_UNSUPPORTED;
     }
     return FASTGL_OK;
@@ -291,9 +423,18 @@ fastgl_status check_dims(int64_t M, int64_t K, int64_t N)
 
 bool misaligned(const void *p) { return ((uintptr_t)p & 3) != 0; }
 
+// Rows per slab: a function of the shape alone, so results do not depend on the device or the run.
+int64_t slab_rows(int64_t M, int64_t K, int64_t N)
+{
+    const int64_t tiles = (K > 0 ? ceil_div(K, kTile) : 1) * ceil_div(N, kTile);
+    int64_t rows = kMaxSlabRows;
+    while (rows > kMinSlabRows && ceil_div(M, rows) * tiles < kSlabFill) rows /= 2;
+    return rows;
+}
+
 size_t bwd_workspace(int64_t M, int64_t K, int64_t N)
 {
-    const int64_t nslab = ceil_div(M, kSlabRows);
+    const int64_t nslab = ceil_div(M, slab_rows(M, K, N));
     return align_up((size_t)nslab * (size_t)(K * N + N) * sizeof(float), 256);
 }
 
@@ -319,12 +460,12 @@ fastgl_status fastgl_update_fwd(const float *H, const float *W, const float *bia
         return FASTGL_ERR_INVALID_ARG;
     }
     GemmArgs g = {};
-    g.a = Operand{H, nullptr, K, vec_ok(H, nullptr, K)};
-    g.b = Operand{W, nullptr, N, vec_ok(W, nullptr, N)};
+    g.a = Operand{H, nullptr, K};
+    g.b = Operand{W, nullptr, N};
     g.c = Y; g.ldc = N;
     g.R = M; g.C = N; g.Kc = K; g.slab = K;
     g.bias = bias; g.relu = relu != 0;
-    return launch_gemm<false, true>(g, (hipStream_t)stream, "fastgl_update_fwd");
+    return launch_gemm<false, true, false, 0>(g, (hipStream_t)stream, "fastgl_update_fwd");
 }
 
 size_t fastgl_update_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N)
@@ -374,27 +515,27 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
     if (dH && M > 0 && K > 0) {
         // dH[m][k] = sum_n dZ[m][n] W[k][n]: both operands have the contracted index contiguous.
         GemmArgs g = {};
-        g.a = Operand{dY, gate, N, vec_ok(dY, gate, N)};
-        g.b = Operand{W, nullptr, N, vec_ok(W, nullptr, N)};
+        g.a = Operand{dY, gate, N};
+        g.b = Operand{W, nullptr, N};
         g.c = dH; g.ldc = K;
         g.R = M; g.C = K; g.Kc = N; g.slab = N;
-        st = launch_gemm<false, false>(g, s, "fastgl_update_bwd (dH)");
+        st = launch_gemm<false, false, false, 1>(g, s, "fastgl_update_bwd (dH)");
         if (st != FASTGL_OK) return st;
     }
     if (want_w) {
         // dW[k][n] = sum_m H[m][k] dZ[m][n], db[n] = sum_m dZ[m][n]: slabs of rows m, partials per slab.
-        const int64_t nslab = ceil_div(M, kSlabRows);
+        const int64_t rows = slab_rows(M, K, N), nslab = ceil_div(M, rows);
         const int64_t stride = K * N + N;
         float *part = (float *)workspace;
         if (nslab > 0) {
             GemmArgs g = {};
-            g.a = Operand{H, nullptr, K, vec_ok(H, nullptr, K)};
-            g.b = Operand{dY, gate, N, vec_ok(dY, gate, N)};
+            g.a = Operand{H, nullptr, K};
+            g.b = Operand{dY, gate, N};
             g.c = part; g.ldc = N; g.c_slab = stride;
-            g.R = K; g.C = N; g.Kc = M; g.slab = kSlabRows;
+            g.R = K; g.C = N; g.Kc = M; g.slab = rows;
             g.split = 1; g.n_outer = nslab;
             g.colsum = part + K * N; g.colsum_slab = stride;
-            st = launch_gemm<true, true>(g, s, "fastgl_update_bwd (dW)");
+            st = launch_gemm<true, true, true, 2>(g, s, "fastgl_update_bwd (dW)");
             if (st != FASTGL_OK) return st;
         }
         const int64_t n_w = K * N, total = n_w + N;
@@ -405,6 +546,10 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
     return FASTGL_OK;
 }
 
-int32_t fastgl_update_slab_rows(void) { return kSlabRows; }
+int32_t fastgl_update_slab_rows(int64_t M, int64_t K, int64_t N)
+{
+    if (M < 0 || K < 0 || N < 0) return 0;
+    return (int32_t)slab_rows(M, K, N);
+}
 
 }  // extern "C"

@@ -83,11 +83,13 @@ def test_plan_and_gather_argument_checks():
 
 def test_update_argument_checks():
     L = B.lib()
-    assert B.fastgl_update_slab_rows() > 0
+    big = B.fastgl_update_slab_rows(512345, 100, 256)
+    assert B.fastgl_update_slab_rows(-1, 4, 4) == 0
+    assert 128 <= B.fastgl_update_slab_rows(100, 100, 256) <= B.fastgl_update_slab_rows(91331, 256, 256) <= big <= 1024
     assert B.fastgl_update_bwd_workspace_bytes(-1, 4, 4) == 0
-    one = B.fastgl_update_bwd_workspace_bytes(B.fastgl_update_slab_rows(), 100, 256)
-    assert one >= 4 * (100 * 256 + 256)
-    assert B.fastgl_update_bwd_workspace_bytes(B.fastgl_update_slab_rows() + 1, 100, 256) >= 2 * one - 256
+    nslab = -(-512345 // big)
+    assert B.fastgl_update_bwd_workspace_bytes(512345, 100, 256) >= 4 * nslab * (100 * 256 + 256)
+    assert B.fastgl_update_bwd_workspace_bytes(512345 + big, 100, 256) > B.fastgl_update_bwd_workspace_bytes(512345, 100, 256)
     assert L.fastgl_update_fwd(FAKE, FAKE, None, -1, 4, 4, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
     assert "negative" in B.fastgl_last_error()
     assert L.fastgl_update_fwd(FAKE, FAKE, None, 2 ** 31, 4, 4, 0, FAKE, None) == B.FASTGL_ERR_UNSUPPORTED

@@ -67,7 +67,7 @@ def run_case(M, K, N, relu, bias, seed, what):
             torch.cuda.synchronize()
     dHr, dWr, dbr = oracle.update_bwd(H, W, Yref if relu else None, dY, relu)
     dZ = np.abs(dY).astype(np.float64) * ((Yref > 0) if relu else 1.0)
-    slab = B.fastgl_update_slab_rows()
+    slab = B.fastgl_update_slab_rows(M, K, N)
     check(dHd.cpu().numpy(), dHr, dZ @ aW.T, N, what + " dH")
     check(dWd.cpu().numpy(), dWr, aH.T @ dZ, min(M, slab), what + " dW")
     check(dbd.cpu().numpy(), dbr, dZ.sum(axis=0), min(M, slab), what + " db")
@@ -160,6 +160,6 @@ def test_update_full_size_sampled():
     Yc, dYc = np.ascontiguousarray(Y[:, cols]), np.ascontiguousarray(dY[:, cols])
     _, dWr, dbr = oracle.update_bwd(H, np.ascontiguousarray(W[:, cols]), Yc, dYc, True, want=("dW", "db"))
     dZc = np.abs(dYc).astype(np.float64) * (Yc > 0)
-    slab = B.fastgl_update_slab_rows()
+    slab = B.fastgl_update_slab_rows(M, K, N)
     check(dWd.cpu().numpy()[:, cols], dWr, np.abs(H).astype(np.float64).T @ dZc, slab, "full dW")
     check(dbd.cpu().numpy()[cols], dbr, dZc.sum(axis=0), slab, "full db")
