@@ -40,6 +40,109 @@ def compulsory_bytes(rowptr_rows, nnz, used_in_rows, out_rows, feat, elem):
     return 4 * (rowptr_rows + 1) + 4 * nnz + used_in_rows * feat * elem + out_rows * feat * elem
 
 
+MFMA_F32_PEAK_TFLOPS = 157.3
+HIDDEN, CLASSES = 256, 47          # hidden width of the benchmark's configs; class count of the products-shaped stand-in
+
+
+def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
+    """Extra leg (not the headline metric): one training step of the whole sampled GCN on the same
+    mini-batch - per layer aggregate (Eq. 1) then update (Eq. 2, Y = act(H W + b)), ReLU between
+    layers, a synthetic upstream gradient at the class scores, then the backward pass: gradients of
+    every W and b, and of every layer input except the raw features."""
+    dev = layers[0]["X"].device
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed + 1)
+    n = len(layers)
+    outs = [HIDDEN] * (n - 1) + [CLASSES]
+    P = []
+    for i, L in enumerate(layers):
+        M, K, N = L["blk"].num_dst, L["feat"], outs[i]
+        if i + 1 < n:
+            assert layers[i + 1]["feat"] == N and layers[i + 1]["blk"].num_src == M
+        p = dict(M=M, K=K, N=N, relu=i + 1 < n)
+        p["W"] = torch.randn((K, N), generator=g, device=dev) / K ** 0.5
+        p["b"] = torch.randn((N,), generator=g, device=dev) * 0.1
+        p["H"] = torch.empty((M, K), device=dev)
+        p["Y"] = torch.empty((M, N), device=dev)
+        p["dW"], p["db"] = torch.empty((K, N), device=dev), torch.empty((N,), device=dev)
+        p["dH"] = torch.empty((M, K), device=dev) if i > 0 else None
+        p["dX"] = torch.empty((L["blk"].num_src, K), device=dev) if i > 0 else None
+        p["ws"] = torch.empty(max(256, B.fastgl_update_bwd_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
+        P.append(p)
+    dlogits = torch.randn((P[-1]["M"], CLASSES), generator=g, device=dev)
+    ev = {}
+
+    def mark(key, fn, record):
+        if not record:
+            return fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        ev.setdefault(key, []).append((e0, e1))
+
+    def step(record=False):
+        plans = None
+
+        def build():
+            nonlocal plans
+            plans = make_plans()
+        mark("plan", build, record)
+        x = layers[0]["X"]
+        for i, (L, p) in enumerate(zip(layers, P)):
+            mark(f"agg_fwd{i}", lambda: B.fastgl_block_aggregate_fwd(
+                L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, x, out=p["H"], plan=plans[i],
+                workspace=workspace), record)
+            mark(f"upd_fwd{i}", lambda: B.fastgl_update_fwd(p["H"], p["W"], p["b"], p["relu"], p["Y"]), record)
+            x = p["Y"]
+        grad = dlogits
+        for i in reversed(range(n)):
+            L, p = layers[i], P[i]
+            mark(f"upd_bwd{i}", lambda: B.fastgl_update_bwd(
+                p["H"], p["W"], p["Y"] if p["relu"] else None, grad, p["relu"], want=(), dH=p["dH"], dW=p["dW"],
+                db=p["db"], workspace=p["ws"]), record)
+            if i > 0:
+                mark(f"agg_bwd{i}", lambda: B.fastgl_block_aggregate_bwd(
+                    L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, p["dH"], grad_X=p["dX"],
+                    plan=plans[i], workspace=workspace), record)
+                grad = p["dX"]
+
+    for _ in range(max(2, args.warmup // 2)):
+        step()
+    torch.cuda.synchronize()
+    steps = max(5, args.steps // 2)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    for _ in range(steps):
+        step(record=True)
+    torch.cuda.synchronize()
+    parts = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in ev.items()}
+    flops_fwd = [2.0 * p["M"] * p["K"] * p["N"] for p in P]
+    flops = sum(flops_fwd) + sum(f * (2 if i > 0 else 1) for i, f in enumerate(flops_fwd))
+    upd_ms = sum(v for k, v in parts.items() if k.startswith("upd"))
+    agg_ms = sum(v for k, v in parts.items() if k.startswith("agg"))
+    dom_ms = parts["upd_fwd0"]
+    ach = flops_fwd[0] / (dom_ms * 1e-3) / 1e12
+    return {
+        "what": "plans + per layer [aggregate, act(H W + b)] forward, then backward (dW, db every layer; "
+                "dH and the backward aggregation for every layer but the input one); widths "
+                f"{[p['K'] for p in P]} -> {outs}",
+        "ms_per_step": round(ms, 4),
+        "parts_ms": {k: round(v, 4) for k, v in parts.items()},
+        "aggregation_ms": round(agg_ms, 4), "update_ms": round(upd_ms, 4), "plan_ms": round(parts["plan"], 4),
+        "update_flops_per_step": flops,
+        "update_tflops": round(flops / (upd_ms * 1e-3) / 1e12, 2),
+        "roofline": {"bound": "mfma", "kernel": "k_update_gemm, forward of the input layer "
+                                                  f"(M={P[0]['M']}, K={P[0]['K']}, N={P[0]['N']}, fp32 MFMA)",
+                     "achieved": round(ach, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(ach / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                     "launch_ms": round(dom_ms, 4), "algorithmic_flops": flops_fwd[0]},
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,6 +152,8 @@ def main() -> int:
     ap.add_argument("--width", type=int, default=32, help="feature width of config 5")
     ap.add_argument("--fanout-order", default="A", choices=["A", "B"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gcn-step", action="store_true",
+                    help="skip the extra leg that times the whole sampled GCN (aggregation + update phase)")
     ap.add_argument("--verbose", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for rocprofv3 byte counters)")
@@ -229,6 +334,9 @@ def main() -> int:
                      "launch_ms": round(dom_ms, 4), "algorithmic_bytes": int(domL["bytes_fwd"])},
         "gen_seconds": round(gen_s, 2),
     }
+
+    if not args.no_gcn_step and w.dtype == "f32" and len(layers) > 1:
+        result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np)
 
     if not args.no_cpu_baseline:
         import oracle
