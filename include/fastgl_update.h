@@ -13,8 +13,8 @@
  * H [M,K], W [K,N], Y/dY [M,N], dH [M,K], dW [K,N], b/db [N]: dense row-major
  * fp32 with no padding between rows.  Products run on the fp32 matrix cores
  * (v_mfma_f32_32x32x2_f32): fp32 multiply, fp32 accumulate.  dW and db are
- * reduced over fixed slabs of rows whose partial results are summed in slab
- * order in fp64, so results do not depend on scheduling.
+ * reduced over fixed slabs of rows whose partial results are summed in fp64 in
+ * a fixed order, so results do not depend on scheduling.
  *
  * Conventions are those of fastgl_agg.h: every array is DEVICE memory owned by
  * the caller, the library allocates nothing, work is enqueued on `stream`

@@ -346,18 +346,41 @@ __global__ __launch_bounds__(256) void k_update_gemm(const GemmArgs g)
     }
 }
 
-// out[e] = sum over slabs, in slab order, in fp64, of part[s*stride + e]; the first n_w elements go
-// to dW, the remaining n_b to db (either may be NULL).
-__global__ __launch_bounds__(256) void k_update_reduce(const float *part, int64_t nslab, int64_t stride,
+// out[e] = sum over slabs of part[s*stride + e], in fp64 and in a fixed order: the slabs are cut into
+// kReduceParts consecutive ranges, each summed in slab order by one thread, and the range sums are
+// added in range order.  The first n_w elements go to dW, the remaining n_b to db (either may be NULL).
+constexpr int kReduceParts = 8, kReduceElems = 256 / kReduceParts;
+
+__global__ __launch_bounds__(256) void k_update_reduce(const float *__restrict__ part, int64_t nslab, int64_t stride,
                                                        int64_t n_w, int64_t n_b, float *dW, float *db)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n_w + n_b) return;
-    float *dst = e < n_w ? (dW ? dW + e : nullptr) : (db ? db + (e - n_w) : nullptr);
-    if (!dst) return;
+    __shared__ double partial[kReduceParts][kReduceElems];
+    const int el = threadIdx.x % kReduceElems, pt = threadIdx.x / kReduceElems;
+    const int64_t e = (int64_t)blockIdx.x * kReduceElems + el;
+    const int64_t per = (nslab + kReduceParts - 1) / kReduceParts;
+    const int64_t lo = pt * per, hi = lo + per < nslab ? lo + per : nslab;
     double s = 0.0;
-    for (int64_t k = 0; k < nslab; ++k) s += (double)part[k * stride + e];
-    *dst = (float)s;
+    if (e < n_w + n_b) {
+        const float *q = part + e;
+        int64_t k = lo;
+        for (; k + 4 <= hi; k += 4) {
+            const float v0 = q[k * stride], v1 = q[(k + 1) * stride], v2 = q[(k + 2) * stride],
+                        v3 = q[(k + 3) * stride];
+            s += (double)v0;
+            s += (double)v1;
+            s += (double)v2;
+            s += (double)v3;
+        }
+        for (; k < hi; ++k) s += (double)q[k * stride];
+    }
+    partial[pt][el] = s;
+    __syncthreads();
+    if (pt != 0 || e >= n_w + n_b) return;
+    double t = partial[0][el];
+#pragma unroll
+    for (int i = 1; i < kReduceParts; ++i) t += partial[i][el];
+    float *dst = e < n_w ? (dW ? dW + e : nullptr) : (db ? db + (e - n_w) : nullptr);
+    if (dst) *dst = (float)t;
 }
 
 // 16-byte loads need every row of both operands to start 16-byte aligned and to hold whole quads.
@@ -539,7 +562,7 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
             if (st != FASTGL_OK) return st;
         }
         const int64_t n_w = K * N, total = n_w + N;
-        hipLaunchKernelGGL(k_update_reduce, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, s, part, nslab,
+        hipLaunchKernelGGL(k_update_reduce, dim3((unsigned)ceil_div(total, kReduceElems)), dim3(256), 0, s, part, nslab,
                            stride, n_w, N, dW, db);
         FASTGL_LAUNCH_CHECK("fastgl_update_bwd (reduce)");
     }
