@@ -1,4 +1,5 @@
-"""ctypes front end of the CPU oracle (oracle/fastgl_oracle.c, oracle/update_oracle.c).
+"""ctypes front end of the CPU oracle (oracle/fastgl_oracle.c, oracle/update_oracle.c,
+oracle/idmap_oracle.c).
 
 TEST INFRASTRUCTURE ONLY.  Only tests/, the smoke check and the benchmark's
 cpu_baseline leg may import this package; the product path never does.  It
@@ -6,7 +7,8 @@ works on host numpy arrays and imports nothing from the GPU package.
 
 Formulas: paper Section 2.1 Eq. 1 (forward) and Section 4.2 Eq. 5 (backward,
 read as the transpose of Eq. 1 applied to the upstream gradient); Section 2.1
-Eq. 2 (update phase, read as the GCN dense transform act(H W + b)).
+Eq. 2 (update phase, read as the GCN dense transform act(H W + b)); Section 2.2 and Section 4.3,
+Algorithm 2 (ID map: global IDs to consecutive local IDs).
 """
 from __future__ import annotations
 
@@ -18,7 +20,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fastgl_oracle.c")
-_SRCS = [_SRC, os.path.join(_HERE, "update_oracle.c")]
+_SRCS = [_SRC, os.path.join(_HERE, "update_oracle.c"), os.path.join(_HERE, "idmap_oracle.c")]
 _LIB = os.path.join(_HERE, "libfastgl_oracle.so")
 
 MODES = {"sum": 0, "mean": 1, "gcn": 2}
@@ -66,6 +68,10 @@ def lib():
         L.fastgl_oracle_update_fwd.restype = i32
         L.fastgl_oracle_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p]
         L.fastgl_oracle_update_bwd.restype = i32
+        L.fastgl_oracle_idmap.argtypes = [p, i64, p, i64, p, p]
+        L.fastgl_oracle_idmap.restype = i64
+        L.fastgl_oracle_fused_map_seq.argtypes = [p, i64, i64, p, p, p]
+        L.fastgl_oracle_fused_map_seq.restype = i64
         _lib = L
     return _lib
 
@@ -216,3 +222,32 @@ def update_bwd(H, W, Y, dY, relu, want=("dH", "dW", "db")):
     if rc:
         raise RuntimeError(f"oracle returned {rc}")
     return dH, dW, db
+
+
+def idmap(dst_gid, nbr_gid):
+    """ID map of one sampled hop (Section 2.2; Section 4.3): destinations keep 0..n_dst-1, every
+    other node is numbered by first appearance in the neighbour list.
+    Returns (local_nbr int32[n_nbr], unique_gid int64[U])."""
+    dst = np.ascontiguousarray(dst_gid, dtype=np.int64)
+    nbr = np.ascontiguousarray(nbr_gid, dtype=np.int64)
+    local = np.empty(nbr.shape[0], np.int32)
+    uniq = np.empty(dst.shape[0] + nbr.shape[0], np.int64)
+    U = lib().fastgl_oracle_idmap(_ptr(dst), dst.shape[0], _ptr(nbr), nbr.shape[0], _ptr(local), _ptr(uniq))
+    if U == -2:
+        raise ValueError("destination IDs repeat")
+    if U < 0:
+        raise RuntimeError(f"oracle returned {U}")
+    return local, uniq[:U].copy()
+
+
+def fused_map_sequential(ids, table_size):
+    """Algorithm 2 run by one thread with HashFunction = id mod table_size.
+    Returns (key int64[table_size], value int64[table_size], local int64[n], LocalID)."""
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    key = np.empty(table_size, np.int64)
+    value = np.empty(table_size, np.int64)
+    local = np.empty(ids.shape[0], np.int64)
+    U = lib().fastgl_oracle_fused_map_seq(_ptr(ids), ids.shape[0], table_size, _ptr(key), _ptr(value), _ptr(local))
+    if U < 0:
+        raise RuntimeError("hash table full")
+    return key, value, local, int(U)
