@@ -379,6 +379,21 @@ def random_block(rng: np.random.Generator, num_dst: int, num_src: int, avg_deg: 
     return blk
 
 
+def hop_global_ids(blk: Block, seed: int, bits: int = 40):
+    """Global IDs for the nodes of a block: local ID l -> (l * A + C) mod 2^bits with A odd, which
+    is one-to-one.  Returns (dst_gid int64[num_dst], nbr_gid int64[E]): what a sampler hands to
+    the ID map for this hop (destinations first, then the sampled neighbours in edge order)."""
+    rng = np.random.default_rng(seed)
+    mask = (1 << bits) - 1
+    a = (int(rng.integers(1, 1 << (bits - 1))) << 1 | 1) & mask
+    c = int(rng.integers(0, 1 << bits))
+
+    def to_gid(local):
+        x = local.astype(np.uint64)
+        return ((x * np.uint64(a) + np.uint64(c)) & np.uint64(mask)).astype(np.int64)
+    return to_gid(np.arange(blk.num_dst)), to_gid(blk.indices)
+
+
 # ----------------------------------------------------------------------------
 # feature matrices
 # ----------------------------------------------------------------------------

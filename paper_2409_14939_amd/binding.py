@@ -26,7 +26,9 @@ EXPORTS = [
     "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk", "fastgl_work_per_group",
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
     "fastgl_update_fwd", "fastgl_update_bwd", "fastgl_update_bwd_workspace_bytes", "fastgl_update_slab_rows",
+    "fastgl_idmap", "fastgl_idmap_table_slots", "fastgl_idmap_workspace_bytes",
 ]
+IDMAP_MODES = {"ordered": 0, "fused": 1}
 
 
 class FastglError(RuntimeError):
@@ -79,6 +81,11 @@ def lib() -> ctypes.CDLL:
         L.fastgl_update_bwd_workspace_bytes.argtypes = [i64, i64, i64]
         L.fastgl_update_bwd_workspace_bytes.restype = sz
         L.fastgl_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p, p, sz, p]
+        L.fastgl_idmap_table_slots.argtypes = [i64]
+        L.fastgl_idmap_table_slots.restype = i64
+        L.fastgl_idmap_workspace_bytes.argtypes = [i64, i64]
+        L.fastgl_idmap_workspace_bytes.restype = sz
+        L.fastgl_idmap.argtypes = [p, i64, p, i64, i32, p, p, p, p, sz, p]
         L.fastgl_update_slab_rows.argtypes = [i64, i64, i64]
         L.fastgl_update_slab_rows.restype = ctypes.c_int32
         _lib = L
@@ -311,3 +318,38 @@ def fastgl_update_bwd(H: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor
     _check(lib().fastgl_update_bwd(_ptr(H), _ptr(W), _ptr(Y), _ptr(dY), M, K, N, int(bool(relu)), _ptr(dH),
                                    _ptr(dW), _ptr(db), _ptr(workspace), workspace.numel(), _stream()))
     return dH, dW, db
+
+
+def fastgl_idmap_table_slots(n_ids: int) -> int:
+    return int(lib().fastgl_idmap_table_slots(n_ids))
+
+
+def fastgl_idmap_workspace_bytes(n_dst: int, n_nbr: int) -> int:
+    return int(lib().fastgl_idmap_workspace_bytes(n_dst, n_nbr))
+
+
+def fastgl_idmap(dst_gid: torch.Tensor, nbr_gid: torch.Tensor, mode: str = "ordered",
+                 local_nbr: Optional[torch.Tensor] = None, unique_gid: Optional[torch.Tensor] = None,
+                 result: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None):
+    """Returns (local_nbr int32[n_nbr], unique_gid int64[n_dst+n_nbr], result int32[2]) - all on the
+    device, nothing is synchronised: result[0] = number of distinct IDs, result[1] = violations."""
+    _dev(dst_gid, torch.int64, "dst_gid")
+    _dev(nbr_gid, torch.int64, "nbr_gid")
+    n_dst, n_nbr = dst_gid.numel(), nbr_gid.numel()
+    dev = dst_gid.device
+    if local_nbr is None:
+        local_nbr = torch.empty(n_nbr, dtype=torch.int32, device=dev)
+    if unique_gid is None:
+        unique_gid = torch.empty(max(n_dst + n_nbr, 1), dtype=torch.int64, device=dev)
+    if result is None:
+        result = torch.empty(2, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(fastgl_idmap_workspace_bytes(n_dst, n_nbr), dtype=torch.uint8, device=dev)
+    _dev(local_nbr, torch.int32, "local_nbr")
+    _dev(unique_gid, torch.int64, "unique_gid")
+    _dev(result, torch.int32, "result")
+    if local_nbr.numel() < n_nbr or unique_gid.numel() < n_dst + n_nbr or result.numel() < 2:
+        raise ValueError("output arrays too small")
+    _check(lib().fastgl_idmap(_ptr(dst_gid), n_dst, _ptr(nbr_gid), n_nbr, IDMAP_MODES[mode], _ptr(local_nbr),
+                              _ptr(unique_gid), _ptr(result), _ptr(workspace), workspace.numel(), _stream()))
+    return local_nbr, unique_gid, result

@@ -1,0 +1,367 @@
+// ID map of the sample phase (paper Section 2.2; Section 4.3, Algorithm 2): global IDs of one
+// sampled hop -> consecutive local IDs.  See include/fastgl_idmap.h for the contract.
+//
+// Table: open addressing with linear probing, 64-bit keys claimed by compare-and-swap from the
+// empty marker -1, capacity a power of two >= 2 x the number of input IDs.  A thread reads the
+// slot with a plain load first and only issues the compare-and-swap when it saw the empty marker:
+// a key changes exactly once (from -1 to an ID), so anything else it reads is final; repeats of a
+// hub node therefore cost loads, not atomics.
+//
+// FUSED mode is Algorithm 2: the claimant of a slot takes the next local ID from a counter (one
+// atomic add per wavefront, the lanes that claimed a slot share it), a second kernel translates.
+// ORDERED mode replaces the counter by "smallest position seen at this slot" (atomic min), then a
+// prefix count over the positions that are first occurrences gives every distinct ID its rank in
+// order of first appearance.  Both remember the slot of every input ID, so translation does not
+// probe again.
+#include "fastgl_idmap.h"
+#include "internal.h"
+
+namespace fastgl {
+namespace {
+
+constexpr int kScanBlock = 1024;             // threads (= positions) per block of the ordered mode's passes
+constexpr int64_t kMaxIds = (int64_t)1 << 30;
+
+struct IdmapArgs {
+    const int64_t *dst_gid, *nbr_gid;
+    int64_t n_dst, n_nbr, n;
+    int64_t *keys;            // [cap]
+    int32_t *vals;            // [cap] ORDERED: smallest position; FUSED: local ID
+    int32_t *lid;             // [cap] ORDERED: local ID
+    int32_t *slot_of;         // [n] slot of every input position (-1: rejected ID)
+    int32_t *block_cnt;       // [blocks + 1]
+    int32_t *local_nbr;
+    int64_t *unique_gid;
+    int32_t *result;          // [0] U, [1] violations
+    uint32_t mask;
+    int shift;                // 64 - log2(cap)
+    int64_t cap;
+    int nblocks;
+    int fused;
+};
+
+__device__ __forceinline__ int64_t id_at(const IdmapArgs &a, int64_t p)
+{
+    return p < a.n_dst ? a.dst_gid[p] : a.nbr_gid[p - a.n_dst];
+}
+
+__device__ __forceinline__ uint32_t hash_slot(int64_t gid, int shift)
+{
+    return (uint32_t)(((uint64_t)gid * 0x9E3779B97F4A7C15ull) >> shift);
+}
+
+// Slot that holds gid after the call; fresh = this thread put it there.  Ends because at most half
+// of the slots are ever taken.
+__device__ __forceinline__ uint32_t insert_id(int64_t *keys, uint32_t mask, int shift, int64_t gid, bool &fresh)
+{
+    uint32_t slot = hash_slot(gid, shift);
+    fresh = false;
+    for (;;) {
+        int64_t k = __hip_atomic_load(&keys[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (k == -1) {
+            k = (int64_t)atomicCAS((unsigned long long *)&keys[slot], (unsigned long long)-1ll,
+                                   (unsigned long long)gid);
+            if (k == -1) {
+                fresh = true;
+                return slot;
+            }
+        }
+        if (k == gid) return slot;
+        slot = (slot + 1) & mask;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_idmap_fill(IdmapArgs a)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0) {
+        a.result[0] = a.fused ? (int32_t)a.n_dst : 0;
+        a.result[1] = 0;
+    }
+    const int64_t s = 4 * i;                    // cap is a multiple of 1024
+    if (s >= a.cap) return;
+    longlong2 e = make_longlong2(-1ll, -1ll);
+    reinterpret_cast<longlong2 *>(a.keys + s)[0] = e;
+    reinterpret_cast<longlong2 *>(a.keys + s)[1] = e;
+    const int v = a.fused ? 0 : INT32_MAX;
+    *reinterpret_cast<int4 *>(a.vals + s) = make_int4(v, v, v, v);
+}
+
+// ORDERED pass 1: claim slots, keep the smallest position per slot.
+__global__ __launch_bounds__(256) void k_idmap_insert_min(IdmapArgs a)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= a.n) return;
+    const int64_t gid = id_at(a, p);
+    if (gid < 0) {
+        a.slot_of[p] = -1;
+        atomicAdd(&a.result[1], 1);
+        return;
+    }
+    bool fresh;
+    const uint32_t slot = insert_id(a.keys, a.mask, a.shift, gid, fresh);
+    a.slot_of[p] = (int32_t)slot;
+    atomicMin(&a.vals[slot], (int32_t)p);
+}
+
+__device__ __forceinline__ bool is_first(const IdmapArgs &a, int64_t p)
+{
+    if (p >= a.n) return false;
+    const int32_t slot = a.slot_of[p];
+    return slot >= 0 && a.vals[slot] == (int32_t)p;
+}
+
+// ORDERED pass 2: first occurrences per block of kScanBlock positions.
+__global__ __launch_bounds__(kScanBlock) void k_idmap_count(IdmapArgs a)
+{
+    const int64_t p = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
+    const int c = __syncthreads_count(is_first(a, p));
+    if (threadIdx.x == 0) a.block_cnt[blockIdx.x] = c;
+}
+
+// Exclusive prefix sum over `count` ints in place (count <= kScanBlock) by one workgroup; returns the
+// total to every thread.  `base` is added to every result.
+__device__ int block_exclusive_scan(int v, int base, int &out_excl)
+{
+    __shared__ int wave_sum[kScanBlock / kWave];
+    __shared__ int total_s;
+    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
+    int incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int t = __shfl_up(incl, d);
+        if (lane >= d) incl += t;
+    }
+    if (lane == kWave - 1) wave_sum[wv] = incl;
+    __syncthreads();
+    if (wv == 0) {
+        const int nw = blockDim.x / kWave;
+        int w = lane < nw ? wave_sum[lane] : 0;
+        int wi = w;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int t = __shfl_up(wi, d);
+            if (lane >= d) wi += t;
+        }
+        if (lane < nw) wave_sum[lane] = wi - w;
+        if (lane == nw - 1) total_s = wi;
+    }
+    __syncthreads();
+    out_excl = base + wave_sum[wv] + incl - v;
+    const int total = total_s;
+    __syncthreads();
+    return total;
+}
+
+// ORDERED pass 3: block counts -> block offsets, total -> result[0].  One workgroup.
+__global__ __launch_bounds__(kScanBlock) void k_idmap_scan(IdmapArgs a)
+{
+    int running = 0;
+    for (int b0 = 0; b0 < a.nblocks; b0 += kScanBlock) {
+        const int b = b0 + threadIdx.x;
+        const int v = b < a.nblocks ? a.block_cnt[b] : 0;
+        int excl;
+        const int total = block_exclusive_scan(v, running, excl);
+        if (b < a.nblocks) a.block_cnt[b] = excl;
+        running += total;
+    }
+    if (threadIdx.x == 0) a.result[0] = running;
+}
+
+// ORDERED pass 4: rank of every first occurrence = its local ID.
+__global__ __launch_bounds__(kScanBlock) void k_idmap_rank(IdmapArgs a)
+{
+    const int64_t p = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
+    const bool first = is_first(a, p);
+    int rank;
+    block_exclusive_scan(first ? 1 : 0, a.block_cnt[blockIdx.x], rank);
+    if (first) {
+        a.lid[a.slot_of[p]] = rank;
+        a.unique_gid[rank] = id_at(a, p);
+    }
+    if (p < a.n_dst && (!first || rank != (int)p)) atomicAdd(&a.result[1], 1);   // repeated destination
+}
+
+// Translation (both modes): the slot of every neighbour entry is known.
+__global__ __launch_bounds__(256) void k_idmap_translate(IdmapArgs a)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= a.n_nbr) return;
+    const int32_t slot = a.slot_of[a.n_dst + e];
+    const int32_t *src = a.fused ? a.vals : a.lid;
+    a.local_nbr[e] = slot >= 0 ? src[slot] : -1;
+}
+
+// FUSED pass 1a: destination i takes local ID i.
+__global__ __launch_bounds__(256) void k_idmap_fused_dst(IdmapArgs a)
+{
+    const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= a.n_dst) return;
+    const int64_t gid = a.dst_gid[p];
+    bool fresh = false;
+    if (gid >= 0) {
+        const uint32_t slot = insert_id(a.keys, a.mask, a.shift, gid, fresh);
+        if (fresh) {
+            a.vals[slot] = (int32_t)p;
+            a.unique_gid[p] = gid;
+        }
+    }
+    if (!fresh) atomicAdd(&a.result[1], 1);       // negative or repeated destination
+}
+
+// FUSED pass 1b (Algorithm 2): whoever claims a slot takes the next local ID.
+__global__ __launch_bounds__(256) void k_idmap_fused_nbr(IdmapArgs a)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool active = e < a.n_nbr;
+    const int64_t gid = active ? a.nbr_gid[e] : -1;
+    bool fresh = false;
+    uint32_t slot = 0;
+    if (gid >= 0) slot = insert_id(a.keys, a.mask, a.shift, gid, fresh);
+    if (active) {
+        a.slot_of[a.n_dst + e] = gid >= 0 ? (int32_t)slot : -1;
+        if (gid < 0) atomicAdd(&a.result[1], 1);
+    }
+    // the lanes of a wavefront that claimed a slot share one atomic add on the counter
+    const unsigned long long claim = __ballot(fresh);
+    if (claim == 0) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int leader = __ffsll((long long)claim) - 1;
+    int base = 0;
+    if (lane == leader) base = atomicAdd(&a.result[0], __popcll(claim));
+    base = __shfl(base, leader);
+    if (fresh) {
+        const int l = base + __popcll(claim & ((1ull << lane) - 1));
+        a.vals[slot] = l;
+        a.unique_gid[l] = gid;
+    }
+}
+
+int64_t table_slots(int64_t n)
+{
+    int64_t cap = 1024;
+    while (cap < 2 * n) cap *= 2;
+    return cap;
+}
+
+struct Layout {
+    size_t keys, vals, lid, slot_of, block_cnt, total;
+};
+
+Layout layout(int64_t n)
+{
+    const int64_t cap = table_slots(n);
+    Layout L;
+    size_t off = 0;
+    L.keys = off; off += align_up((size_t)cap * 8, 256);
+    L.vals = off; off += align_up((size_t)cap * 4, 256);
+    L.lid = off; off += align_up((size_t)cap * 4, 256);
+    L.slot_of = off; off += align_up((size_t)(n > 0 ? n : 1) * 4, 256);
+    L.block_cnt = off; off += align_up((size_t)(ceil_div(n, kScanBlock) + 1) * 4, 256);
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+}  // namespace fastgl
+
+using namespace fastgl;
+
+extern "C" {
+
+int64_t fastgl_idmap_table_slots(int64_t n_ids)
+{
+    if (n_ids < 0 || n_ids >= kMaxIds) return 0;
+    return table_slots(n_ids);
+}
+
+size_t fastgl_idmap_workspace_bytes(int64_t n_dst, int64_t n_nbr)
+{
+    if (n_dst < 0 || n_nbr < 0 || n_dst + n_nbr >= kMaxIds) return 0;
+    return layout(n_dst + n_nbr).total;
+}
+
+fastgl_status fastgl_idmap(const int64_t *dst_gid, int64_t n_dst, const int64_t *nbr_gid, int64_t n_nbr,
+                           fastgl_idmap_mode mode, int32_t *local_nbr, int64_t *unique_gid, int32_t *result,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (n_dst < 0 || n_nbr < 0) {
+        set_error("negative size (n_dst=%lld n_nbr=%lld)", (long long)n_dst, (long long)n_nbr);
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    if (n_dst + n_nbr >= kMaxIds) {
+        set_error("n_dst + n_nbr must stay below 2^30");
+        return FASTGL_ERR_UNSUPPORTED;
+    }
+    if ((int)mode != FASTGL_IDMAP_ORDERED && (int)mode != FASTGL_IDMAP_FUSED) {
+        set_error("unknown ID-map mode %d", (int)mode);
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    const int64_t n = n_dst + n_nbr;
+    if ((n_dst > 0 && !dst_gid) || (n_nbr > 0 && (!nbr_gid || !local_nbr)) || (n > 0 && !unique_gid) || !result) {
+        set_error("NULL array (dst_gid, nbr_gid, local_nbr, unique_gid or result)");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    if ((((uintptr_t)dst_gid | (uintptr_t)nbr_gid | (uintptr_t)unique_gid) & 7) ||
+        (((uintptr_t)local_nbr | (uintptr_t)result) & 3)) {
+        set_error("ID arrays must be 8-byte aligned, local_nbr and result 4-byte aligned");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    if (!workspace || ((uintptr_t)workspace & 255)) {
+        set_error("workspace must be a 256-byte aligned device buffer");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    const Layout L = layout(n);
+    if (workspace_bytes < L.total) {
+        set_error("workspace too small: %zu < %zu bytes", workspace_bytes, L.total);
+        return FASTGL_ERR_WORKSPACE;
+    }
+    char *ws = (char *)workspace;
+    IdmapArgs a = {};
+    a.dst_gid = dst_gid; a.nbr_gid = nbr_gid;
+    a.n_dst = n_dst; a.n_nbr = n_nbr; a.n = n;
+    a.keys = (int64_t *)(ws + L.keys);
+    a.vals = (int32_t *)(ws + L.vals);
+    a.lid = (int32_t *)(ws + L.lid);
+    a.slot_of = (int32_t *)(ws + L.slot_of);
+    a.block_cnt = (int32_t *)(ws + L.block_cnt);
+    a.local_nbr = local_nbr; a.unique_gid = unique_gid; a.result = result;
+    a.cap = table_slots(n);
+    a.mask = (uint32_t)(a.cap - 1);
+    int lg = 0;
+    while (((int64_t)1 << lg) < a.cap) ++lg;
+    a.shift = 64 - lg;
+    a.nblocks = (int)ceil_div(n, kScanBlock);
+    a.fused = mode == FASTGL_IDMAP_FUSED;
+    hipStream_t s = (hipStream_t)stream;
+    auto grid = [](int64_t items, int per) { return dim3((unsigned)(items > 0 ? ceil_div(items, per) : 1)); };
+
+    hipLaunchKernelGGL(k_idmap_fill, grid(a.cap / 4, 256), dim3(256), 0, s, a);
+    FASTGL_LAUNCH_CHECK("fastgl_idmap (fill)");
+    if (a.fused) {
+        if (n_dst > 0) {
+            hipLaunchKernelGGL(k_idmap_fused_dst, grid(n_dst, 256), dim3(256), 0, s, a);
+            FASTGL_LAUNCH_CHECK("fastgl_idmap (destinations)");
+        }
+        if (n_nbr > 0) {
+            hipLaunchKernelGGL(k_idmap_fused_nbr, grid(n_nbr, 256), dim3(256), 0, s, a);
+            FASTGL_LAUNCH_CHECK("fastgl_idmap (fused map)");
+        }
+    } else if (n > 0) {
+        hipLaunchKernelGGL(k_idmap_insert_min, grid(n, 256), dim3(256), 0, s, a);
+        FASTGL_LAUNCH_CHECK("fastgl_idmap (insert)");
+        hipLaunchKernelGGL(k_idmap_count, dim3((unsigned)a.nblocks), dim3(kScanBlock), 0, s, a);
+        FASTGL_LAUNCH_CHECK("fastgl_idmap (count)");
+        hipLaunchKernelGGL(k_idmap_scan, dim3(1), dim3(kScanBlock), 0, s, a);
+        FASTGL_LAUNCH_CHECK("fastgl_idmap (scan)");
+        hipLaunchKernelGGL(k_idmap_rank, dim3((unsigned)a.nblocks), dim3(kScanBlock), 0, s, a);
+        FASTGL_LAUNCH_CHECK("fastgl_idmap (rank)");
+    }
+    if (n_nbr > 0) {
+        hipLaunchKernelGGL(k_idmap_translate, grid(n_nbr, 256), dim3(256), 0, s, a);
+        FASTGL_LAUNCH_CHECK("fastgl_idmap (translate)");
+    }
+    return FASTGL_OK;
+}
+
+}  // extern "C"

@@ -104,3 +104,24 @@ def test_update_argument_checks():
     assert "workspace" in B.fastgl_last_error()
     assert bwd(FAKE, FAKE, FAKE, FAKE, 4, 4, 4, 0, None, FAKE, None, FAKE, 8, None) == B.FASTGL_ERR_WORKSPACE
     assert bwd(FAKE, FAKE, FAKE, FAKE, 4, 4, 4, 0, None, None, None, None, 0, None) == B.FASTGL_OK   # nothing asked
+
+
+def test_idmap_argument_checks():
+    L = B.lib()
+    assert B.fastgl_idmap_table_slots(0) == 1024 and B.fastgl_idmap_table_slots(600) == 2048
+    assert B.fastgl_idmap_table_slots(-1) == 0 and B.fastgl_idmap_table_slots(2 ** 30) == 0
+    cap = B.fastgl_idmap_table_slots(3_000_000)
+    assert cap >= 6_000_000 and cap & (cap - 1) == 0
+    assert B.fastgl_idmap_workspace_bytes(500_000, 2_500_000) >= 16 * cap + 4 * 3_000_000
+    assert B.fastgl_idmap_workspace_bytes(-1, 5) == 0
+    f = L.fastgl_idmap
+    assert f(FAKE, -1, FAKE, 4, 0, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert f(FAKE, 4, FAKE, 2 ** 30, 0, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == B.FASTGL_ERR_UNSUPPORTED
+    assert f(FAKE, 4, FAKE, 4, 2, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "mode" in B.fastgl_last_error()
+    assert f(None, 4, FAKE, 4, 0, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert f(FAKE, 4, FAKE, 4, 0, FAKE, FAKE, None, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert f(FAKE, 4, ctypes.c_void_p(0x1004), 4, 0, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "aligned" in B.fastgl_last_error()
+    assert f(FAKE, 4, FAKE, 4, 0, FAKE, FAKE, FAKE, None, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert f(FAKE, 4, FAKE, 4, 0, FAKE, FAKE, FAKE, FAKE, 64, None) == B.FASTGL_ERR_WORKSPACE
