@@ -8,7 +8,7 @@
 // hub node therefore cost loads, not atomics.
 //
 // FUSED mode is Algorithm 2: the claimant of a slot takes the next local ID from a counter (one
-// atomic add per wavefront, the lanes that claimed a slot share it), a second kernel translates.
+// atomic add per workgroup, the threads that claimed a slot share it), a second kernel translates.
 // ORDERED mode replaces the counter by "smallest position seen at this slot" (atomic min), then a
 // prefix count over the positions that are first occurrences gives every distinct ID its rank in
 // order of first appearance.  Both remember the slot of every input ID, so translation does not
@@ -21,14 +21,22 @@ namespace {
 
 constexpr int kScanBlock = 1024;             // threads (= positions) per block of the ordered mode's passes
 constexpr int64_t kMaxIds = (int64_t)1 << 30;
+constexpr int32_t kNoSlot = 0x7FFFFFFF;      // no table has this many slots
+constexpr int32_t kFirstBit = (int32_t)0x80000000u;
+
+// One table entry: the key and what is looked up through it share a 16-byte line piece.
+struct __attribute__((aligned(16))) Slot {
+    int64_t key;              // global ID, -1 while empty
+    int32_t val;              // ORDERED: smallest position seen; FUSED: local ID
+    int32_t lid;              // ORDERED: local ID
+};
 
 struct IdmapArgs {
     const int64_t *dst_gid, *nbr_gid;
     int64_t n_dst, n_nbr, n;
-    int64_t *keys;            // [cap]
-    int32_t *vals;            // [cap] ORDERED: smallest position; FUSED: local ID
-    int32_t *lid;             // [cap] ORDERED: local ID
-    int32_t *slot_of;         // [n] slot of every input position (-1: rejected ID)
+    Slot *table;              // [cap]
+    int32_t *slot_of;         // [n] slot of every input position (kNoSlot: rejected ID); the ordered mode
+                              // sets bit 31 on positions that are first occurrences
     int32_t *block_cnt;       // [blocks + 1]
     int32_t *local_nbr;
     int64_t *unique_gid;
@@ -52,14 +60,14 @@ __device__ __forceinline__ uint32_t hash_slot(int64_t gid, int shift)
 
 // Slot that holds gid after the call; fresh = this thread put it there.  Ends because at most half
 // of the slots are ever taken.
-__device__ __forceinline__ uint32_t insert_id(int64_t *keys, uint32_t mask, int shift, int64_t gid, bool &fresh)
+__device__ __forceinline__ uint32_t insert_id(Slot *table, uint32_t mask, int shift, int64_t gid, bool &fresh)
 {
     uint32_t slot = hash_slot(gid, shift);
     fresh = false;
     for (;;) {
-        int64_t k = __hip_atomic_load(&keys[slot], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int64_t k = __hip_atomic_load(&table[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (k == -1) {
-            k = (int64_t)atomicCAS((unsigned long long *)&keys[slot], (unsigned long long)-1ll,
+            k = (int64_t)atomicCAS((unsigned long long *)&table[slot].key, (unsigned long long)-1ll,
                                    (unsigned long long)gid);
             if (k == -1) {
                 fresh = true;
@@ -78,13 +86,12 @@ __global__ __launch_bounds__(256) void k_idmap_fill(IdmapArgs a)
         a.result[0] = a.fused ? (int32_t)a.n_dst : 0;
         a.result[1] = 0;
     }
-    const int64_t s = 4 * i;                    // cap is a multiple of 1024
-    if (s >= a.cap) return;
-    longlong2 e = make_longlong2(-1ll, -1ll);
-    reinterpret_cast<longlong2 *>(a.keys + s)[0] = e;
-    reinterpret_cast<longlong2 *>(a.keys + s)[1] = e;
-    const int v = a.fused ? 0 : INT32_MAX;
-    *reinterpret_cast<int4 *>(a.vals + s) = make_int4(v, v, v, v);
+    if (i >= a.cap) return;
+    Slot e;
+    e.key = -1;
+    e.val = a.fused ? 0 : INT32_MAX;
+    e.lid = 0;
+    a.table[i] = e;
 }
 
 // ORDERED pass 1: claim slots, keep the smallest position per slot.
@@ -94,28 +101,30 @@ __global__ __launch_bounds__(256) void k_idmap_insert_min(IdmapArgs a)
     if (p >= a.n) return;
     const int64_t gid = id_at(a, p);
     if (gid < 0) {
-        a.slot_of[p] = -1;
+        a.slot_of[p] = kNoSlot;
         atomicAdd(&a.result[1], 1);
         return;
     }
     bool fresh;
-    const uint32_t slot = insert_id(a.keys, a.mask, a.shift, gid, fresh);
+    const uint32_t slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
     a.slot_of[p] = (int32_t)slot;
-    atomicMin(&a.vals[slot], (int32_t)p);
+    // the value only ever decreases, so a (possibly stale) reading that is already smaller settles it
+    if (__hip_atomic_load(&a.table[slot].val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > (int32_t)p)
+        atomicMin(&a.table[slot].val, (int32_t)p);
 }
 
-__device__ __forceinline__ bool is_first(const IdmapArgs &a, int64_t p)
-{
-    if (p >= a.n) return false;
-    const int32_t slot = a.slot_of[p];
-    return slot >= 0 && a.vals[slot] == (int32_t)p;
-}
-
-// ORDERED pass 2: first occurrences per block of kScanBlock positions.
+// ORDERED pass 2: mark the positions that are first occurrences (bit 31 of slot_of) and count them
+// per block of kScanBlock positions.
 __global__ __launch_bounds__(kScanBlock) void k_idmap_count(IdmapArgs a)
 {
     const int64_t p = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
-    const int c = __syncthreads_count(is_first(a, p));
+    bool first = false;
+    if (p < a.n) {
+        const int32_t slot = a.slot_of[p];
+        first = slot != kNoSlot && a.table[slot].val == (int32_t)p;
+        if (first) a.slot_of[p] = slot | kFirstBit;
+    }
+    const int c = __syncthreads_count(first);
     if (threadIdx.x == 0) a.block_cnt[blockIdx.x] = c;
 }
 
@@ -172,11 +181,12 @@ __global__ __launch_bounds__(kScanBlock) void k_idmap_scan(IdmapArgs a)
 __global__ __launch_bounds__(kScanBlock) void k_idmap_rank(IdmapArgs a)
 {
     const int64_t p = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
-    const bool first = is_first(a, p);
+    const int32_t so = p < a.n ? a.slot_of[p] : kNoSlot;
+    const bool first = so < 0;                     // bit 31
     int rank;
     block_exclusive_scan(first ? 1 : 0, a.block_cnt[blockIdx.x], rank);
     if (first) {
-        a.lid[a.slot_of[p]] = rank;
+        a.table[so & kNoSlot].lid = rank;
         a.unique_gid[rank] = id_at(a, p);
     }
     if (p < a.n_dst && (!first || rank != (int)p)) atomicAdd(&a.result[1], 1);   // repeated destination
@@ -187,9 +197,8 @@ __global__ __launch_bounds__(256) void k_idmap_translate(IdmapArgs a)
 {
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= a.n_nbr) return;
-    const int32_t slot = a.slot_of[a.n_dst + e];
-    const int32_t *src = a.fused ? a.vals : a.lid;
-    a.local_nbr[e] = slot >= 0 ? src[slot] : -1;
+    const int32_t slot = a.slot_of[a.n_dst + e] & kNoSlot;
+    a.local_nbr[e] = slot == kNoSlot ? -1 : (a.fused ? a.table[slot].val : a.table[slot].lid);
 }
 
 // FUSED pass 1a: destination i takes local ID i.
@@ -200,39 +209,39 @@ __global__ __launch_bounds__(256) void k_idmap_fused_dst(IdmapArgs a)
     const int64_t gid = a.dst_gid[p];
     bool fresh = false;
     if (gid >= 0) {
-        const uint32_t slot = insert_id(a.keys, a.mask, a.shift, gid, fresh);
+        const uint32_t slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
         if (fresh) {
-            a.vals[slot] = (int32_t)p;
+            a.table[slot].val = (int32_t)p;
             a.unique_gid[p] = gid;
         }
     }
     if (!fresh) atomicAdd(&a.result[1], 1);       // negative or repeated destination
 }
 
-// FUSED pass 1b (Algorithm 2): whoever claims a slot takes the next local ID.
-__global__ __launch_bounds__(256) void k_idmap_fused_nbr(IdmapArgs a)
+// FUSED pass 1b (Algorithm 2): whoever claims a slot takes the next local ID.  The claimants of a
+// workgroup share one atomic add on the counter (a prefix count inside the workgroup hands out the
+// IDs of the range it returns).
+__global__ __launch_bounds__(kScanBlock) void k_idmap_fused_nbr(IdmapArgs a)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    __shared__ int range_base;
+    const int64_t e = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
     const bool active = e < a.n_nbr;
     const int64_t gid = active ? a.nbr_gid[e] : -1;
     bool fresh = false;
     uint32_t slot = 0;
-    if (gid >= 0) slot = insert_id(a.keys, a.mask, a.shift, gid, fresh);
+    if (gid >= 0) slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
     if (active) {
-        a.slot_of[a.n_dst + e] = gid >= 0 ? (int32_t)slot : -1;
+        a.slot_of[a.n_dst + e] = gid >= 0 ? (int32_t)slot : kNoSlot;
         if (gid < 0) atomicAdd(&a.result[1], 1);
     }
-    // the lanes of a wavefront that claimed a slot share one atomic add on the counter
-    const unsigned long long claim = __ballot(fresh);
-    if (claim == 0) return;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int leader = __ffsll((long long)claim) - 1;
-    int base = 0;
-    if (lane == leader) base = atomicAdd(&a.result[0], __popcll(claim));
-    base = __shfl(base, leader);
+    int mine;
+    const int claimed = block_exclusive_scan(fresh ? 1 : 0, 0, mine);
+    if (claimed == 0) return;
+    if (threadIdx.x == 0) range_base = atomicAdd(&a.result[0], claimed);
+    __syncthreads();
     if (fresh) {
-        const int l = base + __popcll(claim & ((1ull << lane) - 1));
-        a.vals[slot] = l;
+        const int l = range_base + mine;
+        a.table[slot].val = l;
         a.unique_gid[l] = gid;
     }
 }
@@ -245,7 +254,7 @@ int64_t table_slots(int64_t n)
 }
 
 struct Layout {
-    size_t keys, vals, lid, slot_of, block_cnt, total;
+    size_t table, slot_of, block_cnt, total;
 };
 
 Layout layout(int64_t n)
@@ -253,9 +262,7 @@ Layout layout(int64_t n)
     const int64_t cap = table_slots(n);
     Layout L;
     size_t off = 0;
-    L.keys = off; off += align_up((size_t)cap * 8, 256);
-    L.vals = off; off += align_up((size_t)cap * 4, 256);
-    L.lid = off; off += align_up((size_t)cap * 4, 256);
+    L.table = off; off += align_up((size_t)cap * sizeof(Slot), 256);
     L.slot_of = off; off += align_up((size_t)(n > 0 ? n : 1) * 4, 256);
     L.block_cnt = off; off += align_up((size_t)(ceil_div(n, kScanBlock) + 1) * 4, 256);
     L.total = off;
@@ -320,9 +327,7 @@ fastgl_status fastgl_idmap(const int64_t *dst_gid, int64_t n_dst, const int64_t 
     IdmapArgs a = {};
     a.dst_gid = dst_gid; a.nbr_gid = nbr_gid;
     a.n_dst = n_dst; a.n_nbr = n_nbr; a.n = n;
-    a.keys = (int64_t *)(ws + L.keys);
-    a.vals = (int32_t *)(ws + L.vals);
-    a.lid = (int32_t *)(ws + L.lid);
+    a.table = (Slot *)(ws + L.table);
     a.slot_of = (int32_t *)(ws + L.slot_of);
     a.block_cnt = (int32_t *)(ws + L.block_cnt);
     a.local_nbr = local_nbr; a.unique_gid = unique_gid; a.result = result;
@@ -336,7 +341,7 @@ fastgl_status fastgl_idmap(const int64_t *dst_gid, int64_t n_dst, const int64_t 
     hipStream_t s = (hipStream_t)stream;
     auto grid = [](int64_t items, int per) { return dim3((unsigned)(items > 0 ? ceil_div(items, per) : 1)); };
 
-    hipLaunchKernelGGL(k_idmap_fill, grid(a.cap / 4, 256), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_idmap_fill, grid(a.cap, 256), dim3(256), 0, s, a);
     FASTGL_LAUNCH_CHECK("fastgl_idmap (fill)");
     if (a.fused) {
         if (n_dst > 0) {
@@ -344,7 +349,7 @@ fastgl_status fastgl_idmap(const int64_t *dst_gid, int64_t n_dst, const int64_t 
             FASTGL_LAUNCH_CHECK("fastgl_idmap (destinations)");
         }
         if (n_nbr > 0) {
-            hipLaunchKernelGGL(k_idmap_fused_nbr, grid(n_nbr, 256), dim3(256), 0, s, a);
+            hipLaunchKernelGGL(k_idmap_fused_nbr, grid(n_nbr, kScanBlock), dim3(kScanBlock), 0, s, a);
             FASTGL_LAUNCH_CHECK("fastgl_idmap (fused map)");
         }
     } else if (n > 0) {
