@@ -44,6 +44,60 @@ MFMA_F32_PEAK_TFLOPS = 157.3
 HIDDEN, CLASSES = 256, 47          # hidden width of the benchmark's configs; class count of the products-shaped stand-in
 
 
+def idmap_leg(args, w, B, bg, torch, np, with_cpu):
+    """Extra leg (not the headline metric): the ID map of the sample phase (paper Section 2.2;
+    Section 4.3, Algorithm 2) for every hop of the same mini-batch: destination global IDs + sampled
+    neighbour global IDs (scrambled 40-bit IDs) -> the block's `indices` and its source-node list."""
+    dev = torch.device("cuda:0")
+    hops = []
+    for i, blk in enumerate(w.blocks):
+        dst, nbr = bg.hop_global_ids(blk, w.seed + i)
+        h = dict(dst=torch.from_numpy(dst).to(dev), nbr=torch.from_numpy(nbr).to(dev), host=(dst, nbr), blk=blk)
+        n = dst.size + nbr.size
+        h["ws"] = torch.empty(B.fastgl_idmap_workspace_bytes(dst.size, nbr.size), dtype=torch.uint8, device=dev)
+        h["local"] = torch.empty(nbr.size, dtype=torch.int32, device=dev)
+        h["uniq"] = torch.empty(n, dtype=torch.int64, device=dev)
+        h["res"] = torch.empty(2, dtype=torch.int32, device=dev)
+        # table fill + one entry touched per ID + IDs in + slot array out and in + indices out + source list out
+        h["bytes"] = 16 * B.fastgl_idmap_table_slots(n) + 16 * n + 8 * n + 8 * n + 4 * nbr.size + 8 * blk.num_src
+        hops.append(h)
+    n_ids = sum(h["dst"].numel() + h["nbr"].numel() for h in hops)
+    out = {"what": "global -> local IDs of every hop of the mini-batch (64-bit IDs, hash table with "
+                   "compare-and-swap insertion); 'ordered' numbers by first appearance (reproducible), "
+                   "'fused' by a counter as the paper's Algorithm 2 does",
+           "ids_per_step": n_ids}
+    reps = max(5, args.steps // 2)
+    for mode in ("ordered", "fused"):
+        def run():
+            for h in hops:
+                B.fastgl_idmap(h["dst"], h["nbr"], mode, h["local"], h["uniq"], h["res"], h["ws"])
+        for _ in range(3):
+            run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        for h in hops:                       # the result of the last run must be a clean map of the right size
+            U, bad = (int(x) for x in h["res"].cpu().numpy())
+            assert bad == 0 and U == h["blk"].num_src, (mode, U, bad)
+        out[mode] = {"ms": round(ms, 4), "gids_per_s": round(n_ids / ms / 1e6, 3),
+                     "hbm_gbps_algorithmic": round(sum(h["bytes"] for h in hops) / ms / 1e6, 1),
+                     "hbm_frac_of_peak": round(sum(h["bytes"] for h in hops) / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    if with_cpu:
+        import oracle
+        t0 = time.perf_counter()
+        for h in hops:
+            oracle.idmap(*h["host"])
+        dt = time.perf_counter() - t0
+        out["cpu_oracle"] = {"gids_per_s": round(n_ids / dt / 1e9, 5), "cores": 1, "kind": "oracle",
+                             "sample": f"one pass over all {len(hops)} hops (sort-based definition), {dt:.1f} s"}
+    return out
+
+
 def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
     """Extra leg (not the headline metric): one training step of the whole sampled GCN on the same
     mini-batch - per layer aggregate (Eq. 1) then update (Eq. 2, Y = act(H W + b)), ReLU between
@@ -152,6 +206,8 @@ def main() -> int:
     ap.add_argument("--width", type=int, default=32, help="feature width of config 5")
     ap.add_argument("--fanout-order", default="A", choices=["A", "B"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-idmap", action="store_true",
+                    help="skip the extra leg that times the ID map (global -> local IDs) of the mini-batch's hops")
     ap.add_argument("--no-gcn-step", action="store_true",
                     help="skip the extra leg that times the whole sampled GCN (aggregation + update phase)")
     ap.add_argument("--verbose", action="store_true")
@@ -335,6 +391,8 @@ def main() -> int:
         "gen_seconds": round(gen_s, 2),
     }
 
+    if not args.no_idmap:
+        result["idmap"] = idmap_leg(args, w, B, bg, torch, np, with_cpu=not args.no_cpu_baseline)
     if not args.no_gcn_step and w.dtype == "f32" and len(layers) > 1:
         result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np)
 
