@@ -379,6 +379,22 @@ def random_block(rng: np.random.Generator, num_dst: int, num_src: int, avg_deg: 
     return blk
 
 
+def minibatch_node_sets(n_batches: int, seed: int, n: int = 2_400_000, avg: float = 50.0, gamma: float = 2.1,
+                        n_seeds: int = 8000, fanouts: Sequence[int] = (15, 10, 5)):
+    """Node sets of several mini-batches sampled from ONE graph (the products-shaped Chung-Lu graph
+    by default): for each mini-batch the global IDs of the source nodes of its input-layer block, in
+    local-ID order (distinct).  These are the nodes whose features a mini-batch needs; consecutive
+    mini-batches share many of them (the hubs), which is what the Match process exploits."""
+    g = ChungLu(n, avg, gamma, math.sqrt(n * avg), seed)
+    out = []
+    for b in range(n_batches):
+        rng = np.random.Generator(np.random.PCG64([seed, b]))
+        seeds = _sample_distinct(rng, n, n_seeds)
+        _, src_rank = _sampled_layers(g, rng, seeds, list(fanouts))
+        out.append(g.global_id(src_rank).astype(np.int64))
+    return out
+
+
 def hop_global_ids(blk: Block, seed: int, bits: int = 40):
     """Global IDs for the nodes of a block: local ID l -> (l * A + C) mod 2^bits with A odd, which
     is one-to-one.  Returns (dst_gid int64[num_dst], nbr_gid int64[E]): what a sampler hands to

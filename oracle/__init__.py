@@ -1,5 +1,5 @@
 """ctypes front end of the CPU oracle (oracle/fastgl_oracle.c, oracle/update_oracle.c,
-oracle/idmap_oracle.c).
+oracle/idmap_oracle.c, oracle/match_oracle.c).
 
 TEST INFRASTRUCTURE ONLY.  Only tests/, the smoke check and the benchmark's
 cpu_baseline leg may import this package; the product path never does.  It
@@ -8,7 +8,8 @@ works on host numpy arrays and imports nothing from the GPU package.
 Formulas: paper Section 2.1 Eq. 1 (forward) and Section 4.2 Eq. 5 (backward,
 read as the transpose of Eq. 1 applied to the upstream gradient); Section 2.1
 Eq. 2 (update phase, read as the GCN dense transform act(H W + b)); Section 2.2 and Section 4.3,
-Algorithm 2 (ID map: global IDs to consecutive local IDs).
+Algorithm 2 (ID map: global IDs to consecutive local IDs); Section 4.1 (Match process, match degree,
+Algorithm 1: Greedy Reorder Strategy).
 """
 from __future__ import annotations
 
@@ -20,7 +21,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fastgl_oracle.c")
-_SRCS = [_SRC, os.path.join(_HERE, "update_oracle.c"), os.path.join(_HERE, "idmap_oracle.c")]
+_SRCS = [_SRC, os.path.join(_HERE, "update_oracle.c"), os.path.join(_HERE, "idmap_oracle.c"),
+         os.path.join(_HERE, "match_oracle.c")]
 _LIB = os.path.join(_HERE, "libfastgl_oracle.so")
 
 MODES = {"sum": 0, "mean": 1, "gcn": 2}
@@ -68,6 +70,14 @@ def lib():
         L.fastgl_oracle_update_fwd.restype = i32
         L.fastgl_oracle_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p]
         L.fastgl_oracle_update_bwd.restype = i32
+        L.fastgl_oracle_match.argtypes = [p, i64, p, i64, p, p, p]
+        L.fastgl_oracle_match.restype = i64
+        L.fastgl_oracle_overlap.argtypes = [p, i64, p, i64]
+        L.fastgl_oracle_overlap.restype = i64
+        L.fastgl_oracle_greedy_reorder.argtypes = [p, p, i64, p]
+        L.fastgl_oracle_greedy_reorder.restype = i32
+        L.fastgl_oracle_assemble.argtypes = [p, p, p, i64, i64, i64, p]
+        L.fastgl_oracle_assemble.restype = i32
         L.fastgl_oracle_idmap.argtypes = [p, i64, p, i64, p, p]
         L.fastgl_oracle_idmap.restype = i64
         L.fastgl_oracle_fused_map_seq.argtypes = [p, i64, i64, p, p, p]
@@ -251,3 +261,66 @@ def fused_map_sequential(ids, table_size):
     if U < 0:
         raise RuntimeError("hash table full")
     return key, value, local, int(U)
+
+
+def _i64(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def match(prev_gid, new_gid):
+    """Match process (Section 4.1): returns (match_row int32[n_new] = row in the last mini-batch or
+    -1, load_pos int32[n_load] ascending, load_gid int64[n_load])."""
+    prev, new = _i64(prev_gid), _i64(new_gid)
+    mrow = np.empty(new.shape[0], np.int32)
+    lpos = np.empty(new.shape[0], np.int32)
+    lgid = np.empty(new.shape[0], np.int64)
+    k = lib().fastgl_oracle_match(_ptr(prev), prev.shape[0], _ptr(new), new.shape[0], _ptr(mrow), _ptr(lpos),
+                                  _ptr(lgid))
+    if k == -2:
+        raise ValueError("IDs of the last mini-batch repeat")
+    if k < 0:
+        raise RuntimeError(f"oracle returned {k}")
+    return mrow, lpos[:k].copy(), lgid[:k].copy()
+
+
+def overlap(a, b) -> int:
+    a, b = _i64(a), _i64(b)
+    return int(lib().fastgl_oracle_overlap(_ptr(a), a.shape[0], _ptr(b), b.shape[0]))
+
+
+def match_degree(a, b) -> float:
+    """M_ij = N_o / min(N_i, N_j) (Section 4.1)."""
+    return overlap(a, b) / min(len(a), len(b))
+
+
+def overlap_matrix(batches):
+    n = len(batches)
+    O = np.zeros((n, n), np.int64)
+    for i in range(n):
+        for j in range(n):
+            O[i, j] = len(batches[i]) if i == j else overlap(batches[i], batches[j])
+    return O
+
+
+def greedy_reorder(overlap_counts, sizes):
+    """Algorithm 1: returns the ReorderedList as 0-based mini-batch indices."""
+    O, sz = _i64(overlap_counts), _i64(sizes)
+    n = sz.shape[0]
+    assert O.shape == (n, n)
+    order = np.empty(n, np.int32)
+    if lib().fastgl_oracle_greedy_reorder(_ptr(O), _ptr(sz), n, _ptr(order)):
+        raise RuntimeError("oracle failed")
+    return order
+
+
+def assemble(X_prev, X_load, match_row):
+    X_prev, X_load = np.ascontiguousarray(X_prev), np.ascontiguousarray(X_load)
+    mrow = _i32(match_row)
+    assert X_prev.dtype == X_load.dtype and X_prev.shape[1:] == X_load.shape[1:]
+    feat = X_prev.shape[1]
+    out = np.empty((mrow.shape[0], feat), X_prev.dtype)
+    assert int((mrow < 0).sum()) == X_load.shape[0]
+    if lib().fastgl_oracle_assemble(_ptr(X_prev), _ptr(X_load), _ptr(mrow), mrow.shape[0], feat,
+                                    X_prev.dtype.itemsize, _ptr(out)):
+        raise RuntimeError("oracle failed")
+    return out
