@@ -27,7 +27,10 @@ EXPORTS = [
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
     "fastgl_update_fwd", "fastgl_update_bwd", "fastgl_update_bwd_workspace_bytes", "fastgl_update_slab_rows",
     "fastgl_idmap", "fastgl_idmap_table_slots", "fastgl_idmap_workspace_bytes",
+    "fastgl_match", "fastgl_match_workspace_bytes", "fastgl_assemble_rows", "fastgl_overlap_counts",
+    "fastgl_overlap_workspace_bytes", "fastgl_greedy_reorder",
 ]
+MAX_REORDER_BATCHES = 64
 IDMAP_MODES = {"ordered": 0, "fused": 1}
 
 
@@ -81,6 +84,15 @@ def lib() -> ctypes.CDLL:
         L.fastgl_update_bwd_workspace_bytes.argtypes = [i64, i64, i64]
         L.fastgl_update_bwd_workspace_bytes.restype = sz
         L.fastgl_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p, p, sz, p]
+        L.fastgl_match_workspace_bytes.argtypes = [i64, i64]
+        L.fastgl_match_workspace_bytes.restype = sz
+        L.fastgl_match.argtypes = [p, i64, p, i64, p, p, p, p, p, sz, p]
+        L.fastgl_assemble_rows.argtypes = [p, i64, p, i64, p, i64, i64, i32, p, p]
+        L.fastgl_overlap_workspace_bytes.argtypes = [i64]
+        L.fastgl_overlap_workspace_bytes.restype = sz
+        L.fastgl_overlap_counts.argtypes = [p, ctypes.POINTER(i64), i32, p, p, p, sz, p]
+        L.fastgl_greedy_reorder.argtypes = [ctypes.POINTER(i64), ctypes.POINTER(i64), i64,
+                                            ctypes.POINTER(ctypes.c_int32)]
         L.fastgl_idmap_table_slots.argtypes = [i64]
         L.fastgl_idmap_table_slots.restype = i64
         L.fastgl_idmap_workspace_bytes.argtypes = [i64, i64]
@@ -353,3 +365,83 @@ def fastgl_idmap(dst_gid: torch.Tensor, nbr_gid: torch.Tensor, mode: str = "orde
     _check(lib().fastgl_idmap(_ptr(dst_gid), n_dst, _ptr(nbr_gid), n_nbr, IDMAP_MODES[mode], _ptr(local_nbr),
                               _ptr(unique_gid), _ptr(result), _ptr(workspace), workspace.numel(), _stream()))
     return local_nbr, unique_gid, result
+
+
+def fastgl_match_workspace_bytes(n_prev: int, n_new: int) -> int:
+    return int(lib().fastgl_match_workspace_bytes(n_prev, n_new))
+
+
+def fastgl_match(prev_gid: torch.Tensor, new_gid: torch.Tensor, src_row=None, load_pos=None, load_gid=None,
+                 result=None, workspace=None):
+    """Returns (src_row int32[n_new], load_pos int32[n_new], load_gid int64[n_new], result int32[2]) on
+    the device, nothing synchronised: result[0] = rows to load, result[1] = violations."""
+    _dev(prev_gid, torch.int64, "prev_gid")
+    _dev(new_gid, torch.int64, "new_gid")
+    n_prev, n_new, dev = prev_gid.numel(), new_gid.numel(), new_gid.device
+    src_row = torch.empty(n_new, dtype=torch.int32, device=dev) if src_row is None else src_row
+    load_pos = torch.empty(n_new, dtype=torch.int32, device=dev) if load_pos is None else load_pos
+    load_gid = torch.empty(n_new, dtype=torch.int64, device=dev) if load_gid is None else load_gid
+    result = torch.empty(2, dtype=torch.int32, device=dev) if result is None else result
+    if workspace is None:
+        workspace = torch.empty(fastgl_match_workspace_bytes(n_prev, n_new), dtype=torch.uint8, device=dev)
+    _dev(src_row, torch.int32, "src_row")
+    _dev(load_pos, torch.int32, "load_pos")
+    _dev(load_gid, torch.int64, "load_gid")
+    _dev(result, torch.int32, "result")
+    if min(src_row.numel(), load_pos.numel(), load_gid.numel()) < n_new or result.numel() < 2:
+        raise ValueError("output arrays too small")
+    _check(lib().fastgl_match(_ptr(prev_gid), n_prev, _ptr(new_gid), n_new, _ptr(src_row), _ptr(load_pos),
+                              _ptr(load_gid), _ptr(result), _ptr(workspace), workspace.numel(), _stream()))
+    return src_row, load_pos, load_gid, result
+
+
+def fastgl_assemble_rows(X_prev: torch.Tensor, X_load: torch.Tensor, src_row: torch.Tensor, n_load: int,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """X_load may have more rows than n_load (a buffer sized for the worst case); the first n_load count."""
+    dt = _feat_dtype(X_prev)
+    _dev(X_prev, X_prev.dtype, "X_prev")
+    _dev(X_load, X_prev.dtype, "X_load")
+    _dev(src_row, torch.int32, "src_row")
+    feat, n_new = X_prev.shape[1], src_row.numel()
+    if X_load.shape[1] != feat or X_load.shape[0] < n_load:
+        raise ValueError("X_load must be [>= n_load, feat]")
+    if out is None:
+        out = torch.empty((n_new, feat), dtype=X_prev.dtype, device=X_prev.device)
+    _dev(out, X_prev.dtype, "out")
+    if tuple(out.shape) != (n_new, feat):
+        raise ValueError("out must be [n_new, feat]")
+    _check(lib().fastgl_assemble_rows(_ptr(X_prev), X_prev.shape[0], _ptr(X_load), n_load, _ptr(src_row), n_new,
+                                      feat, dt, _ptr(out), _stream()))
+    return out
+
+
+def fastgl_overlap_workspace_bytes(total_ids: int) -> int:
+    return int(lib().fastgl_overlap_workspace_bytes(total_ids))
+
+
+def fastgl_overlap_counts(gid: torch.Tensor, offsets, workspace: Optional[torch.Tensor] = None):
+    """gid: the node lists of n mini-batches one after the other (device int64); offsets: n+1 host
+    ints.  Returns (counts int64[n,n], violations int32[1]) on the device."""
+    _dev(gid, torch.int64, "gid")
+    n = len(offsets) - 1
+    off = (ctypes.c_int64 * (n + 1))(*[int(x) for x in offsets])
+    counts = torch.empty((n, n), dtype=torch.int64, device=gid.device)
+    viol = torch.empty(1, dtype=torch.int32, device=gid.device)
+    if workspace is None:
+        workspace = torch.empty(fastgl_overlap_workspace_bytes(gid.numel()), dtype=torch.uint8, device=gid.device)
+    _check(lib().fastgl_overlap_counts(_ptr(gid), off, n, _ptr(counts), _ptr(viol), _ptr(workspace),
+                                       workspace.numel(), _stream()))
+    return counts, viol
+
+
+def fastgl_greedy_reorder(overlap, sizes):
+    """Host-side Algorithm 1: overlap = n x n nested sequence / array of ints, sizes = n ints."""
+    n = len(sizes)
+    flat = [int(x) for row in overlap for x in row]
+    if len(flat) != n * n:
+        raise ValueError("overlap must be n x n")
+    ov = (ctypes.c_int64 * max(n * n, 1))(*flat)
+    sz_ = (ctypes.c_int64 * max(n, 1))(*[int(x) for x in sizes])
+    order = (ctypes.c_int32 * max(n, 1))()
+    _check(lib().fastgl_greedy_reorder(ov, sz_, n, order))
+    return [int(order[i]) for i in range(n)]

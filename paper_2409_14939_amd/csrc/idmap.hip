@@ -14,22 +14,13 @@
 // order of first appearance.  Both remember the slot of every input ID, so translation does not
 // probe again.
 #include "fastgl_idmap.h"
+#include "hash_table.h"
 #include "internal.h"
 
 namespace fastgl {
 namespace {
 
-constexpr int kScanBlock = 1024;             // threads (= positions) per block of the ordered mode's passes
-constexpr int64_t kMaxIds = (int64_t)1 << 30;
-constexpr int32_t kNoSlot = 0x7FFFFFFF;      // no table has this many slots
 constexpr int32_t kFirstBit = (int32_t)0x80000000u;
-
-// One table entry: the key and what is looked up through it share a 16-byte line piece.
-struct __attribute__((aligned(16))) Slot {
-    int64_t key;              // global ID, -1 while empty
-    int32_t val;              // ORDERED: smallest position seen; FUSED: local ID
-    int32_t lid;              // ORDERED: local ID
-};
 
 struct IdmapArgs {
     const int64_t *dst_gid, *nbr_gid;
@@ -51,32 +42,6 @@ struct IdmapArgs {
 __device__ __forceinline__ int64_t id_at(const IdmapArgs &a, int64_t p)
 {
     return p < a.n_dst ? a.dst_gid[p] : a.nbr_gid[p - a.n_dst];
-}
-
-__device__ __forceinline__ uint32_t hash_slot(int64_t gid, int shift)
-{
-    return (uint32_t)(((uint64_t)gid * 0x9E3779B97F4A7C15ull) >> shift);
-}
-
-// Slot that holds gid after the call; fresh = this thread put it there.  Ends because at most half
-// of the slots are ever taken.
-__device__ __forceinline__ uint32_t insert_id(Slot *table, uint32_t mask, int shift, int64_t gid, bool &fresh)
-{
-    uint32_t slot = hash_slot(gid, shift);
-    fresh = false;
-    for (;;) {
-        int64_t k = __hip_atomic_load(&table[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (k == -1) {
-            k = (int64_t)atomicCAS((unsigned long long *)&table[slot].key, (unsigned long long)-1ll,
-                                   (unsigned long long)gid);
-            if (k == -1) {
-                fresh = true;
-                return slot;
-            }
-        }
-        if (k == gid) return slot;
-        slot = (slot + 1) & mask;
-    }
 }
 
 __global__ __launch_bounds__(256) void k_idmap_fill(IdmapArgs a)
@@ -128,53 +93,11 @@ __global__ __launch_bounds__(kScanBlock) void k_idmap_count(IdmapArgs a)
     if (threadIdx.x == 0) a.block_cnt[blockIdx.x] = c;
 }
 
-// Exclusive prefix sum over `count` ints in place (count <= kScanBlock) by one workgroup; returns the
-// total to every thread.  `base` is added to every result.
-__device__ int block_exclusive_scan(int v, int base, int &out_excl)
-{
-    __shared__ int wave_sum[kScanBlock / kWave];
-    __shared__ int total_s;
-    const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x / kWave;
-    int incl = v;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int t = __shfl_up(incl, d);
-        if (lane >= d) incl += t;
-    }
-    if (lane == kWave - 1) wave_sum[wv] = incl;
-    __syncthreads();
-    if (wv == 0) {
-        const int nw = blockDim.x / kWave;
-        int w = lane < nw ? wave_sum[lane] : 0;
-        int wi = w;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int t = __shfl_up(wi, d);
-            if (lane >= d) wi += t;
-        }
-        if (lane < nw) wave_sum[lane] = wi - w;
-        if (lane == nw - 1) total_s = wi;
-    }
-    __syncthreads();
-    out_excl = base + wave_sum[wv] + incl - v;
-    const int total = total_s;
-    __syncthreads();
-    return total;
-}
-
 // ORDERED pass 3: block counts -> block offsets, total -> result[0].  One workgroup.
 __global__ __launch_bounds__(kScanBlock) void k_idmap_scan(IdmapArgs a)
 {
-    int running = 0;
-    for (int b0 = 0; b0 < a.nblocks; b0 += kScanBlock) {
-        const int b = b0 + threadIdx.x;
-        const int v = b < a.nblocks ? a.block_cnt[b] : 0;
-        int excl;
-        const int total = block_exclusive_scan(v, running, excl);
-        if (b < a.nblocks) a.block_cnt[b] = excl;
-        running += total;
-    }
-    if (threadIdx.x == 0) a.result[0] = running;
+    const int total = scan_block_counts(a.block_cnt, a.nblocks);
+    if (threadIdx.x == 0) a.result[0] = total;
 }
 
 // ORDERED pass 4: rank of every first occurrence = its local ID.
@@ -244,13 +167,6 @@ __global__ __launch_bounds__(kScanBlock) void k_idmap_fused_nbr(IdmapArgs a)
         a.table[slot].val = l;
         a.unique_gid[l] = gid;
     }
-}
-
-int64_t table_slots(int64_t n)
-{
-    int64_t cap = 1024;
-    while (cap < 2 * n) cap *= 2;
-    return cap;
 }
 
 struct Layout {
@@ -333,9 +249,7 @@ fastgl_status fastgl_idmap(const int64_t *dst_gid, int64_t n_dst, const int64_t 
     a.local_nbr = local_nbr; a.unique_gid = unique_gid; a.result = result;
     a.cap = table_slots(n);
     a.mask = (uint32_t)(a.cap - 1);
-    int lg = 0;
-    while (((int64_t)1 << lg) < a.cap) ++lg;
-    a.shift = 64 - lg;
+    a.shift = table_shift(a.cap);
     a.nblocks = (int)ceil_div(n, kScanBlock);
     a.fused = mode == FASTGL_IDMAP_FUSED;
     hipStream_t s = (hipStream_t)stream;

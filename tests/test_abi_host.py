@@ -125,3 +125,44 @@ def test_idmap_argument_checks():
     assert "aligned" in B.fastgl_last_error()
     assert f(FAKE, 4, FAKE, 4, 0, FAKE, FAKE, FAKE, None, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
     assert f(FAKE, 4, FAKE, 4, 0, FAKE, FAKE, FAKE, FAKE, 64, None) == B.FASTGL_ERR_WORKSPACE
+
+
+def test_match_argument_checks_and_host_reorder():
+    L = B.lib()
+    assert B.fastgl_match_workspace_bytes(1000, 10) >= 16 * 2048
+    assert B.fastgl_match_workspace_bytes(-1, 10) == 0 and B.fastgl_overlap_workspace_bytes(-1) == 0
+    assert B.fastgl_overlap_workspace_bytes(1000) >= 16 * 2048 + 4000
+    m = L.fastgl_match
+    assert m(FAKE, -1, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert m(FAKE, 2 ** 30, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == B.FASTGL_ERR_UNSUPPORTED
+    assert m(FAKE, 4, None, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert m(FAKE, 4, FAKE, 4, FAKE, FAKE, FAKE, FAKE, None, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert m(FAKE, 4, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 64, None) == B.FASTGL_ERR_WORKSPACE
+    a = L.fastgl_assemble_rows
+    assert a(FAKE, 4, FAKE, 4, FAKE, 4, 0, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert a(FAKE, 4, FAKE, 4, FAKE, 4, 8, 2, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert a(FAKE, 4, FAKE, 4, None, 4, 8, 0, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert a(FAKE, 4, FAKE, 4, FAKE, 0, 8, 0, None, None) == B.FASTGL_OK                    # nothing to do
+    off = (ctypes.c_int64 * 3)(0, 5, 3)
+    o = L.fastgl_overlap_counts
+    assert o(FAKE, off, 2, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "offsets" in B.fastgl_last_error()
+    assert o(FAKE, off, 65, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    # Algorithm 1 runs on the host: no GPU needed
+    assert B.fastgl_greedy_reorder([], []) == []
+    assert B.fastgl_greedy_reorder([[7]], [7]) == [0]
+    O = [[9, 5, 4, 0], [5, 9, 0, 1], [4, 0, 9, 8], [0, 1, 8, 9]]
+    assert B.fastgl_greedy_reorder(O, [9, 9, 9, 9]) == [0, 1, 3, 2]
+    assert B.fastgl_greedy_reorder([[10, 2, 5], [2, 10, 0], [5, 0, 10]], [10, 10, 10]) == [0, 2, 1]
+    assert B.fastgl_greedy_reorder([[3, 0, 0], [0, 3, 0], [0, 0, 3]], [3, 3, 3]) == [0, 1, 2]   # ties: smallest index
+
+
+def test_host_reorder_against_oracle():
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(5)
+    for n in (1, 2, 5, 9, 17):
+        sets = [rng.choice(80, size=int(rng.integers(4, 40)), replace=False) for _ in range(n)]
+        sizes = [len(s) for s in sets]
+        O = oracle.overlap_matrix(sets)
+        assert B.fastgl_greedy_reorder(O.tolist(), sizes) == oracle.greedy_reorder(O, sizes).tolist()
