@@ -98,6 +98,92 @@ def idmap_leg(args, w, B, bg, torch, np, with_cpu):
     return out
 
 
+def match_leg(args, w, B, bg, torch, np):
+    """Extra leg (not the headline metric): the Match process and the Greedy Reorder Strategy (paper
+    Section 4.1) over several mini-batches sampled from ONE products-shaped graph.  The raw features
+    sit in a device-resident table; with Match only the rows that the last mini-batch does not hold
+    are gathered from it, the rest is copied from the last mini-batch's feature matrix."""
+    dev = torch.device("cuda:0")
+    nb, feat, n_nodes = args.match_batches, w.widths[0], 2_400_000
+    t0 = time.time()
+    sets = bg.minibatch_node_sets(nb, w.seed)
+    gen_s = time.time() - t0
+    sizes = [len(x) for x in sets]
+    offsets = [0] + [int(x) for x in np.cumsum(sizes)]
+    allg = torch.from_numpy(np.concatenate(sets)).to(dev)
+    gids = [allg[offsets[i]:offsets[i + 1]] for i in range(nb)]
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed + 2)
+    table = torch.empty((n_nodes, feat), device=dev)
+    for lo in range(0, n_nodes, 600_000):
+        table[lo:lo + 600_000] = torch.randn((min(600_000, n_nodes - lo), feat), generator=g, device=dev)
+    reps = max(5, args.steps // 2)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ows = torch.empty(B.fastgl_overlap_workspace_bytes(allg.numel()), dtype=torch.uint8, device=dev)
+    counts, viol = B.fastgl_overlap_counts(allg, offsets, ows)
+    overlap_ms = timed(lambda: B.fastgl_overlap_counts(allg, offsets, ows))
+    O = counts.cpu().numpy()
+    assert int(viol.cpu()[0]) == 0
+    order = B.fastgl_greedy_reorder(O.tolist(), sizes)
+
+    def loaded(seq):
+        return sizes[seq[0]] + sum(sizes[b] - int(O[a, b]) for a, b in zip(seq[:-1], seq[1:]))
+    plain = list(range(nb))
+    needed = sum(sizes)
+
+    # one transition of the reordered list, timed step by step
+    a, b = order[0], order[1]
+    mws = torch.empty(B.fastgl_match_workspace_bytes(sizes[a], sizes[b]), dtype=torch.uint8, device=dev)
+    src_row, load_pos, load_gid, res = B.fastgl_match(gids[a], gids[b], workspace=mws)
+    n_load, bad = (int(x) for x in res.cpu().numpy())
+    assert bad == 0 and n_load == sizes[b] - int(O[a, b])
+    X_prev = B.fastgl_gather_rows(table, gids[a])
+    X_load = torch.empty((sizes[b], feat), device=dev)
+    X_new = torch.empty((sizes[b], feat), device=dev)
+    match_ms = timed(lambda: B.fastgl_match(gids[a], gids[b], src_row, load_pos, load_gid, res, mws))
+    gather_load_ms = timed(lambda: B.fastgl_gather_rows(table, load_gid[:n_load], out=X_load[:n_load]))
+    assemble_ms = timed(lambda: B.fastgl_assemble_rows(X_prev, X_load, src_row, n_load, out=X_new))
+    gather_all_ms = timed(lambda: B.fastgl_gather_rows(table, gids[b], out=X_new))
+    B.fastgl_assemble_rows(X_prev, X_load, src_row, n_load, out=X_new)
+    ref = B.fastgl_gather_rows(table, gids[b])
+    assert torch.equal(X_new, ref), "Match + assemble must equal loading every row"
+    row_bytes = feat * 4
+    asm_bytes = 2 * sizes[b] * row_bytes + 4 * sizes[b]
+    return {
+        "what": f"{nb} mini-batches sampled from one products-shaped graph; features ({feat} x f32) in a device table",
+        "nodes_per_minibatch": sizes, "gen_seconds": round(gen_s, 1),
+        "match_degree_mean": round(float(np.mean([O[i, j] / min(sizes[i], sizes[j]) for i in range(nb)
+                                                  for j in range(i)])), 4),
+        "rows_needed": needed, "rows_loaded_sampled_order": loaded(plain), "rows_loaded_reordered": loaded(order),
+        "load_fraction_sampled_order": round(loaded(plain) / needed, 4),
+        "load_fraction_reordered": round(loaded(order) / needed, 4),
+        "order": order,
+        "overlap_counts_ms": round(overlap_ms, 4),
+        "overlap_gids_per_s": round(allg.numel() / overlap_ms / 1e6, 3),
+        "transition": {"from": a, "to": b, "n_new": sizes[b], "n_load": n_load,
+                       "match_ms": round(match_ms, 4),
+                       "match_gids_per_s": round((sizes[a] + sizes[b]) / match_ms / 1e6, 3),
+                       "gather_loaded_rows_ms": round(gather_load_ms, 4),
+                       "assemble_ms": round(assemble_ms, 4),
+                       "assemble_hbm_gbps": round(asm_bytes / assemble_ms / 1e6, 1),
+                       "assemble_hbm_frac_of_peak": round(asm_bytes / assemble_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                       "with_match_ms": round(match_ms + gather_load_ms + assemble_ms, 4),
+                       "gather_every_row_ms": round(gather_all_ms, 4)},
+    }
+
+
 def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
     """Extra leg (not the headline metric): one training step of the whole sampled GCN on the same
     mini-batch - per layer aggregate (Eq. 1) then update (Eq. 2, Y = act(H W + b)), ReLU between
@@ -208,6 +294,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-idmap", action="store_true",
                     help="skip the extra leg that times the ID map (global -> local IDs) of the mini-batch's hops")
+    ap.add_argument("--no-match", action="store_true",
+                    help="skip the extra leg that times Match / Reorder over several mini-batches of one graph")
+    ap.add_argument("--match-batches", type=int, default=4)
     ap.add_argument("--no-gcn-step", action="store_true",
                     help="skip the extra leg that times the whole sampled GCN (aggregation + update phase)")
     ap.add_argument("--verbose", action="store_true")
@@ -393,6 +482,8 @@ def main() -> int:
 
     if not args.no_idmap:
         result["idmap"] = idmap_leg(args, w, B, bg, torch, np, with_cpu=not args.no_cpu_baseline)
+    if not args.no_match and args.config == 2:
+        result["match_reorder"] = match_leg(args, w, B, bg, torch, np)
     if not args.no_gcn_step and w.dtype == "f32" and len(layers) > 1:
         result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np)
 
