@@ -1,5 +1,5 @@
 """ctypes front end of the CPU oracle (oracle/fastgl_oracle.c, oracle/update_oracle.c,
-oracle/idmap_oracle.c, oracle/match_oracle.c).
+oracle/idmap_oracle.c, oracle/match_oracle.c, oracle/edge_oracle.c).
 
 TEST INFRASTRUCTURE ONLY.  Only tests/, the smoke check and the benchmark's
 cpu_baseline leg may import this package; the product path never does.  It
@@ -9,7 +9,8 @@ Formulas: paper Section 2.1 Eq. 1 (forward) and Section 4.2 Eq. 5 (backward,
 read as the transpose of Eq. 1 applied to the upstream gradient); Section 2.1
 Eq. 2 (update phase, read as the GCN dense transform act(H W + b)); Section 2.2 and Section 4.3,
 Algorithm 2 (ID map: global IDs to consecutive local IDs); Section 4.1 (Match process, match degree,
-Algorithm 1: Greedy Reorder Strategy).
+Algorithm 1: Greedy Reorder Strategy); Eq. 1 differentiated with respect to the edge weights, and
+the softmax over a target node's incoming edges that produces attention weights.
 """
 from __future__ import annotations
 
@@ -22,7 +23,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fastgl_oracle.c")
 _SRCS = [_SRC, os.path.join(_HERE, "update_oracle.c"), os.path.join(_HERE, "idmap_oracle.c"),
-         os.path.join(_HERE, "match_oracle.c")]
+         os.path.join(_HERE, "match_oracle.c"), os.path.join(_HERE, "edge_oracle.c")]
 _LIB = os.path.join(_HERE, "libfastgl_oracle.so")
 
 MODES = {"sum": 0, "mean": 1, "gcn": 2}
@@ -70,6 +71,12 @@ def lib():
         L.fastgl_oracle_update_fwd.restype = i32
         L.fastgl_oracle_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p]
         L.fastgl_oracle_update_bwd.restype = i32
+        L.fastgl_oracle_edge_weight_grad.argtypes = [p, p, i64, i64, i64, i32, i32, p, p, p, p]
+        L.fastgl_oracle_edge_weight_grad.restype = i32
+        L.fastgl_oracle_edge_softmax_fwd.argtypes = [p, i64, p, p]
+        L.fastgl_oracle_edge_softmax_fwd.restype = i32
+        L.fastgl_oracle_edge_softmax_bwd.argtypes = [p, i64, p, p, p]
+        L.fastgl_oracle_edge_softmax_bwd.restype = i32
         L.fastgl_oracle_match.argtypes = [p, i64, p, i64, p, p, p]
         L.fastgl_oracle_match.restype = i64
         L.fastgl_oracle_overlap.argtypes = [p, i64, p, i64]
@@ -322,5 +329,38 @@ def assemble(X_prev, X_load, match_row):
     assert int((mrow < 0).sum()) == X_load.shape[0]
     if lib().fastgl_oracle_assemble(_ptr(X_prev), _ptr(X_load), _ptr(mrow), mrow.shape[0], feat,
                                     X_prev.dtype.itemsize, _ptr(out)):
+        raise RuntimeError("oracle failed")
+    return out
+
+
+def edge_weight_grad(indptr, indices, num_src, mode, dtype, X, G):
+    """dL/dw_e = c_u s_v <G[u], X[v]> for every edge (Eq. 1 differentiated by its weights)."""
+    indptr, indices = _i32(indptr), _i32(indices)
+    X, G = _feat_array(X, dtype), _feat_array(G, dtype)
+    num_dst = indptr.shape[0] - 1
+    assert X.shape[0] == num_src and G.shape == (num_dst, X.shape[1])
+    gw = np.empty(indices.shape[0], np.float32)
+    scratch = np.empty(max(num_src, 1), np.int32)
+    rc = lib().fastgl_oracle_edge_weight_grad(_ptr(indptr), _ptr(indices), num_dst, num_src, X.shape[1],
+                                              MODES[mode], DTYPES[dtype], _ptr(X), _ptr(G), _ptr(scratch), _ptr(gw))
+    if rc:
+        raise RuntimeError(f"oracle returned {rc}")
+    return gw
+
+
+def edge_softmax_fwd(indptr, score):
+    indptr, score = _i32(indptr), _f32(score)
+    assert score.shape[0] == indptr[-1]
+    alpha = np.zeros_like(score)
+    if lib().fastgl_oracle_edge_softmax_fwd(_ptr(indptr), indptr.shape[0] - 1, _ptr(score), _ptr(alpha)):
+        raise RuntimeError("oracle failed")
+    return alpha
+
+
+def edge_softmax_bwd(indptr, alpha, grad_alpha):
+    indptr, alpha, grad_alpha = _i32(indptr), _f32(alpha), _f32(grad_alpha)
+    out = np.zeros_like(alpha)
+    if lib().fastgl_oracle_edge_softmax_bwd(_ptr(indptr), indptr.shape[0] - 1, _ptr(alpha), _ptr(grad_alpha),
+                                            _ptr(out)):
         raise RuntimeError("oracle failed")
     return out
