@@ -29,6 +29,8 @@ EXPORTS = [
     "fastgl_idmap", "fastgl_idmap_table_slots", "fastgl_idmap_workspace_bytes",
     "fastgl_match", "fastgl_match_workspace_bytes", "fastgl_assemble_rows", "fastgl_overlap_counts",
     "fastgl_overlap_workspace_bytes", "fastgl_greedy_reorder",
+    "fastgl_edge_workspace_bytes", "fastgl_edge_weight_grad", "fastgl_edge_softmax_fwd", "fastgl_edge_softmax_bwd",
+    "fastgl_edge_softmax_long_row",
 ]
 MAX_REORDER_BATCHES = 64
 IDMAP_MODES = {"ordered": 0, "fused": 1}
@@ -93,6 +95,12 @@ def lib() -> ctypes.CDLL:
         L.fastgl_overlap_counts.argtypes = [p, ctypes.POINTER(i64), i32, p, p, p, sz, p]
         L.fastgl_greedy_reorder.argtypes = [ctypes.POINTER(i64), ctypes.POINTER(i64), i64,
                                             ctypes.POINTER(ctypes.c_int32)]
+        L.fastgl_edge_workspace_bytes.argtypes = [i64, i64]
+        L.fastgl_edge_workspace_bytes.restype = sz
+        L.fastgl_edge_weight_grad.argtypes = [p, p, i64, i64, i64, i64, i32, i32, p, p, p, p, p, sz, p]
+        L.fastgl_edge_softmax_fwd.argtypes = [p, i64, i64, p, p, p, sz, p]
+        L.fastgl_edge_softmax_bwd.argtypes = [p, i64, i64, p, p, p, p, sz, p]
+        L.fastgl_edge_softmax_long_row.restype = ctypes.c_int32
         L.fastgl_idmap_table_slots.argtypes = [i64]
         L.fastgl_idmap_table_slots.restype = i64
         L.fastgl_idmap_workspace_bytes.argtypes = [i64, i64]
@@ -445,3 +453,72 @@ def fastgl_greedy_reorder(overlap, sizes):
     order = (ctypes.c_int32 * max(n, 1))()
     _check(lib().fastgl_greedy_reorder(ov, sz_, n, order))
     return [int(order[i]) for i in range(n)]
+
+
+def fastgl_edge_workspace_bytes(num_dst: int, num_edges: int) -> int:
+    return int(lib().fastgl_edge_workspace_bytes(num_dst, num_edges))
+
+
+def fastgl_edge_softmax_long_row() -> int:
+    return int(lib().fastgl_edge_softmax_long_row())
+
+
+def _edge_ws(indptr, num_edges, workspace):
+    if workspace is None:
+        workspace = torch.empty(fastgl_edge_workspace_bytes(indptr.numel() - 1, num_edges), dtype=torch.uint8,
+                                device=indptr.device)
+    return workspace
+
+
+def fastgl_edge_weight_grad(indptr, indices, num_src: int, mode: str, X: torch.Tensor, grad_out: torch.Tensor,
+                            plan: Optional[Plan] = None, grad_w: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    dt = _feat_dtype(X)
+    _dev(X, X.dtype, "X")
+    _dev(grad_out, X.dtype, "grad_out")
+    num_dst, num_edges, feat = indptr.numel() - 1, indices.numel(), X.shape[1]
+    if X.shape[0] != num_src or tuple(grad_out.shape) != (num_dst, feat):
+        raise ValueError("X must be [num_src, feat] and grad_out [num_dst, feat]")
+    if grad_w is None:
+        grad_w = torch.empty(num_edges, dtype=torch.float32, device=X.device)
+    _dev(grad_w, torch.float32, "grad_w")
+    if grad_w.numel() != num_edges:
+        raise ValueError("grad_w must have one entry per edge")
+    workspace = _edge_ws(indptr, num_edges, workspace)
+    _check(lib().fastgl_edge_weight_grad(_ptr(indptr), _ptr(indices), num_dst, num_src, num_edges, feat, MODES[mode],
+                                         dt, _ptr(X), _ptr(grad_out), plan.handle if plan is not None else None,
+                                         _ptr(grad_w), _ptr(workspace), workspace.numel(), _stream()))
+    return grad_w
+
+
+def fastgl_edge_softmax_fwd(indptr, score: torch.Tensor, alpha: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(indptr, torch.int32, "indptr")
+    _dev(score, torch.float32, "score")
+    alpha = torch.empty_like(score) if alpha is None else alpha
+    _dev(alpha, torch.float32, "alpha")
+    if alpha.numel() != score.numel():
+        raise ValueError("alpha must have one entry per edge")
+    workspace = _edge_ws(indptr, score.numel(), workspace)
+    _check(lib().fastgl_edge_softmax_fwd(_ptr(indptr), indptr.numel() - 1, score.numel(), _ptr(score), _ptr(alpha),
+                                         _ptr(workspace), workspace.numel(), _stream()))
+    return alpha
+
+
+def fastgl_edge_softmax_bwd(indptr, alpha: torch.Tensor, grad_alpha: torch.Tensor,
+                            grad_score: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(indptr, torch.int32, "indptr")
+    _dev(alpha, torch.float32, "alpha")
+    _dev(grad_alpha, torch.float32, "grad_alpha")
+    grad_score = torch.empty_like(alpha) if grad_score is None else grad_score
+    _dev(grad_score, torch.float32, "grad_score")
+    if grad_alpha.numel() != alpha.numel() or grad_score.numel() != alpha.numel():
+        raise ValueError("per-edge arrays must have one entry per edge")
+    workspace = _edge_ws(indptr, alpha.numel(), workspace)
+    _check(lib().fastgl_edge_softmax_bwd(_ptr(indptr), indptr.numel() - 1, alpha.numel(), _ptr(alpha),
+                                         _ptr(grad_alpha), _ptr(grad_score), _ptr(workspace), workspace.numel(),
+                                         _stream()))
+    return grad_score

@@ -166,3 +166,30 @@ def test_host_reorder_against_oracle():
         sizes = [len(s) for s in sets]
         O = oracle.overlap_matrix(sets)
         assert B.fastgl_greedy_reorder(O.tolist(), sizes) == oracle.greedy_reorder(O, sizes).tolist()
+
+
+def test_edge_argument_checks():
+    L = B.lib()
+    assert B.fastgl_edge_softmax_long_row() >= 64
+    assert B.fastgl_edge_workspace_bytes(10, 1000) >= 4000 and B.fastgl_edge_workspace_bytes(-1, 5) == 0
+    g = L.fastgl_edge_weight_grad
+
+    def grad(indptr=FAKE, indices=FAKE, nd=4, ns=4, ne=4, feat=8, mode=0, dt=0, X=FAKE, G=FAKE, plan=None, gw=FAKE,
+             ws=FAKE, wsb=1 << 30):
+        return g(indptr, indices, nd, ns, ne, feat, mode, dt, X, G, plan, gw, ws, wsb, None)
+    assert grad(nd=-1) == B.FASTGL_ERR_INVALID_ARG
+    assert grad(feat=0) == B.FASTGL_ERR_INVALID_ARG
+    assert grad(mode=3) == B.FASTGL_ERR_INVALID_ARG
+    assert grad(X=None) == B.FASTGL_ERR_INVALID_ARG
+    assert grad(mode=2) == B.FASTGL_ERR_INVALID_ARG and "plan" in B.fastgl_last_error()
+    assert grad(ws=None) == B.FASTGL_ERR_INVALID_ARG
+    assert grad(wsb=8) == B.FASTGL_ERR_WORKSPACE
+    assert grad(ne=0, indices=None, X=None) == B.FASTGL_OK                    # nothing to do
+    f = L.fastgl_edge_softmax_fwd
+    assert f(None, 4, 4, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert f(FAKE, 4, 4, None, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert f(FAKE, 4, 4, FAKE, FAKE, FAKE, 8, None) == B.FASTGL_ERR_WORKSPACE
+    assert f(FAKE, 0, 4, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    b = L.fastgl_edge_softmax_bwd
+    assert b(FAKE, 4, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
+    assert b(FAKE, 4, 0, None, None, None, None, 0, None) == B.FASTGL_OK
