@@ -21,7 +21,8 @@ namespace {
 
 constexpr int kLongRow = 1024;       // softmax rows longer than this go to the workgroup-per-row pass
 constexpr int kLongGrid = 256;       // workgroups of that pass
-constexpr int kEdgeUnroll = 4;       // edges in flight per lane group in k_edge_dot
+constexpr int kEdgeUnroll = 4;       // edges in flight per lane group in k_edge_dot (reduce4 assumes 4)
+constexpr int kEdgeSteps = 8;        // batches of that many edges per lane group
 
 // ---------------------------------------------------------------- edge -> destination row
 __global__ __launch_bounds__(256) void k_edge_rows(const int32_t *__restrict__ indptr, int64_t num_dst, int64_t E,
@@ -53,6 +54,25 @@ __device__ __forceinline__ float group_sum<float>(float v, int lanes)
 {
     for (int d = lanes >> 1; d > 0; d >>= 1) v += __shfl_xor(v, d);
     return v;
+}
+
+// Sums of four values over a group of `lanes` >= 4 lanes with 2 + 1 + (log2(lanes) - 2) exchanges
+// instead of 4 log2(lanes): the first exchange leaves each half of the group with two of the four
+// sums, the second each quarter with one, the rest finish that one.  Returns the sum of value
+// number `which` (0..3, set here) - the same in every lane of a quarter.
+template <typename ACC>
+__device__ __forceinline__ ACC reduce4(const ACC (&v)[4], int l, int lanes, int &which)
+{
+    int d = lanes >> 1;
+    const bool up = (l & d) != 0;
+    const ACC r0 = (up ? v[2] : v[0]) + __shfl_xor(up ? v[0] : v[2], d);
+    const ACC r1 = (up ? v[3] : v[1]) + __shfl_xor(up ? v[1] : v[3], d);
+    d >>= 1;
+    const bool up2 = (l & d) != 0;
+    ACC r = (up2 ? r1 : r0) + __shfl_xor(up2 ? r0 : r1, d);
+    for (d >>= 1; d > 0; d >>= 1) r += __shfl_xor(r, d);
+    which = (up ? 2 : 0) + (up2 ? 1 : 0);
+    return r;
 }
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -117,6 +137,19 @@ struct DotArgs {
     int mode;                    // 0 none, 1: 1/len, 2: 1/sqrt(len) of the destination row
 };
 
+// c_u * s_v of the aggregation mode.
+__device__ __forceinline__ double edge_scale(const DotArgs &a, int32_t u, int32_t v)
+{
+    double scale = 1.0;
+    if (a.mode) {
+        const int len = a.indptr[u + 1] - a.indptr[u];
+        const double d = len < 1 ? 1.0 : (double)len;
+        scale = a.mode == 1 ? 1.0 / d : 1.0 / sqrt(d);
+    }
+    if (a.src_scale) scale *= (double)a.src_scale[v];
+    return scale;
+}
+
 template <bool BF16, int PIECE>
 __global__ __launch_bounds__(256) void k_edge_dot(const DotArgs a)
 {
@@ -124,34 +157,53 @@ __global__ __launch_bounds__(256) void k_edge_dot(const DotArgs a)
     const int lanes = a.lanes;
     const int groups_per_block = 256 / lanes;
     const int grp = threadIdx.x / lanes, l = threadIdx.x % lanes;
-    const int64_t e0 = ((int64_t)blockIdx.x * groups_per_block + grp) * kEdgeUnroll;
-    ACC acc[kEdgeUnroll];
-    int32_t u[kEdgeUnroll], v[kEdgeUnroll];
+    // a group takes kEdgeSteps batches of kEdgeUnroll consecutive edges; the row and column of the
+    // next batch's edges are fetched while the current batch's rows are in flight
+    const int64_t first = ((int64_t)blockIdx.x * groups_per_block + grp) * (kEdgeUnroll * kEdgeSteps);
+    int32_t u[kEdgeUnroll], v[kEdgeUnroll], un[kEdgeUnroll], vn[kEdgeUnroll];
 #pragma unroll
     for (int k = 0; k < kEdgeUnroll; ++k) {
-        const int64_t e = e0 + k < a.E ? e0 + k : a.E - 1;        // a clamped edge is computed and dropped
-        u[k] = a.edge_row[e];
-        v[k] = a.indices[e];
-        acc[k] = 0;
+        const int64_t e = first + k < a.E ? first + k : a.E - 1;     // a clamped edge is computed and dropped
+        un[k] = a.edge_row[e];
+        vn[k] = a.indices[e];
     }
-    for (int p = l; p < a.pieces; p += lanes) {
-        const int64_t off = (int64_t)p * PIECE;
+    for (int step = 0; step < kEdgeSteps; ++step) {
+        const int64_t e0 = first + (int64_t)step * kEdgeUnroll;
+        if (e0 >= a.E) break;                                        // uniform over the group
 #pragma unroll
-        for (int k = 0; k < kEdgeUnroll; ++k)
-            acc[k] += piece_dot<BF16, PIECE, ACC>(a.X + (int64_t)v[k] * a.row_bytes, a.G + (int64_t)u[k] * a.row_bytes, off);
-    }
+        for (int k = 0; k < kEdgeUnroll; ++k) {
+            u[k] = un[k];
+            v[k] = vn[k];
+        }
+        if (step + 1 < kEdgeSteps) {
 #pragma unroll
-    for (int k = 0; k < kEdgeUnroll; ++k) {
-        const ACC dot = group_sum<ACC>(acc[k], lanes);
-        if (l == 0 && e0 + k < a.E) {
-            double scale = 1.0;
-            if (a.mode) {
-                const int len = a.indptr[u[k] + 1] - a.indptr[u[k]];
-                const double d = len < 1 ? 1.0 : (double)len;
-                scale = a.mode == 1 ? 1.0 / d : 1.0 / sqrt(d);
+            for (int k = 0; k < kEdgeUnroll; ++k) {
+                const int64_t e = e0 + kEdgeUnroll + k < a.E ? e0 + kEdgeUnroll + k : a.E - 1;
+                un[k] = a.edge_row[e];
+                vn[k] = a.indices[e];
             }
-            if (a.src_scale) scale *= (double)a.src_scale[v[k]];
-            a.grad_w[e0 + k] = (float)((double)dot * scale);
+        }
+        ACC acc[kEdgeUnroll];
+#pragma unroll
+        for (int k = 0; k < kEdgeUnroll; ++k) acc[k] = 0;
+        for (int p = l; p < a.pieces; p += lanes) {
+            const int64_t off = (int64_t)p * PIECE;
+#pragma unroll
+            for (int k = 0; k < kEdgeUnroll; ++k)
+                acc[k] += piece_dot<BF16, PIECE, ACC>(a.X + (int64_t)v[k] * a.row_bytes,
+                                                      a.G + (int64_t)u[k] * a.row_bytes, off);
+        }
+        if (lanes >= 4) {
+            int k;
+            const ACC dot = reduce4<ACC>(acc, l, lanes, k);
+            if ((l & (lanes / 4 - 1)) == 0 && e0 + k < a.E)          // first lane of each quarter
+                a.grad_w[e0 + k] = (float)((double)dot * edge_scale(a, u[k], v[k]));
+        } else {
+#pragma unroll
+            for (int k = 0; k < kEdgeUnroll; ++k) {
+                const ACC dot = group_sum<ACC>(acc[k], lanes);
+                if (l == 0 && e0 + k < a.E) a.grad_w[e0 + k] = (float)((double)dot * edge_scale(a, u[k], v[k]));
+            }
         }
     }
 }
@@ -307,7 +359,7 @@ template <bool BF16, int PIECE>
 void launch_dot(const DotArgs &a, hipStream_t s)
 {
     const int groups_per_block = 256 / a.lanes;
-    const int64_t blocks = ceil_div(a.E, (int64_t)groups_per_block * kEdgeUnroll);
+    const int64_t blocks = ceil_div(a.E, (int64_t)groups_per_block * kEdgeUnroll * kEdgeSteps);
     hipLaunchKernelGGL((k_edge_dot<BF16, PIECE>), dim3((unsigned)blocks), dim3(256), 0, s, a);
 }
 
