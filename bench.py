@@ -184,6 +184,53 @@ def match_leg(args, w, B, bg, torch, np):
     }
 
 
+def edge_leg(args, w, layers, workspace, B, torch, np):
+    """Extra leg (not the headline metric): one attention-style pass over the input-layer block with
+    learned edge weights - softmax of per-edge scores over every destination's incoming edges, the
+    aggregation weighted by it (SUM mode), and the backward pass: dL/dw per edge (sampled dot
+    products), the softmax backward, the weighted backward aggregation."""
+    L = layers[0]
+    blk, feat, dev = L["blk"], L["feat"], L["X"].device
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed + 3)
+    score = torch.randn(blk.num_edges, generator=g, device=dev)
+    alpha, gw, gs = torch.empty_like(score), torch.empty_like(score), torch.empty_like(score)
+    ews = torch.empty(B.fastgl_edge_workspace_bytes(blk.num_dst, blk.num_edges), dtype=torch.uint8, device=dev)
+    plan = B.fastgl_block_plan_create(L["indptr"], L["indices"], blk.num_src, B.PLAN_ALL | B.PLAN_PERM)
+    reps = max(5, args.steps // 2)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    t = {
+        "softmax_fwd": timed(lambda: B.fastgl_edge_softmax_fwd(L["indptr"], score, alpha, ews)),
+        "aggregate_fwd_weighted": timed(lambda: B.fastgl_block_aggregate_fwd(
+            L["indptr"], L["indices"], alpha, blk.num_src, "sum", L["X"], out=L["out"], plan=plan, workspace=workspace)),
+        "edge_weight_grad": timed(lambda: B.fastgl_edge_weight_grad(
+            L["indptr"], L["indices"], blk.num_src, "sum", L["X"], L["G"], grad_w=gw, workspace=ews)),
+        "softmax_bwd": timed(lambda: B.fastgl_edge_softmax_bwd(L["indptr"], alpha, gw, gs, ews)),
+        "aggregate_bwd_weighted": timed(lambda: B.fastgl_block_aggregate_bwd(
+            L["indptr"], L["indices"], alpha, blk.num_src, "sum", L["G"], grad_X=L["dX"], plan=plan, workspace=workspace)),
+    }
+    # compulsory bytes of the weight gradient: CSR + every referenced X row once + every grad row once + E results
+    byt = L["bytes_fwd"] + 4 * blk.num_edges
+    ach = byt / t["edge_weight_grad"] / 1e6
+    return {"what": f"input-layer block (E={blk.num_edges}, F={feat}, f32), SUM mode with learned weights",
+            "ms": {k: round(v, 4) for k, v in t.items()}, "total_ms": round(sum(t.values()), 4),
+            "gedges_per_s": round(5 * blk.num_edges / sum(t.values()) / 1e6, 3),
+            "roofline": {"bound": "hbm", "kernel": "k_edge_dot (dL/dw per edge)", "achieved": round(ach, 1),
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
+                         "launch_ms": round(t["edge_weight_grad"], 4), "algorithmic_bytes": int(byt)}}
+
+
 def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
     """Extra leg (not the headline metric): one training step of the whole sampled GCN on the same
     mini-batch - per layer aggregate (Eq. 1) then update (Eq. 2, Y = act(H W + b)), ReLU between
@@ -297,6 +344,8 @@ def main() -> int:
     ap.add_argument("--no-match", action="store_true",
                     help="skip the extra leg that times Match / Reorder over several mini-batches of one graph")
     ap.add_argument("--match-batches", type=int, default=4)
+    ap.add_argument("--no-edge", action="store_true",
+                    help="skip the extra leg that times the learned-edge-weight path (edge softmax, weight gradient)")
     ap.add_argument("--no-gcn-step", action="store_true",
                     help="skip the extra leg that times the whole sampled GCN (aggregation + update phase)")
     ap.add_argument("--verbose", action="store_true")
@@ -484,6 +533,8 @@ def main() -> int:
         result["idmap"] = idmap_leg(args, w, B, bg, torch, np, with_cpu=not args.no_cpu_baseline)
     if not args.no_match and args.config == 2:
         result["match_reorder"] = match_leg(args, w, B, bg, torch, np)
+    if not args.no_edge and w.dtype == "f32":
+        result["edge_weights"] = edge_leg(args, w, layers, workspace, B, torch, np)
     if not args.no_gcn_step and w.dtype == "f32" and len(layers) > 1:
         result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np)
 
