@@ -25,17 +25,16 @@ constexpr int kEdgeUnroll = 4;       // edges in flight per lane group in k_edge
 constexpr int kEdgeSteps = 8;        // batches of that many edges per lane group
 
 // ---------------------------------------------------------------- edge -> destination row
+// A group of 8 lanes writes the row number over the edges of one row (rows of sampled blocks are
+// short; a row of 10^4 edges costs one group ~10^3 steps).
 __global__ __launch_bounds__(256) void k_edge_rows(const int32_t *__restrict__ indptr, int64_t num_dst, int64_t E,
                                                    int32_t *__restrict__ edge_row)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= E) return;
-    int64_t lo = 0, hi = num_dst;                 // largest u with indptr[u] <= e
-    while (hi - lo > 1) {
-        const int64_t mid = (lo + hi) >> 1;
-        if (indptr[mid] <= e) lo = mid; else hi = mid;
-    }
-    edge_row[e] = (int32_t)lo;
+    (void)E;
+    const int64_t u = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
+    if (u >= num_dst) return;
+    const int b = indptr[u], e = indptr[u + 1];
+    for (int k = b + (threadIdx.x & 7); k < e; k += 8) edge_row[k] = (int32_t)u;
 }
 
 // ---------------------------------------------------------------- dL/dw_e
@@ -468,7 +467,7 @@ fastgl_status fastgl_edge_weight_grad(const int32_t *indptr, const int32_t *indi
     a.lanes = 1;
     while (a.lanes < 64 && a.lanes < a.pieces) a.lanes *= 2;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(k_edge_rows, dim3((unsigned)ceil_div(num_edges, 256)), dim3(256), 0, s, indptr, num_dst,
+    hipLaunchKernelGGL(k_edge_rows, dim3((unsigned)ceil_div(num_dst * 8, 256)), dim3(256), 0, s, indptr, num_dst,
                        num_edges, (int32_t *)a.edge_row);
     FASTGL_LAUNCH_CHECK("fastgl_edge_weight_grad (edge rows)");
     const bool bf = dtype == FASTGL_BF16;
