@@ -5,9 +5,10 @@
 // One tiled kernel serves all four products.  A workgroup of 4 wavefronts owns
 // a 128 x 128 tile of the result (each wavefront a 64 x 64 quarter = 2 x 2
 // accumulators of v_mfma_f32_32x32x2_f32) and walks the contracted dimension in
-// steps of 32, staged through LDS.  Each operand is copied to LDS in the layout
+// steps of 16, staged through two LDS buffers; at most 128 registers per lane, so
+// four workgroups share a compute unit.  Each operand is copied to LDS in the layout
 // it has in memory, so both kinds of operand get coalesced global loads:
-//   "row" operand   mem[out][contract]  -> lds[out][32 + 4]  (read back 16 B per lane)
+//   "row" operand   mem[out][contract]  -> lds[out][16 + 4]  (read back 16 B per lane)
 //   "col" operand   mem[contract][out]  -> lds[contract][128 + 8]
 // Inside a group of 8 contracted indices lane half h (lanes 32h..32h+31) takes
 // indices 4h..4h+3, and MFMA number t multiplies index 4h+t of both operands;
@@ -19,14 +20,8 @@ namespace fastgl {
 namespace {
 
 constexpr int kTile = 128;              // rows and columns of a workgroup's result tile
-#ifndef FASTGL_UPD_STEP
-#define FASTGL_UPD_STEP 32
-#endif
-#ifndef FASTGL_UPD_BUFFERS
-#define FASTGL_UPD_BUFFERS 1
-#endif
-constexpr int kStep = FASTGL_UPD_STEP;  // contracted indices per LDS stage
-constexpr int kBuffers = FASTGL_UPD_BUFFERS;
+constexpr int kStep = 16;               // contracted indices per LDS stage
+constexpr int kBuffers = 2;             // LDS stages (one barrier per stage with two)
 constexpr int kLoads = kStep / 8;       // 16-byte loads per thread and operand tile
 constexpr int kRowStride = kStep + 4;   // floats between rows of a "row" operand in LDS
 constexpr int kColStride = kTile + 8;   // floats between contracted indices of a "col" operand
@@ -221,7 +216,7 @@ __device__ __forceinline__ void mma_stage(const float *la, const float *lb, int 
 }
 
 template <bool A_COL, bool B_COL, bool COLSUM, bool VEC, bool GATE_A, bool GATE_B>
-__global__ __launch_bounds__(256) void k_update_gemm(const GemmArgs g)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_update_gemm(const GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) float lds_a[kBuffers][kOperandFloats];
     __shared__ __attribute__((aligned(16))) float lds_b[kBuffers][kOperandFloats];
