@@ -113,3 +113,28 @@ def test_edge_paths_on_the_sampled_workload():
     close(gw.cpu().numpy(), oracle.edge_weight_grad(blk.indptr, blk.indices, blk.num_src, "gcn", "f32", X, G),
           1e-5, 1e-6, "grad_w")
     softmax_case(blk, 5, "config2 input layer")
+
+
+def test_edge_random_block_sweep():
+    """Seeded sweep over block shapes and widths (lane-group sizes 1..64, 2/4/8/16-byte pieces)."""
+    rng = np.random.default_rng(77)
+    for case in range(16):
+        nd, ns = int(rng.integers(1, 400)), int(rng.integers(1, 600))
+        blk = bg.random_block(rng, nd, ns, float(rng.uniform(0.5, 9)), empty_frac=0.2,
+                              hub_rows=int(rng.integers(0, 3)), hub_deg=int(rng.integers(100, 3000)))
+        feat = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 17, 32, 48, 64, 100, 129, 200, 300, 514]))
+        dtype = "f32" if case % 2 == 0 else "bf16"
+        mode = MODES[case % 3]
+        X, G = make_inputs(rng, ns, feat, dtype), make_inputs(rng, nd, feat, dtype)
+        print(f"case edge sweep {case} dst={nd} src={ns} E={blk.num_edges} F={feat} {dtype} {mode}", flush=True)
+        ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
+        plan = B.fastgl_block_plan_create(ip, ix, ns, B.PLAN_FWD | B.PLAN_SRC_DEG) if mode == "gcn" else None
+        gw = B.fastgl_edge_weight_grad(ip, ix, ns, mode, dev_feat(X, dtype), dev_feat(G, dtype), plan=plan)
+        torch.cuda.synchronize()
+        ref = oracle.edge_weight_grad(blk.indptr, blk.indices, ns, mode, dtype, X, G)
+        if dtype == "f32":
+            close(gw.cpu().numpy(), ref, 1e-5, 1e-6, "grad_w")
+        else:
+            close(gw.cpu().numpy(), ref, 2e-2, 1e-5 * max(1.0, np.sqrt(feat)), "grad_w")
+        if blk.num_edges:
+            softmax_case(blk, 500 + case, f"sweep {case}")

@@ -102,3 +102,20 @@ def test_idmap_ordered_is_reproducible():
     a = run(dst, nbr, "ordered")
     b = run(dst, nbr, "ordered")
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_idmap_random_sweep():
+    """Seeded sweep: sizes around the block sizes of the counting passes, spans from heavy repeats to
+    all-distinct."""
+    rng = np.random.default_rng(31)
+    for case in range(12):
+        n_dst = int(rng.choice([0, 1, 5, 255, 256, 1023, 1024, 1025, 3000]))
+        n_nbr = int(rng.choice([0, 1, 7, 1023, 1024, 1025, 2048, 5000, 20000]))
+        span = int(rng.choice([max(n_dst, 1) + 3, 10 ** 4, 10 ** 7, 2 ** 45]))
+        pool = np.unique(rng.integers(0, span, size=4 * (n_dst + 4)))
+        rng.shuffle(pool)
+        if pool.size < n_dst:
+            continue
+        dst = pool[:n_dst]
+        nbr = rng.integers(0, span, size=n_nbr)
+        check(dst, nbr, f"sweep {case}")

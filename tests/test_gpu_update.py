@@ -7,7 +7,8 @@ the textbook bound is |err| <= (L+2) u sum_k |a_k b_k| + u |ref| with u = 2^-24,
 order of the sum.  L is the contracted length (K for Y, N for dH) and the slab height for dW / db,
 whose slab partials are added in fp64.  That bound is checked element by element; because it is
 loose (it is a worst case), the root-mean-square error is also checked against the random-walk
-estimate 2 u sqrt(L) rms(ref), which a wrong or dropped term breaks by orders of magnitude."""
+estimate 2 u sqrt(L) s, s = the larger of rms(ref) and rms(sum|terms|)/sqrt(L) (the size of the
+partial sums), which a wrong or dropped term breaks by orders of magnitude."""
 import numpy as np
 import pytest
 import torch
@@ -35,9 +36,11 @@ def check(got, ref, absprod, L, what):
         i = np.unravel_index(np.argmax(err - lim), err.shape)
         raise AssertionError(f"{what}: {bad.sum()} of {bad.size} beyond the rounding bound; worst at {i}: "
                              f"got {got[i]!r} ref {ref[i]!r} bound {lim[i]!r}")
-    rms_ref = np.sqrt(np.mean(ref ** 2))
+    # random-walk estimate: the partial sums of a chain of L terms are of the size of the result, or,
+    # where the result cancels, of sum|terms| / sqrt(L)
+    scale = max(np.sqrt(np.mean(ref ** 2)), np.sqrt(np.mean(np.broadcast_to(absprod, ref.shape) ** 2)) / np.sqrt(max(L, 1)))
     rms_err = np.sqrt(np.mean(err ** 2))
-    assert rms_err <= 2 * U * np.sqrt(max(L, 1)) * rms_ref + 1e-30, (what, rms_err, rms_ref)
+    assert rms_err <= 2 * U * np.sqrt(max(L, 1)) * scale + 1e-30, (what, rms_err, scale)
 
 
 def run_case(M, K, N, relu, bias, seed, what):
@@ -212,3 +215,16 @@ def test_gcn_layers_chain_against_oracle():
         got, ref = got.cpu().numpy().astype(np.float64), ref.astype(np.float64)
         rel = np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2))
         assert rel < 2e-5, (name, rel)
+
+
+def test_update_random_shape_sweep():
+    """Seeded sweep over shapes that mix every edge path of the tiled kernel: contracted lengths
+    around the stage size, rows and columns around the tile size, extents that are and are not
+    multiples of 4 (16-byte or scalar loads), with and without the ReLU gate."""
+    rng = np.random.default_rng(2024)
+    picks_m = [1, 2, 63, 64, 65, 127, 128, 129, 255, 257, 1023, 1025, 2050]
+    picks_k = [1, 2, 3, 4, 7, 8, 9, 15, 16, 17, 31, 33, 64, 100, 130]
+    picks_n = [1, 2, 4, 5, 8, 31, 32, 33, 64, 127, 128, 129, 132, 200, 256]
+    for case in range(24):
+        M, K, N = int(rng.choice(picks_m)), int(rng.choice(picks_k)), int(rng.choice(picks_n))
+        run_case(M, K, N, relu=bool(case % 2), bias=bool((case // 2) % 2), seed=9000 + case, what=f"sweep {case}")
