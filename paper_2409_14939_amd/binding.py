@@ -176,9 +176,9 @@ class Plan:
         return v
 
     def destroy(self) -> None:
-        if self.handle is not None:
-            lib().fastgl_block_plan_destroy(self.handle)
-            self.handle = None
+        if self.handle is not None and _lib is not None:      # _lib is gone while the interpreter shuts down
+            _lib.fastgl_block_plan_destroy(self.handle)
+        self.handle = None
 
     def __del__(self):
         self.destroy()
