@@ -71,6 +71,10 @@ def lib():
         L.fastgl_oracle_update_fwd.restype = i32
         L.fastgl_oracle_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p]
         L.fastgl_oracle_update_bwd.restype = i32
+        L.fastgl_oracle_update_fwd_dt.argtypes = [p, p, p, i64, i64, i64, i32, i32, p]
+        L.fastgl_oracle_update_fwd_dt.restype = i32
+        L.fastgl_oracle_update_bwd_dt.argtypes = [p, p, p, p, i64, i64, i64, i32, i32, p, p, p]
+        L.fastgl_oracle_update_bwd_dt.restype = i32
         L.fastgl_oracle_edge_weight_grad.argtypes = [p, p, i64, i64, i64, i32, i32, p, p, p, p]
         L.fastgl_oracle_edge_weight_grad.restype = i32
         L.fastgl_oracle_edge_softmax_fwd.argtypes = [p, i64, p, p]
@@ -364,3 +368,31 @@ def edge_softmax_bwd(indptr, alpha, grad_alpha):
                                             _ptr(out)):
         raise RuntimeError("oracle failed")
     return out
+
+
+def update_fwd_bf16(H, W, b, relu):
+    """Eq. 2 with bf16 storage: H, W and the result are bf16 bit patterns (uint16), the bias fp32."""
+    H, W = _feat_array(H, "bf16"), _feat_array(W, "bf16")
+    b = None if b is None else _f32(b)
+    M, K = H.shape
+    assert W.shape[0] == K
+    Y = np.empty((M, W.shape[1]), np.uint16)
+    if lib().fastgl_oracle_update_fwd_dt(_ptr(H), _ptr(W), _ptr(b), M, K, W.shape[1], int(bool(relu)), 1, _ptr(Y)):
+        raise RuntimeError("oracle failed")
+    return Y
+
+
+def update_bwd_bf16(H, W, Y, dY, relu, want=("dH", "dW", "db")):
+    """Gradients with bf16 storage: H, W, Y, dY and dH are bf16 bit patterns, dW and db fp32."""
+    H, W, dY = _feat_array(H, "bf16"), _feat_array(W, "bf16"), _feat_array(dY, "bf16")
+    Y = None if Y is None else _feat_array(Y, "bf16")
+    assert not relu or Y is not None
+    M, K = H.shape
+    N = W.shape[1]
+    dH = np.empty((M, K), np.uint16) if "dH" in want else None
+    dW = np.empty((K, N), np.float32) if "dW" in want else None
+    db = np.empty(N, np.float32) if "db" in want else None
+    if lib().fastgl_oracle_update_bwd_dt(_ptr(H), _ptr(W), _ptr(Y), _ptr(dY), M, K, N, int(bool(relu)), 1,
+                                         _ptr(dH), _ptr(dW), _ptr(db)):
+        raise RuntimeError("oracle failed")
+    return dH, dW, db

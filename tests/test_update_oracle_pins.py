@@ -132,3 +132,39 @@ def test_u5_finite_differences_through_relu():
         bp[j] += eps
         bm[j] -= eps
         assert abs((loss(H8, W8, bp) - loss(H8, W8, bm)) / (2 * eps) - db[j]) < 1e-4
+
+
+def test_u9_bf16_storage():
+    """bf16 storage: inputs are read exactly, results are the fp64 sums rounded once to bf16 (Y, dH)
+    or fp32 (dW, db).  Pinned by small integers (exact in every format), by the fp32 oracle on the
+    same values (identical sums before the final rounding) and by numpy fp64."""
+    import blockgen as bg
+    # small integers: everything is exact, the two storage types must agree bit for bit
+    H = np.array([[1, 2, 3], [-1, 0, 4]], np.float32)
+    W = np.array([[1, 2], [0, -1], [-1, 3]], np.float32)
+    b = np.array([1.0, -2.0], np.float32)
+    Yb = oracle.update_fwd_bf16(bg.to_bf16_bits(H), bg.to_bf16_bits(W), b, True)
+    assert np.array_equal(bg.bf16_bits_to_f32(Yb), oracle.update_fwd(H, W, b, True))
+    dY = np.array([[1, -2], [3, 5]], np.float32)
+    dHb, dWb, dbb = oracle.update_bwd_bf16(bg.to_bf16_bits(H), bg.to_bf16_bits(W), Yb, bg.to_bf16_bits(dY), True)
+    dH, dW, db = oracle.update_bwd(H, W, bg.bf16_bits_to_f32(Yb), dY, True)
+    assert np.array_equal(bg.bf16_bits_to_f32(dHb), dH) and np.array_equal(dWb, dW) and np.array_equal(dbb, db)
+    # random bf16 inputs: fp64 sums through numpy, one rounding to bf16
+    rng = np.random.default_rng(0)
+    Hb, Wb = bg.to_bf16_bits(_rand(rng, 23, 37)), bg.to_bf16_bits(_rand(rng, 37, 11))
+    dYb = bg.to_bf16_bits(_rand(rng, 23, 11))
+    H64, W64, dY64 = (bg.bf16_bits_to_f32(a).astype(np.float64) for a in (Hb, Wb, dYb))
+    Z = H64 @ W64
+    Yb = oracle.update_fwd_bf16(Hb, Wb, None, False)
+    assert np.array_equal(Yb, np.array([[oracle.double_to_bf16(z) for z in row] for row in Z], np.uint16))
+    dHb, dWb, dbb = oracle.update_bwd_bf16(Hb, Wb, None, dYb, False)
+    ref_dH = dY64 @ W64.T
+    assert np.array_equal(dHb, np.array([[oracle.double_to_bf16(z) for z in row] for row in ref_dH], np.uint16))
+    np.testing.assert_allclose(dWb, (H64.T @ dY64).astype(np.float32), rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(dbb, dY64.sum(axis=0).astype(np.float32), rtol=1e-6, atol=1e-6)
+    # the ReLU gate reads the bf16 forward output
+    Yr = oracle.update_fwd_bf16(Hb, Wb, None, True)
+    dHr, _, dbr = oracle.update_bwd_bf16(Hb, Wb, Yr, dYb, True)
+    gate = bg.bf16_bits_to_f32(Yr) > 0
+    np.testing.assert_allclose(dbr, (dY64 * gate).sum(axis=0).astype(np.float32), rtol=1e-6, atol=1e-6)
+    assert np.array_equal(dHr, np.array([[oracle.double_to_bf16(z) for z in row] for row in (dY64 * gate) @ W64.T], np.uint16))
