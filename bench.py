@@ -236,7 +236,7 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
     mini-batch - per layer aggregate (Eq. 1) then update (Eq. 2, Y = act(H W + b)), ReLU between
     layers, a synthetic upstream gradient at the class scores, then the backward pass: gradients of
     every W and b, and of every layer input except the raw features."""
-    dev = layers[0]["X"].device
+    dev, tdt = layers[0]["X"].device, layers[0]["X"].dtype      # bf16 workloads keep bf16 activations and weights
     g = torch.Generator(device="cuda")
     g.manual_seed(w.seed + 1)
     n = len(layers)
@@ -247,16 +247,16 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
         if i + 1 < n:
             assert layers[i + 1]["feat"] == N and layers[i + 1]["blk"].num_src == M
         p = dict(M=M, K=K, N=N, relu=i + 1 < n)
-        p["W"] = torch.randn((K, N), generator=g, device=dev) / K ** 0.5
+        p["W"] = (torch.randn((K, N), generator=g, device=dev) / K ** 0.5).to(tdt)
         p["b"] = torch.randn((N,), generator=g, device=dev) * 0.1
-        p["H"] = torch.empty((M, K), device=dev)
-        p["Y"] = torch.empty((M, N), device=dev)
+        p["H"] = torch.empty((M, K), device=dev, dtype=tdt)
+        p["Y"] = torch.empty((M, N), device=dev, dtype=tdt)
         p["dW"], p["db"] = torch.empty((K, N), device=dev), torch.empty((N,), device=dev)
-        p["dH"] = torch.empty((M, K), device=dev) if i > 0 else None
-        p["dX"] = torch.empty((L["blk"].num_src, K), device=dev) if i > 0 else None
+        p["dH"] = torch.empty((M, K), device=dev, dtype=tdt) if i > 0 else None
+        p["dX"] = torch.empty((L["blk"].num_src, K), device=dev, dtype=tdt) if i > 0 else None
         p["ws"] = torch.empty(max(256, B.fastgl_update_bwd_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
         P.append(p)
-    dlogits = torch.randn((P[-1]["M"], CLASSES), generator=g, device=dev)
+    dlogits = torch.randn((P[-1]["M"], CLASSES), generator=g, device=dev).to(tdt)
     ev = {}
 
     def mark(key, fn, record):
@@ -563,7 +563,7 @@ def main() -> int:
         result["match_reorder"] = match_leg(args, w, B, bg, torch, np)
     if not args.no_edge and w.dtype == "f32":
         result["edge_weights"] = edge_leg(args, w, layers, workspace, B, torch, np)
-    if not args.no_gcn_step and w.dtype == "f32" and len(layers) > 1:
+    if not args.no_gcn_step and len(layers) > 1:
         result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np)
 
     if not args.no_cpu_baseline:

@@ -53,6 +53,20 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
                                 float *dH, float *dW, float *db,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same two passes with bf16 storage (bit patterns in uint16_t): H, W, Y, dY
+ * and dH are bf16; the bias and the weight gradients dW, db stay fp32.
+ * Elements are widened to fp32 on their way into LDS, products and sums are the
+ * fp32 ones of the calls above (a bf16 x bf16 product is exact in fp32), Y and
+ * dH are rounded to bf16 (nearest even) at the store.  Arrays must be aligned
+ * to their element size; everything else is as above. */
+fastgl_status fastgl_update_fwd_bf16(const uint16_t *H, const uint16_t *W, const float *bias,
+                                     int64_t M, int64_t K, int64_t N, int relu,
+                                     uint16_t *Y, void *stream);
+fastgl_status fastgl_update_bwd_bf16(const uint16_t *H, const uint16_t *W, const uint16_t *Y,
+                                     const uint16_t *dY, int64_t M, int64_t K, int64_t N, int relu,
+                                     uint16_t *dH, float *dW, float *db,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
 /* Rows of H per dW/db slab for this shape (the length of the longest fp32
  * accumulation chain of the backward pass): a function of M, K, N alone,
  * between 128 and 1024; 0 for negative sizes. */

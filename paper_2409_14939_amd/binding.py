@@ -26,6 +26,7 @@ EXPORTS = [
     "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk", "fastgl_work_per_group",
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
     "fastgl_update_fwd", "fastgl_update_bwd", "fastgl_update_bwd_workspace_bytes", "fastgl_update_slab_rows",
+    "fastgl_update_fwd_bf16", "fastgl_update_bwd_bf16",
     "fastgl_idmap", "fastgl_idmap_table_slots", "fastgl_idmap_workspace_bytes",
     "fastgl_match", "fastgl_match_workspace_bytes", "fastgl_assemble_rows", "fastgl_overlap_counts",
     "fastgl_overlap_workspace_bytes", "fastgl_greedy_reorder",
@@ -83,6 +84,7 @@ def lib() -> ctypes.CDLL:
         L.fastgl_block_validate.argtypes = [p, p, i64, i64, i64, p, ctypes.POINTER(i64), p]
         L.fastgl_last_error.restype = ctypes.c_char_p
         L.fastgl_update_fwd.argtypes = [p, p, p, i64, i64, i64, i32, p, p]
+        L.fastgl_update_fwd_bf16.argtypes = L.fastgl_update_fwd.argtypes
         L.fastgl_update_bwd_workspace_bytes.argtypes = [i64, i64, i64]
         L.fastgl_update_bwd_workspace_bytes.restype = sz
         L.fastgl_update_bwd.argtypes = [p, p, p, p, i64, i64, i64, i32, p, p, p, p, sz, p]
@@ -106,6 +108,7 @@ def lib() -> ctypes.CDLL:
         L.fastgl_idmap_workspace_bytes.argtypes = [i64, i64]
         L.fastgl_idmap_workspace_bytes.restype = sz
         L.fastgl_idmap.argtypes = [p, i64, p, i64, i32, p, p, p, p, sz, p]
+        L.fastgl_update_bwd_bf16.argtypes = L.fastgl_update_bwd.argtypes
         L.fastgl_update_slab_rows.argtypes = [i64, i64, i64]
         L.fastgl_update_slab_rows.restype = ctypes.c_int32
         _lib = L
@@ -293,50 +296,58 @@ def fastgl_update_bwd_workspace_bytes(M: int, K: int, N: int) -> int:
 
 def fastgl_update_fwd(H: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Tensor], relu: bool,
                       Y: Optional[torch.Tensor] = None) -> torch.Tensor:
-    _dev(H, torch.float32, "H")
-    _dev(W, torch.float32, "W")
+    """H, W (and Y) float32, or all bfloat16 (the bias stays float32)."""
+    dt = H.dtype
+    _feat_dtype(H)
+    _dev(H, dt, "H")
+    _dev(W, dt, "W")
     (M, K), N = H.shape, W.shape[1]
     if W.shape[0] != K or (bias is not None and bias.shape != (N,)):
         raise ValueError("W must be [K,N] and bias [N]")
     if bias is not None:
         _dev(bias, torch.float32, "bias")
     if Y is None:
-        Y = torch.empty((M, N), dtype=torch.float32, device=H.device)
+        Y = torch.empty((M, N), dtype=dt, device=H.device)
     elif Y.shape != (M, N):
         raise ValueError("Y must be [M,N]")
-    _dev(Y, torch.float32, "Y")
-    _check(lib().fastgl_update_fwd(_ptr(H), _ptr(W), _ptr(bias), M, K, N, int(bool(relu)), _ptr(Y), _stream()))
+    _dev(Y, dt, "Y")
+    fn = lib().fastgl_update_fwd if dt == torch.float32 else lib().fastgl_update_fwd_bf16
+    _check(fn(_ptr(H), _ptr(W), _ptr(bias), M, K, N, int(bool(relu)), _ptr(Y), _stream()))
     return Y
 
 
 def fastgl_update_bwd(H: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor], dY: torch.Tensor, relu: bool,
                       want=("dH", "dW", "db"), dH=None, dW=None, db=None,
                       workspace: Optional[torch.Tensor] = None):
-    """Returns (dH, dW, db); parts not named in `want` (and not passed in) are None."""
-    _dev(H, torch.float32, "H")
-    _dev(W, torch.float32, "W")
-    _dev(dY, torch.float32, "dY")
+    """Returns (dH, dW, db); parts not named in `want` (and not passed in) are None.  H, W, Y, dY, dH
+    float32, or all bfloat16; dW and db are float32 either way."""
+    dt = H.dtype
+    _feat_dtype(H)
+    _dev(H, dt, "H")
+    _dev(W, dt, "W")
+    _dev(dY, dt, "dY")
     if Y is not None:
-        _dev(Y, torch.float32, "Y")
+        _dev(Y, dt, "Y")
     (M, K), N = H.shape, W.shape[1]
     if W.shape[0] != K or dY.shape != (M, N) or (Y is not None and Y.shape != (M, N)):
         raise ValueError("shapes must be H [M,K], W [K,N], Y and dY [M,N]")
     if dH is None and "dH" in want:
-        dH = torch.empty((M, K), dtype=torch.float32, device=H.device)
+        dH = torch.empty((M, K), dtype=dt, device=H.device)
     if dW is None and "dW" in want:
         dW = torch.empty((K, N), dtype=torch.float32, device=H.device)
     if db is None and "db" in want:
         db = torch.empty((N,), dtype=torch.float32, device=H.device)
     for t, shape, name in ((dH, (M, K), "dH"), (dW, (K, N), "dW"), (db, (N,), "db")):
         if t is not None:
-            _dev(t, torch.float32, name)
+            _dev(t, dt if name == "dH" else torch.float32, name)
             if tuple(t.shape) != shape:
                 raise ValueError(f"{name} must have shape {shape}")
     if workspace is None:
         workspace = torch.empty(max(fastgl_update_bwd_workspace_bytes(M, K, N), 256), dtype=torch.uint8,
                                 device=H.device)
-    _check(lib().fastgl_update_bwd(_ptr(H), _ptr(W), _ptr(Y), _ptr(dY), M, K, N, int(bool(relu)), _ptr(dH),
-                                   _ptr(dW), _ptr(db), _ptr(workspace), workspace.numel(), _stream()))
+    fn = lib().fastgl_update_bwd if dt == torch.float32 else lib().fastgl_update_bwd_bf16
+    _check(fn(_ptr(H), _ptr(W), _ptr(Y), _ptr(dY), M, K, N, int(bool(relu)), _ptr(dH), _ptr(dW), _ptr(db),
+              _ptr(workspace), workspace.numel(), _stream()))
     return dH, dW, db
 
 

@@ -33,14 +33,14 @@ constexpr int kSlabFill = 640;          // workgroups wanted before slabs stop s
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct Operand {
-    const float *p;       // element (out o, contracted k) at p[o*ld + k] ("row") or p[k*ld + o] ("col")
-    const float *gate;    // same layout, or NULL; where gate <= 0 the element reads as 0 (ReLU derivative)
-    int64_t ld;
+    const void *p;        // element (out o, contracted k) at p[o*ld + k] ("row") or p[k*ld + o] ("col")
+    const void *gate;     // same layout, or NULL; where gate <= 0 the element reads as 0 (ReLU derivative)
+    int64_t ld;           // fp32 or bf16 elements (the kernel's BF16 argument says which)
 };
 
 struct GemmArgs {
     Operand a, b;
-    float *c;                   // [R][C] result (of slab s: c + s*c_slab)
+    void *c;                    // [R][C] result (of slab s: c + s*c_slab): fp32, or bf16 for Y / dH of a bf16 call
     int64_t ldc, c_slab;
     int64_t R, C, Kc;           // result rows, result columns, contracted length
     int64_t slab;               // contracted indices per slab (>= Kc when not split)
@@ -61,49 +61,87 @@ struct GemmArgs {
 // mask_quad, called when the registers are written to LDS, zeroes what does not exist or is gated
 // off.  VEC: one 16-byte load; the host selects it only when every extent is a multiple of 4, so
 // nvalid is 0 or 4.
-template <bool GATE>
-struct Quad {
-    float4 v;
-    float4 g[GATE ? 1 : 0];
+template <bool BF16>
+struct QuadBits;
+template <>
+struct QuadBits<false> {
+    typedef float4 type;
+    typedef float elem;
+};
+template <>
+struct QuadBits<true> {
+    typedef uint2 type;           // four bf16
+    typedef uint16_t elem;
 };
 
-// `base` is uniform over the workgroup (the tile's origin), `off` a per-lane 32-bit element offset.
-template <bool VEC, bool GATE>
-__device__ __forceinline__ void load_quad(const float *__restrict__ base, const float *__restrict__ gate,
-                                          uint32_t off, int nvalid, Quad<GATE> &q)
+template <bool GATE, bool BF16>
+struct Quad {
+    typename QuadBits<BF16>::type v;
+    typename QuadBits<BF16>::type g[GATE ? 1 : 0];
+};
+
+__device__ __forceinline__ float4 quad_to_f32(float4 q) { return q; }
+__device__ __forceinline__ float4 quad_to_f32(uint2 q)
 {
+    return make_float4(__uint_as_float(q.x << 16), __uint_as_float(q.x & 0xFFFF0000u), __uint_as_float(q.y << 16),
+                       __uint_as_float(q.y & 0xFFFF0000u));
+}
+
+// `base` is uniform over the workgroup (the tile's origin), `off` a per-lane 32-bit element offset.
+template <bool VEC, bool GATE, bool BF16>
+__device__ __forceinline__ void load_quad(const void *__restrict__ base_, const void *__restrict__ gate_,
+                                          uint32_t off, int nvalid, Quad<GATE, BF16> &q)
+{
+    typedef typename QuadBits<BF16>::type Q;
+    typedef typename QuadBits<BF16>::elem E;
+    const E *base = static_cast<const E *>(base_), *gate = static_cast<const E *>(gate_);
     if (VEC) {
         const uint32_t o = nvalid >= 4 ? off : 0u;
-        q.v = *reinterpret_cast<const float4 *>(base + o);
-        if (GATE) q.g[0] = *reinterpret_cast<const float4 *>(gate + o);
+        q.v = *reinterpret_cast<const Q *>(base + o);
+        if (GATE) q.g[0] = *reinterpret_cast<const Q *>(gate + o);
     } else {
-        float e[4], f[4];
+        E e[4], f[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t o = i < nvalid ? off + i : 0u;
             e[i] = base[o];
             if (GATE) f[i] = gate[o];
         }
-        q.v = make_float4(e[0], e[1], e[2], e[3]);
-        if (GATE) q.g[0] = make_float4(f[0], f[1], f[2], f[3]);
+        if constexpr (BF16) {
+            q.v = make_uint2((uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16));
+            if (GATE) q.g[0] = make_uint2((uint32_t)f[0] | ((uint32_t)f[1] << 16), (uint32_t)f[2] | ((uint32_t)f[3] << 16));
+        } else {
+            q.v = make_float4(e[0], e[1], e[2], e[3]);
+            if (GATE) q.g[0] = make_float4(f[0], f[1], f[2], f[3]);
+        }
     }
 }
 
-template <bool GATE>
-__device__ __forceinline__ float4 mask_quad(const Quad<GATE> &q, int nvalid)
+template <bool GATE, bool BF16>
+__device__ __forceinline__ float4 mask_quad(const Quad<GATE, BF16> &q, int nvalid)
 {
-    float4 v = q.v;
+    float4 v = quad_to_f32(q.v);
     if (GATE) {
-        v.x = q.g[0].x > 0.f ? v.x : 0.f;
-        v.y = q.g[0].y > 0.f ? v.y : 0.f;
-        v.z = q.g[0].z > 0.f ? v.z : 0.f;
-        v.w = q.g[0].w > 0.f ? v.w : 0.f;
+        const float4 g = quad_to_f32(q.g[0]);
+        v.x = g.x > 0.f ? v.x : 0.f;
+        v.y = g.y > 0.f ? v.y : 0.f;
+        v.z = g.z > 0.f ? v.z : 0.f;
+        v.w = g.w > 0.f ? v.w : 0.f;
     }
     v.x = nvalid > 0 ? v.x : 0.f;
     v.y = nvalid > 1 ? v.y : 0.f;
     v.z = nvalid > 2 ? v.z : 0.f;
     v.w = nvalid > 3 ? v.w : 0.f;
     return v;
+}
+
+// fp32 -> bf16, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
 }
 
 __device__ __forceinline__ int clamp4(int64_t n) { return n >= 4 ? 4 : (n <= 0 ? 0 : (int)n); }
@@ -113,19 +151,20 @@ __device__ __forceinline__ int clamp4(int64_t n) { return n >= 4 ? 4 : (n <= 0 ?
 // is out index t/(kStep/4) + s*(1024/kStep); "col" operand: 32 lanes cover the 128 out indices of
 // one contracted index and slot s is contracted index t/32 + 8s.  Lane offsets are relative to
 // the tile's origin and stay the same from stage to stage (the host keeps 160*ld below 2^32).
-template <bool COL, bool VEC, bool GATE>
+template <bool COL, bool VEC, bool GATE, bool BF16>
 struct TileMover {
     static constexpr int kq_n = kStep / 4, rows = 256 / kq_n;
-    Quad<GATE> r[kLoads];
+    typedef typename QuadBits<BF16>::elem E;
+    Quad<GATE, BF16> r[kLoads];
     uint32_t off[kLoads];   // element offset of slot s from the tile origin
     int nv_out;             // row: bit s set if slot s is an existing out index; col: quad elements in range
     int64_t ld, o0;
-    const float *p, *gate;
+    const E *p, *gate;
 
     __device__ __forceinline__ void init(const Operand &op, int64_t o0_, int64_t omax)
     {
         const int t = threadIdx.x;
-        ld = op.ld; o0 = o0_; p = op.p; gate = op.gate;
+        ld = op.ld; o0 = o0_; p = static_cast<const E *>(op.p); gate = static_cast<const E *>(op.gate);
         nv_out = 0;
 #pragma unroll
         for (int s = 0; s < kLoads; ++s) {
@@ -152,7 +191,7 @@ struct TileMover {
         const int64_t origin = COL ? k0 * ld + o0 : o0 * ld + k0;      // uniform
 #pragma unroll
         for (int s = 0; s < kLoads; ++s)
-            load_quad<VEC, GATE>(p + origin, GATE ? gate + origin : nullptr, off[s], nvalid(s, k0, kend), r[s]);
+            load_quad<VEC, GATE, BF16>(p + origin, GATE ? gate + origin : nullptr, off[s], nvalid(s, k0, kend), r[s]);
     }
 
     // (k0, kend) must be those of the fetch that filled the registers.
@@ -161,7 +200,7 @@ struct TileMover {
         const int t = threadIdx.x;
 #pragma unroll
         for (int s = 0; s < kLoads; ++s) {
-            const float4 v = mask_quad<GATE>(r[s], nvalid(s, k0, kend));
+            const float4 v = mask_quad<GATE, BF16>(r[s], nvalid(s, k0, kend));
             if (!COL)
                 *reinterpret_cast<float4 *>(lds + (t / kq_n + rows * s) * kRowStride + 4 * (t % kq_n)) = v;
             else
@@ -215,7 +254,7 @@ __device__ __forceinline__ void mma_stage(const float *la, const float *lb, int 
     }
 }
 
-template <bool A_COL, bool B_COL, bool COLSUM, bool VEC, bool GATE_A, bool GATE_B>
+template <bool A_COL, bool B_COL, bool COLSUM, bool VEC, bool GATE_A, bool GATE_B, bool BF16>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_update_gemm(const GemmArgs g)
 {
     __shared__ __attribute__((aligned(16))) float lds_a[kBuffers][kOperandFloats];
@@ -260,8 +299,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     float bsum[2] = {0.f, 0.f};
 
-    TileMover<A_COL, VEC, GATE_A> ma;
-    TileMover<B_COL, VEC, GATE_B> mb;
+    TileMover<A_COL, VEC, GATE_A, BF16> ma;
+    TileMover<B_COL, VEC, GATE_B, BF16> mb;
     ma.init(g.a, r0, g.R);
     mb.init(g.b, c0, g.C);
     if (kbeg < kend) {
@@ -293,9 +332,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
     // Accumulator element e of lane (h, l32) is row 8*(e/4) + 4*h + e%4, column l32 of its 32 x 32 tile.
     const int64_t row0 = r0 + wr * 64 + 4 * h, col0 = c0 + wc * 64 + l32;
-    float *cb = g.c + slab_id * g.c_slab + row0 * g.ldc + col0;
+    // Y and dH of a bf16 call are bf16; slab partials are always fp32.  Y and dH leave with streaming
+    // stores; slab partials are re-read at once.
+    constexpr bool OUT_BF16 = BF16 && !COLSUM, STREAM = !COLSUM;
+    typedef typename QuadBits<OUT_BF16>::elem OutT;
+    OutT *cb = static_cast<OutT *>(g.c) + slab_id * g.c_slab + row0 * g.ldc + col0;
     const bool relu = g.relu != 0;
-    constexpr bool STREAM = !COLSUM;    // Y and dH leave with streaming stores; slab partials are re-read at once
+    auto put = [](OutT *dst, float v, bool stream) {
+        if constexpr (OUT_BF16) {
+            const uint16_t w = f32_to_bf16(v);
+            if (stream) __builtin_nontemporal_store(w, dst); else *dst = w;
+        } else {
+            if (stream) __builtin_nontemporal_store(v, dst); else *dst = v;
+        }
+    };
     if (r0 + kTile <= g.R && c0 + kTile <= g.C) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
@@ -306,11 +356,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 for (int e = 0; e < 16; ++e) {
                     float v = acc[i][j][e] + bj;
                     if (relu) v = v > 0.f ? v : 0.f;
-                    float *dst = &cb[(int64_t)(32 * i + 8 * (e >> 2) + (e & 3)) * g.ldc + 32 * j];
-                    if (STREAM)
-                        __builtin_nontemporal_store(v, dst);
-                    else
-                        *dst = v;
+                    put(&cb[(int64_t)(32 * i + 8 * (e >> 2) + (e & 3)) * g.ldc + 32 * j], v, STREAM);
                 }
         }
     } else {
@@ -327,7 +373,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                     if (row0 + dr >= g.R) continue;
                     float v = acc[i][j][e] + bj;
                     if (relu) v = v > 0.f ? v : 0.f;
-                    cb[(int64_t)dr * g.ldc + 32 * j] = v;
+                    put(&cb[(int64_t)dr * g.ldc + 32 * j], v, false);
                 }
         }
     }
@@ -378,28 +424,31 @@ __global__ __launch_bounds__(256) void k_update_reduce(const float *__restrict__
     if (dst) *dst = (float)t;
 }
 
-// 16-byte loads need every row of both operands to start 16-byte aligned and to hold whole quads.
-bool quad_ok(const Operand &op)
+// Quad loads (16 bytes of fp32, 8 bytes of bf16) need every row of the operand to start aligned to a
+// quad and to hold whole quads.
+bool quad_ok(const Operand &op, bool bf16)
 {
-    return op.p && op.ld % 4 == 0 && (((uintptr_t)op.p | (uintptr_t)op.gate) & 15) == 0;
+    const uintptr_t m = bf16 ? 7 : 15;
+    return op.p && op.ld % 4 == 0 && (((uintptr_t)op.p | (uintptr_t)op.gate) & m) == 0;
 }
 
 // WHICH names the operand that may carry a gate: 0 none, 1 a, 2 b.
-template <bool A_COL, bool B_COL, bool COLSUM, int WHICH, bool VEC>
+template <bool A_COL, bool B_COL, bool COLSUM, int WHICH, bool VEC, bool BF16>
 void launch_gates(const GemmArgs &g, unsigned blocks, hipStream_t s)
 {
     if (WHICH == 1 && g.a.gate)
-        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, WHICH == 1, false>), dim3(blocks), dim3(256), 0,
-                           s, g);
+        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, WHICH == 1, false, BF16>), dim3(blocks), dim3(256),
+                           0, s, g);
     else if (WHICH == 2 && g.b.gate)
-        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, false, WHICH == 2>), dim3(blocks), dim3(256), 0,
-                           s, g);
+        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, false, WHICH == 2, BF16>), dim3(blocks), dim3(256),
+                           0, s, g);
     else
-        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, false, false>), dim3(blocks), dim3(256), 0, s, g);
+        hipLaunchKernelGGL((k_update_gemm<A_COL, B_COL, COLSUM, VEC, false, false, BF16>), dim3(blocks), dim3(256), 0, s,
+                           g);
 }
 
 template <bool A_COL, bool B_COL, bool COLSUM, int WHICH>
-fastgl_status launch_gemm(GemmArgs &g, hipStream_t s, const char *what)
+fastgl_status launch_gemm(GemmArgs &g, bool bf16, hipStream_t s, const char *what)
 {
     g.tiles_r = (int)ceil_div(g.R, kTile);
     g.tiles_c = (int)ceil_div(g.C, kTile);
@@ -412,16 +461,20 @@ fastgl_status launch_gemm(GemmArgs &g, hipStream_t s, const char *what)
         set_error("%s: too many tiles (%lld)", what, (long long)blocks);
         return FASTGL_ERR_UNSUPPORTED;
     }
-    bool vec = quad_ok(g.a) && quad_ok(g.b);
+    bool vec = quad_ok(g.a, bf16) && quad_ok(g.b, bf16);
     if (g.R == 0) {            // operand a has no elements: give its (all masked) loads a readable address
         g.a.p = g.b.p;
         g.a.gate = nullptr;
         vec = false;
     }
-    if (vec)
-        launch_gates<A_COL, B_COL, COLSUM, WHICH, true>(g, (unsigned)blocks, s);
-    else
-        launch_gates<A_COL, B_COL, COLSUM, WHICH, false>(g, (unsigned)blocks, s);
+    const unsigned nb = (unsigned)blocks;
+    if (bf16) {
+        if (vec) launch_gates<A_COL, B_COL, COLSUM, WHICH, true, true>(g, nb, s);
+        else launch_gates<A_COL, B_COL, COLSUM, WHICH, false, true>(g, nb, s);
+    } else {
+        if (vec) launch_gates<A_COL, B_COL, COLSUM, WHICH, true, false>(g, nb, s);
+        else launch_gates<A_COL, B_COL, COLSUM, WHICH, false, false>(g, nb, s);
+    }
     FASTGL_LAUNCH_CHECK(what);
     return FASTGL_OK;
 }
@@ -438,8 +491,6 @@ fastgl_status check_dims(int64_t M, int64_t K, int64_t N)
     }
     return FASTGL_OK;
 }
-
-bool misaligned(const void *p) { return ((uintptr_t)p & 3) != 0; }
 
 // Rows per slab: a function of the shape alone, so results do not depend on the device or the run.
 int64_t slab_rows(int64_t M, int64_t K, int64_t N)
@@ -461,10 +512,12 @@ size_t bwd_workspace(int64_t M, int64_t K, int64_t N)
 
 using namespace fastgl;
 
-extern "C" {
+namespace {
 
-fastgl_status fastgl_update_fwd(const float *H, const float *W, const float *bias, int64_t M, int64_t K,
-                                int64_t N, int relu, float *Y, void *stream)
+bool misaligned_to(const void *p, uintptr_t bytes) { return ((uintptr_t)p & (bytes - 1)) != 0; }
+
+fastgl_status update_fwd(bool bf16, const void *H, const void *W, const float *bias, int64_t M, int64_t K, int64_t N,
+                         int relu, void *Y, void *stream)
 {
     fastgl_status st = check_dims(M, K, N);
     if (st != FASTGL_OK) return st;
@@ -473,8 +526,9 @@ fastgl_status fastgl_update_fwd(const float *H, const float *W, const float *bia
         set_error("H, W or Y is NULL");
         return FASTGL_ERR_INVALID_ARG;
     }
-    if (misaligned(H) || misaligned(W) || misaligned(bias) || misaligned(Y)) {
-        set_error("matrices must be 4-byte aligned");
+    const uintptr_t el = bf16 ? 2 : 4;
+    if (misaligned_to(H, el) || misaligned_to(W, el) || misaligned_to(bias, 4) || misaligned_to(Y, el)) {
+        set_error("matrices must be aligned to their element size");
         return FASTGL_ERR_INVALID_ARG;
     }
     GemmArgs g = {};
@@ -483,18 +537,12 @@ fastgl_status fastgl_update_fwd(const float *H, const float *W, const float *bia
     g.c = Y; g.ldc = N;
     g.R = M; g.C = N; g.Kc = K; g.slab = K;
     g.bias = bias; g.relu = relu != 0;
-    return launch_gemm<false, true, false, 0>(g, (hipStream_t)stream, "fastgl_update_fwd");
+    return launch_gemm<false, true, false, 0>(g, bf16, (hipStream_t)stream, "fastgl_update_fwd");
 }
 
-size_t fastgl_update_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N)
-{
-    if (M < 0 || K < 0 || N < 0) return 0;
-    return bwd_workspace(M, K, N);
-}
-
-fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, const float *dY, int64_t M,
-                                int64_t K, int64_t N, int relu, float *dH, float *dW, float *db,
-                                void *workspace, size_t workspace_bytes, void *stream)
+fastgl_status update_bwd(bool bf16, const void *H, const void *W, const void *Y, const void *dY, int64_t M, int64_t K,
+                         int64_t N, int relu, void *dH, float *dW, float *db, void *workspace, size_t workspace_bytes,
+                         void *stream)
 {
     fastgl_status st = check_dims(M, K, N);
     if (st != FASTGL_OK) return st;
@@ -511,9 +559,10 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
         set_error("dW needs H");
         return FASTGL_ERR_INVALID_ARG;
     }
-    if (misaligned(H) || misaligned(W) || misaligned(Y) || misaligned(dY) || misaligned(dH) || misaligned(dW) ||
-        misaligned(db)) {
-        set_error("matrices must be 4-byte aligned");
+    const uintptr_t el = bf16 ? 2 : 4;
+    if (misaligned_to(H, el) || misaligned_to(W, el) || misaligned_to(Y, el) || misaligned_to(dY, el) ||
+        misaligned_to(dH, el) || misaligned_to(dW, 4) || misaligned_to(db, 4)) {
+        set_error("matrices must be aligned to their element size");
         return FASTGL_ERR_INVALID_ARG;
     }
     const size_t need = want_w ? bwd_workspace(M, K, N) : 0;
@@ -528,7 +577,7 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
         }
     }
     hipStream_t s = (hipStream_t)stream;
-    const float *gate = relu ? Y : nullptr;
+    const void *gate = relu ? Y : nullptr;
 
     if (dH && M > 0 && K > 0) {
         // dH[m][k] = sum_n dZ[m][n] W[k][n]: both operands have the contracted index contiguous.
@@ -537,7 +586,7 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
         g.b = Operand{W, nullptr, N};
         g.c = dH; g.ldc = K;
         g.R = M; g.C = K; g.Kc = N; g.slab = N;
-        st = launch_gemm<false, false, false, 1>(g, s, "fastgl_update_bwd (dH)");
+        st = launch_gemm<false, false, false, 1>(g, bf16, s, "fastgl_update_bwd (dH)");
         if (st != FASTGL_OK) return st;
     }
     if (want_w) {
@@ -553,7 +602,7 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
             g.R = K; g.C = N; g.Kc = M; g.slab = rows;
             g.split = 1; g.n_outer = nslab;
             g.colsum = part + K * N; g.colsum_slab = stride;
-            st = launch_gemm<true, true, true, 2>(g, s, "fastgl_update_bwd (dW)");
+            st = launch_gemm<true, true, true, 2>(g, bf16, s, "fastgl_update_bwd (dW)");
             if (st != FASTGL_OK) return st;
         }
         const int64_t n_w = K * N, total = n_w + N;
@@ -562,6 +611,42 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
         FASTGL_LAUNCH_CHECK("fastgl_update_bwd (reduce)");
     }
     return FASTGL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+fastgl_status fastgl_update_fwd(const float *H, const float *W, const float *bias, int64_t M, int64_t K,
+                                int64_t N, int relu, float *Y, void *stream)
+{
+    return update_fwd(false, H, W, bias, M, K, N, relu, Y, stream);
+}
+
+fastgl_status fastgl_update_fwd_bf16(const uint16_t *H, const uint16_t *W, const float *bias, int64_t M, int64_t K,
+                                     int64_t N, int relu, uint16_t *Y, void *stream)
+{
+    return update_fwd(true, H, W, bias, M, K, N, relu, Y, stream);
+}
+
+size_t fastgl_update_bwd_workspace_bytes(int64_t M, int64_t K, int64_t N)
+{
+    if (M < 0 || K < 0 || N < 0) return 0;
+    return bwd_workspace(M, K, N);
+}
+
+fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, const float *dY, int64_t M,
+                                int64_t K, int64_t N, int relu, float *dH, float *dW, float *db,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    return update_bwd(false, H, W, Y, dY, M, K, N, relu, dH, dW, db, workspace, workspace_bytes, stream);
+}
+
+fastgl_status fastgl_update_bwd_bf16(const uint16_t *H, const uint16_t *W, const uint16_t *Y, const uint16_t *dY,
+                                     int64_t M, int64_t K, int64_t N, int relu, uint16_t *dH, float *dW, float *db,
+                                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    return update_bwd(true, H, W, Y, dY, M, K, N, relu, dH, dW, db, workspace, workspace_bytes, stream);
 }
 
 int32_t fastgl_update_slab_rows(int64_t M, int64_t K, int64_t N)

@@ -15,7 +15,7 @@ def declared_symbols():
     text = "".join(open(os.path.join(ROOT, "include", f)).read()
                    for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(fastgl_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(fastgl_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():

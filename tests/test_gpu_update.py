@@ -228,3 +228,53 @@ def test_update_random_shape_sweep():
     for case in range(24):
         M, K, N = int(rng.choice(picks_m)), int(rng.choice(picks_k)), int(rng.choice(picks_n))
         run_case(M, K, N, relu=bool(case % 2), bias=bool((case // 2) % 2), seed=9000 + case, what=f"sweep {case}")
+
+
+# ---- bf16 storage ------------------------------------------------------------------------
+def dev_bf16(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint16).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def host_bf16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def close_bf16(got_bits, ref_bits, absprod, L, what):
+    """bf16 results: the kernel sums in fp32 and rounds fp32 -> bf16, the oracle rounds the fp64 sum
+    once: they agree up to one bf16 unit (2^-8 relative, the task's 2e-2 with room to spare) plus the
+    fp32 accumulation bound where the sum cancels."""
+    import blockgen as bg
+    got, ref = bg.bf16_bits_to_f32(got_bits).astype(np.float64), bg.bf16_bits_to_f32(ref_bits).astype(np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    lim = 2.0 ** -7 * np.abs(ref) + (L + 2) * U * absprod + 1e-30
+    bad = np.abs(got - ref) > lim
+    assert not bad.any(), (what, int(bad.sum()), got[bad][:3], ref[bad][:3])
+    assert (got_bits == ref_bits).mean() > 0.97, (what, (got_bits == ref_bits).mean())     # almost always the same bits
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("M,K,N", [(300, 128, 256), (1500, 256, 256), (2500, 256, 47), (257, 18, 130), (1, 40, 5),
+                                   (1025, 36, 260)])
+def test_update_parity_bf16(M, K, N, relu):
+    import blockgen as bg
+    rng = np.random.default_rng(M + K + N)
+    Hb = bg.to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    Wb = bg.to_bf16_bits((rng.standard_normal((K, N)) / np.sqrt(K)).astype(np.float32))
+    b = rng.standard_normal(N).astype(np.float32) if N % 2 == 0 else None
+    dYb = bg.to_bf16_bits(rng.standard_normal((M, N)).astype(np.float32))
+    print(f"case update bf16 M={M} K={K} N={N} relu={relu}", flush=True)
+    Hd, Wd = dev_bf16(Hb), dev_bf16(Wb)
+    Yd = B.fastgl_update_fwd(Hd, Wd, dev(b), relu)
+    torch.cuda.synchronize()
+    Yref = oracle.update_fwd_bf16(Hb, Wb, b, relu)
+    aH, aW = np.abs(bg.bf16_bits_to_f32(Hb)).astype(np.float64), np.abs(bg.bf16_bits_to_f32(Wb)).astype(np.float64)
+    close_bf16(host_bf16(Yd), Yref, aH @ aW + (0 if b is None else np.abs(b)), K + 1, "Y")
+    # gate both backward passes with the oracle's forward output (a last-bit difference may flip a sign at 0)
+    dHd, dWd, dbd = B.fastgl_update_bwd(Hd, Wd, dev_bf16(Yref) if relu else None, dev_bf16(dYb), relu)
+    torch.cuda.synchronize()
+    dHr, dWr, dbr = oracle.update_bwd_bf16(Hb, Wb, Yref if relu else None, dYb, relu)
+    dZ = np.abs(bg.bf16_bits_to_f32(dYb)).astype(np.float64) * ((bg.bf16_bits_to_f32(Yref) > 0) if relu else 1.0)
+    close_bf16(host_bf16(dHd), dHr, dZ @ aW.T, N, "dH")
+    slab = B.fastgl_update_slab_rows(M, K, N)
+    check(dWd.cpu().numpy(), dWr, aH.T @ dZ, min(M, slab), "dW (bf16 inputs)")
+    check(dbd.cpu().numpy(), dbr, dZ.sum(axis=0), min(M, slab), "db (bf16 inputs)")
