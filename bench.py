@@ -98,7 +98,7 @@ def idmap_leg(args, w, B, bg, torch, np, with_cpu):
     return out
 
 
-def match_leg(args, w, B, bg, torch, np):
+def match_leg(args, w, B, bg, torch, np, with_cpu=False):
     """Extra leg (not the headline metric): the Match process and the Greedy Reorder Strategy (paper
     Section 4.1) over several mini-batches sampled from ONE products-shaped graph.  The raw features
     sit in a device-resident table; with Match only the rows that the last mini-batch does not hold
@@ -161,7 +161,16 @@ def match_leg(args, w, B, bg, torch, np):
     assert torch.equal(X_new, ref), "Match + assemble must equal loading every row"
     row_bytes = feat * 4
     asm_bytes = 2 * sizes[b] * row_bytes + 4 * sizes[b]
+    cpu = None
+    if with_cpu:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.match(sets[a], sets[b])
+        dt = time.perf_counter() - t0
+        cpu = {"match_gids_per_s": round((sizes[a] + sizes[b]) / dt / 1e9, 5), "cores": 1, "kind": "oracle",
+               "sample": f"the same transition (sort + binary search), {dt:.2f} s"}
     return {
+        "cpu_oracle": cpu,
         "what": f"{nb} mini-batches sampled from one products-shaped graph; features ({feat} x f32) in a device table",
         "nodes_per_minibatch": sizes, "gen_seconds": round(gen_s, 1),
         "match_degree_mean": round(float(np.mean([O[i, j] / min(sizes[i], sizes[j]) for i in range(nb)
@@ -184,7 +193,7 @@ def match_leg(args, w, B, bg, torch, np):
     }
 
 
-def edge_leg(args, w, layers, workspace, B, torch, np):
+def edge_leg(args, w, layers, workspace, B, torch, np, with_cpu=False):
     """Extra leg (not the headline metric): one attention-style pass over the input-layer block with
     learned edge weights - softmax of per-edge scores over every destination's incoming edges, the
     aggregation weighted by it (SUM mode), and the backward pass: dL/dw per edge (sampled dot
@@ -223,7 +232,19 @@ def edge_leg(args, w, layers, workspace, B, torch, np):
     # compulsory bytes of the weight gradient: CSR + every referenced X row once + every grad row once + E results
     byt = L["bytes_fwd"] + 4 * blk.num_edges
     ach = byt / t["edge_weight_grad"] / 1e6
-    return {"what": f"input-layer block (E={blk.num_edges}, F={feat}, f32), SUM mode with learned weights",
+    cpu = None
+    if with_cpu:
+        import oracle
+        rows = min(blk.num_dst, 100_000)                 # a bounded sample: the first rows of the block
+        ne = int(blk.indptr[rows])
+        Xh, Gh = L["X"].cpu().numpy(), L["G"][:rows].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.edge_weight_grad(blk.indptr[:rows + 1], blk.indices[:ne], blk.num_src, "sum", "f32", Xh, Gh)
+        oracle.edge_softmax_fwd(blk.indptr[:rows + 1], score[:ne].cpu().numpy())
+        dt = time.perf_counter() - t0
+        cpu = {"gedges_per_s": round(2 * ne / dt / 1e9, 5), "cores": 1, "kind": "oracle",
+               "sample": f"weight gradient + softmax forward over the first {rows} rows ({ne} edges), {dt:.2f} s"}
+    return {"cpu_oracle": cpu, "what": f"input-layer block (E={blk.num_edges}, F={feat}, f32), SUM mode with learned weights",
             "ms": {k: round(v, 4) for k, v in t.items()}, "total_ms": round(sum(t.values()), 4),
             "gedges_per_s": round(5 * blk.num_edges / sum(t.values()) / 1e6, 3),
             "roofline": {"bound": "hbm", "kernel": "k_edge_dot (dL/dw per edge)", "achieved": round(ach, 1),
@@ -231,7 +252,7 @@ def edge_leg(args, w, layers, workspace, B, torch, np):
                          "launch_ms": round(t["edge_weight_grad"], 4), "algorithmic_bytes": int(byt)}}
 
 
-def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
+def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=False):
     """Extra leg (not the headline metric): one training step of the whole sampled GCN on the same
     mini-batch - per layer aggregate (Eq. 1) then update (Eq. 2, Y = act(H W + b)), ReLU between
     layers, a synthetic upstream gradient at the class scores, then the backward pass: gradients of
@@ -340,7 +361,18 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np):
     agg_ms = sum(v for k, v in parts.items() if k.startswith("agg"))
     dom_ms = parts["upd_fwd0"]
     ach = flops_fwd[0] / (dom_ms * 1e-3) / 1e12
+    cpu = None
+    if with_cpu and tdt == torch.float32:
+        import oracle
+        rows = min(P[0]["M"], 4000)                      # a bounded sample: the first rows of the input layer
+        Hh, Wh, bh = P[0]["H"][:rows].cpu().numpy(), P[0]["W"].cpu().numpy(), P[0]["b"].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.update_fwd(Hh, Wh, bh, True)
+        dt = time.perf_counter() - t0
+        cpu = {"update_tflops": round(2.0 * rows * P[0]["K"] * P[0]["N"] / dt / 1e12, 6), "cores": 1, "kind": "oracle",
+               "sample": f"forward update of the first {rows} rows of the input layer (fp64 triple loop), {dt:.2f} s"}
     return {
+        "cpu_oracle": cpu,
         "what": "plans + per layer [aggregate, act(H W + b)] forward, then backward (dW, db every layer; "
                 "dH and the backward aggregation for every layer but the input one); widths "
                 f"{[p['K'] for p in P]} -> {outs}",
@@ -560,11 +592,13 @@ def main() -> int:
     if not args.no_idmap:
         result["idmap"] = idmap_leg(args, w, B, bg, torch, np, with_cpu=not args.no_cpu_baseline)
     if not args.no_match and args.config == 2:
-        result["match_reorder"] = match_leg(args, w, B, bg, torch, np)
+        result["match_reorder"] = match_leg(args, w, B, bg, torch, np, with_cpu=not args.no_cpu_baseline)
     if not args.no_edge and w.dtype == "f32":
-        result["edge_weights"] = edge_leg(args, w, layers, workspace, B, torch, np)
+        result["edge_weights"] = edge_leg(args, w, layers, workspace, B, torch, np,
+                                          with_cpu=not args.no_cpu_baseline)
     if not args.no_gcn_step and len(layers) > 1:
-        result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np)
+        result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np,
+                                          with_cpu=not args.no_cpu_baseline)
 
     if not args.no_cpu_baseline:
         import oracle
