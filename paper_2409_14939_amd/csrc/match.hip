@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void k_overlap_count(OverlapArgs a)
         }
     }
     __syncthreads();
-    if (threadIdx.x < a.n && hist[threadIdx.x])
+    if ((int)threadIdx.x < a.n && hist[threadIdx.x])
         atomicAdd(&a.counts[(int64_t)b * a.n + threadIdx.x], (unsigned long long)hist[threadIdx.x]);
 }
 
