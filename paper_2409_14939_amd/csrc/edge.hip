@@ -8,8 +8,8 @@
 // one edge, several edges are in flight per group, and the lanes' partial dot products are added
 // with cross-lane reads.  The destination of every edge comes from a small expansion pass.
 //
-// Softmax: a group of 8 lanes walks one destination row three times (maximum, sum of exponentials,
-// write); rows longer than kLongRow are queued and taken by whole workgroups afterwards.  exp and
+// Softmax: a group of 8, 32 or 64 lanes (by the block's mean row length) walks one destination row
+// three times (maximum, sum of exponentials, write); rows longer than kLongRow are queued and taken by whole workgroups afterwards.  exp and
 // the sums are fp64, so the result is the correctly rounded quotient up to one unit in the last place.
 #include <type_traits>
 
@@ -247,9 +247,9 @@ __device__ __forceinline__ void softmax_row_bwd(const float *__restrict__ alpha,
     for (int k = b + l; k < e; k += lanes) ds[k] = (float)((double)alpha[k] * ((double)da[k] - s));
 }
 
+template <int lanes>
 __global__ __launch_bounds__(256) void k_edge_softmax_rows(const SoftmaxArgs a)
 {
-    constexpr int lanes = 8;
     const int64_t u = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / lanes;
     const int l = threadIdx.x % lanes;
     int b = 0, e = 0;
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(256) void k_edge_softmax_rows(const SoftmaxArgs a)
             e = b;
         }
     }
-    // all 8 lanes of a group hold the same (b, e): the cross-lane sums below see whole groups
+    // all lanes of a group hold the same (b, e): the cross-lane sums below see whole groups
     if (a.backward)
         softmax_row_bwd(a.in0, a.in1, a.out, b, e, l, lanes);
     else
@@ -383,7 +383,14 @@ fastgl_status softmax(bool backward, const int32_t *indptr, int64_t num_dst, int
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(k_zero_i32, dim3(1), dim3(1), 0, s, a.queue_len);
     FASTGL_LAUNCH_CHECK("edge softmax (reset)");
-    hipLaunchKernelGGL(k_edge_softmax_rows, dim3((unsigned)ceil_div(num_dst * 8, 256)), dim3(256), 0, s, a);
+    // lanes per destination row by the block's mean row length (rows of sampled blocks are short)
+    const int64_t mean = E / (num_dst > 0 ? num_dst : 1);
+    if (mean < 24)
+        hipLaunchKernelGGL(k_edge_softmax_rows<8>, dim3((unsigned)ceil_div(num_dst * 8, 256)), dim3(256), 0, s, a);
+    else if (mean < 96)
+        hipLaunchKernelGGL(k_edge_softmax_rows<32>, dim3((unsigned)ceil_div(num_dst * 32, 256)), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL(k_edge_softmax_rows<64>, dim3((unsigned)ceil_div(num_dst * 64, 256)), dim3(256), 0, s, a);
     FASTGL_LAUNCH_CHECK("edge softmax (rows)");
     hipLaunchKernelGGL(k_edge_softmax_long, dim3(kLongGrid), dim3(256), 0, s, a);
     FASTGL_LAUNCH_CHECK("edge softmax (long rows)");

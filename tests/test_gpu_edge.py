@@ -83,7 +83,9 @@ def test_edge_softmax_ragged_with_long_rows():
     assert B.fastgl_edge_softmax_long_row() < 1500        # the hub rows below take the workgroup-per-row pass
     softmax_case(ragged_block(), 1, "ragged")
     blk = bg.random_block(np.random.default_rng(2), 300, 900, 3.0, empty_frac=0.3, hub_rows=40, hub_deg=5000)
-    softmax_case(blk, 3, "many long rows")
+    softmax_case(blk, 3, "many long rows")                 # mean row length > 96: 64 lanes per row
+    blk = bg.random_block(np.random.default_rng(4), 2000, 5000, 50.0, empty_frac=0.1, hub_rows=3, hub_deg=1200)
+    softmax_case(blk, 5, "medium rows")                    # mean row length 24..96: 32 lanes per row
 
 
 def test_edge_softmax_degenerate():
