@@ -11,10 +11,16 @@
  *             dH = dZ W^T,  dW = H^T dZ,  db = column sums of dZ
  *
  * H [M,K], W [K,N], Y/dY [M,N], dH [M,K], dW [K,N], b/db [N]: dense row-major
- * fp32 with no padding between rows.  Products run on the fp32 matrix cores
- * (v_mfma_f32_32x32x2_f32): fp32 multiply, fp32 accumulate.  dW and db are
- * reduced over fixed slabs of rows whose partial results are summed in fp64 in
- * a fixed order, so results do not depend on scheduling.
+ * fp32 with no padding between rows.  Products run on the bf16 matrix cores
+ * (v_mfma_f32_32x32x16_bf16) with fp32 accumulation: every fp32 element is cut
+ * into three bf16 pieces whose sum is the element exactly, and six of the nine
+ * piece products are added up, which leaves a relative error of at most 2^-23
+ * (2^-28 on average) in a product of two elements - the accuracy of an fp32
+ * multiply-add chain, at several times its speed.  An input element that is
+ * not finite, or larger in magnitude than the largest bf16 (3.39e38), turns
+ * every result it enters into NaN.  dW and db are reduced over fixed slabs of
+ * rows whose partial results are summed in fp64 in a fixed order, so results
+ * do not depend on scheduling.
  *
  * Conventions are those of fastgl_agg.h: every array is DEVICE memory owned by
  * the caller, the library allocates nothing, work is enqueued on `stream`
@@ -55,9 +61,8 @@ fastgl_status fastgl_update_bwd(const float *H, const float *W, const float *Y, 
 
 /* The same two passes with bf16 storage (bit patterns in uint16_t): H, W, Y, dY
  * and dH are bf16; the bias and the weight gradients dW, db stay fp32.
- * Elements are widened to fp32 on their way into LDS, products and sums are the
- * fp32 ones of the calls above (a bf16 x bf16 product is exact in fp32), Y and
- * dH are rounded to bf16 (nearest even) at the store.  Arrays must be aligned
+ * One bf16 piece per element and one exact product per pair, summed in fp32 as
+ * in the calls above; Y and dH are rounded to bf16 (nearest even) at the store.  Arrays must be aligned
  * to their element size; everything else is as above. */
 fastgl_status fastgl_update_fwd_bf16(const uint16_t *H, const uint16_t *W, const float *bias,
                                      int64_t M, int64_t K, int64_t N, int relu,

@@ -1,18 +1,28 @@
-// Update phase of a sampled GCN layer (paper Section 2.1, Eq. 2) on the fp32
-// matrix cores of gfx950: Y = act(H W + b) and its three gradients.  See
-// include/fastgl_update.h for the contract of every entry point.
+// Update phase of a sampled GCN layer (paper Section 2.1, Eq. 2) on the matrix cores of gfx950:
+// Y = act(H W + b) and its three gradients.  See include/fastgl_update.h for the contract of every
+// entry point.
 //
-// One tiled kernel serves all four products.  A workgroup of 4 wavefronts owns
-// a 128 x 128 tile of the result (each wavefront a 64 x 64 quarter = 2 x 2
-// accumulators of v_mfma_f32_32x32x2_f32) and walks the contracted dimension in
-// steps of 16, staged through two LDS buffers; at most 128 registers per lane, so
-// four workgroups share a compute unit.  Each operand is copied to LDS in the layout
-// it has in memory, so both kinds of operand get coalesced global loads:
-//   "row" operand   mem[out][contract]  -> lds[out][16 + 4]  (read back 16 B per lane)
-//   "col" operand   mem[contract][out]  -> lds[contract][128 + 8]
-// Inside a group of 8 contracted indices lane half h (lanes 32h..32h+31) takes
-// indices 4h..4h+3, and MFMA number t multiplies index 4h+t of both operands;
-// the sum over the contracted index does not care about this order.
+// One tiled kernel serves all four products.  A workgroup of 4 wavefronts owns a 128 x 128 tile of
+// the result (each wavefront a 64 x 64 quarter = 2 x 2 accumulators of v_mfma_f32_32x32x16_bf16)
+// and walks the contracted dimension in steps of 16, staged through two LDS buffers; three
+// workgroups share a compute unit.
+//
+// The bf16 instruction runs at 16 times the rate of the fp32 one, so fp32 operands are not
+// multiplied as fp32: an element x is cut into three bf16 planes, x = x1 + x2 + x3 exactly
+// (x1 = bf16(x), x2 = bf16(x - x1), x3 = x - x1 - x2: 8 + 8 + 8 significant bits, each rounding to
+// nearest, so |x2| <= 2^-8 |x| and |x3| <= 2^-16 |x|), when a tile is written to LDS.  Of the nine
+// plane products six are kept: a1 b3, a3 b1, a2 b2, a1 b2, a2 b1, a1 b1 (smallest first, all into
+// the same fp32 accumulator); the three dropped ones are below 2^-23 |a||b| together, and below
+// 2^-28 |a||b| on average.  bf16 storage needs one plane and one product.  An element that is not
+// finite, or beyond the largest bf16 (3.39e38), turns the results it enters into NaN.
+//
+// Each operand is copied to LDS from the layout it has in memory, so both kinds of operand get
+// coalesced global loads.  One plane of an operand tile (128 out x 16 contracted) in LDS:
+//   "row" operand   mem[out][contract]: 32 bytes per out index; the two 16-byte halves (contracted
+//                   0..7, 8..15) swap places where bit 2 ^ bit 3 of the out index is set
+//                   (conflict-free 16-byte reads)
+//   "col" operand   mem[contract][out]: [pair p = contracted 2p, 2p+1][out] dwords, 128 + 8 per pair
+// Lane half h (lanes 32h..32h+31) multiplies contracted indices 8h .. 8h+7 of both operands.
 #include "fastgl_update.h"
 #include "internal.h"
 
@@ -21,11 +31,6 @@ namespace {
 
 constexpr int kTile = 128;              // rows and columns of a workgroup's result tile
 constexpr int kStep = 16;               // contracted indices per LDS stage
-constexpr int kBuffers = 2;             // LDS stages (one barrier per stage with two)
-constexpr int kLoads = kStep / 8;       // 16-byte loads per thread and operand tile
-constexpr int kRowStride = kStep + 4;   // floats between rows of a "row" operand in LDS
-constexpr int kColStride = kTile + 8;   // floats between contracted indices of a "col" operand
-constexpr int kOperandFloats = (kTile * kRowStride > kStep * kColStride) ? kTile * kRowStride : kStep * kColStride;
 constexpr int kMaxSlabRows = 1024;      // most rows of H per dW / db partial
 constexpr int kMinSlabRows = 128;
 constexpr int kSlabFill = 640;          // workgroups wanted before slabs stop shrinking
@@ -146,195 +151,15 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 
 __device__ __forceinline__ int clamp4(int64_t n) { return n >= 4 ? 4 : (n <= 0 ? 0 : (int)n); }
 
-// One 128 (out) x kStep (contracted) operand tile: global -> registers (fetch), registers -> LDS
-// (stage).  "row" operand: kStep/4 lanes cover the contracted indices of one out index and slot s
-// is out index t/(kStep/4) + s*(1024/kStep); "col" operand: 32 lanes cover the 128 out indices of
-// one contracted index and slot s is contracted index t/32 + 8s.  Lane offsets are relative to
-// the tile's origin and stay the same from stage to stage (the host keeps 160*ld below 2^32).
-template <bool COL, bool VEC, bool GATE, bool BF16>
-struct TileMover {
-    static constexpr int kq_n = kStep / 4, rows = 256 / kq_n;
-    typedef typename QuadBits<BF16>::elem E;
-    Quad<GATE, BF16> r[kLoads];
-    uint32_t off[kLoads];   // element offset of slot s from the tile origin
-    int nv_out;             // row: bit s set if slot s is an existing out index; col: quad elements in range
-    int64_t ld, o0;
-    const E *p, *gate;
-
-    __device__ __forceinline__ void init(const Operand &op, int64_t o0_, int64_t omax)
-    {
-        const int t = threadIdx.x;
-        ld = op.ld; o0 = o0_; p = static_cast<const E *>(op.p); gate = static_cast<const E *>(op.gate);
-        nv_out = 0;
-#pragma unroll
-        for (int s = 0; s < kLoads; ++s) {
-            if (!COL) {
-                const int dr = t / kq_n + rows * s;
-                off[s] = (uint32_t)dr * (uint32_t)ld + 4u * (t % kq_n);
-                if (o0 + dr < omax) nv_out |= 1 << s;
-            } else {
-                off[s] = (uint32_t)((t >> 5) + 8 * s) * (uint32_t)ld + 4u * (t & 31);
-            }
-        }
-        if (COL) nv_out = clamp4(omax - (o0 + 4 * (t & 31)));
-    }
-
-    __device__ __forceinline__ int nvalid(int s, int64_t k0, int64_t kend) const
-    {
-        const int t = threadIdx.x;
-        if (!COL) return (nv_out >> s) & 1 ? clamp4(kend - (k0 + 4 * (t % kq_n))) : 0;
-        return k0 + (t >> 5) + 8 * s < kend ? nv_out : 0;
-    }
-
-    __device__ __forceinline__ void fetch(int64_t k0, int64_t kend)
-    {
-        const int64_t origin = COL ? k0 * ld + o0 : o0 * ld + k0;      // uniform
-#pragma unroll
-        for (int s = 0; s < kLoads; ++s)
-            load_quad<VEC, GATE, BF16>(p + origin, GATE ? gate + origin : nullptr, off[s], nvalid(s, k0, kend), r[s]);
-    }
-
-    // (k0, kend) must be those of the fetch that filled the registers.
-    __device__ __forceinline__ void stage(float *lds, int64_t k0, int64_t kend) const
-    {
-        const int t = threadIdx.x;
-#pragma unroll
-        for (int s = 0; s < kLoads; ++s) {
-            const float4 v = mask_quad<GATE, BF16>(r[s], nvalid(s, k0, kend));
-            if (!COL)
-                *reinterpret_cast<float4 *>(lds + (t / kq_n + rows * s) * kRowStride + 4 * (t % kq_n)) = v;
-            else
-                *reinterpret_cast<float4 *>(lds + ((t >> 5) + 8 * s) * kColStride + 4 * (t & 31)) = v;
-        }
-    }
-};
-
-// The four values (contracted indices 8c+4h .. 8c+4h+3) of out index o.
-template <bool COL>
-__device__ __forceinline__ float4 read_frag(const float *lds, int o, int c, int h)
+// Writes a wavefront's 64 x 64 quarter of the result tile at (r0, c0): bias, activation, rounding.
+// Accumulator element e of lane (h, l32) is row 8*(e/4) + 4*h + e%4, column l32 of its 32 x 32 tile.
+// Y and dH of a bf16 call are bf16; slab partials are always fp32.  Y and dH leave with streaming
+// stores (STREAM); slab partials are re-read at once.
+template <bool OUT_BF16, bool STREAM>
+__device__ __forceinline__ void write_tile(const GemmArgs &g, const f32x16 (&acc)[2][2], int64_t r0, int64_t c0,
+                                           int64_t slab_id, int wr, int wc, int h, int l32)
 {
-    if (!COL) return *reinterpret_cast<const float4 *>(lds + o * kRowStride + 8 * c + 4 * h);
-    const float *q = lds + (8 * c + 4 * h) * kColStride + o;
-    return make_float4(q[0], q[kColStride], q[2 * kColStride], q[3 * kColStride]);
-}
-
-// The MFMAs of one group of 8 contracted indices; consecutive MFMAs go to different accumulators.
-__device__ __forceinline__ void mma_group(const float4 (&fa)[2], const float4 (&fb)[2], f32x16 (&acc)[2][2])
-{
-#pragma unroll
-    for (int t = 0; t < 4; ++t)
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const float av = t == 0 ? fa[i].x : t == 1 ? fa[i].y : t == 2 ? fa[i].z : fa[i].w;
-                const float bv = t == 0 ? fb[j].x : t == 1 ? fb[j].y : t == 2 ? fb[j].z : fb[j].w;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-            }
-}
-
-// All MFMAs of `nchunk` groups of 8 contracted indices of the staged tiles.
-template <bool A_COL, bool B_COL, bool COLSUM>
-__device__ __forceinline__ void mma_stage(const float *la, const float *lb, int nchunk, int wr, int wc, int l32,
-                                          int h, f32x16 (&acc)[2][2], float (&bsum)[2])
-{
-#pragma unroll 1
-    for (int c = 0; c < nchunk; ++c) {
-        float4 fa[2], fb[2];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            fa[i] = read_frag<A_COL>(la, wr * 64 + i * 32 + l32, c, h);
-            fb[i] = read_frag<B_COL>(lb, wc * 64 + i * 32 + l32, c, h);
-        }
-        if (COLSUM) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j) bsum[j] += (fb[j].x + fb[j].y) + (fb[j].z + fb[j].w);
-        }
-        mma_group(fa, fb, acc);
-    }
-}
-
-template <bool A_COL, bool B_COL, bool COLSUM, bool VEC, bool GATE_A, bool GATE_B, bool BF16>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_update_gemm(const GemmArgs g)
-{
-    __shared__ __attribute__((aligned(16))) float lds_a[kBuffers][kOperandFloats];
-    __shared__ __attribute__((aligned(16))) float lds_b[kBuffers][kOperandFloats];
-
-    // Workgroups are dealt round-robin to the 8 L2 domains; the ones that share an operand tile
-    // (same outer index) are given consecutive slots of one domain.
-    const int64_t bid = blockIdx.x;
-    const int xcd = (int)(bid % kXcds);
-    const int64_t q = bid / kXcds;
-    const int n_inner = g.split ? g.tiles_r * g.tiles_c : g.tiles_c;
-    const int inner = (int)(q % n_inner);
-    const int64_t outer = (q / n_inner) * kXcds + xcd;
-    if (outer >= g.n_outer) return;
-    int64_t tile_r, kbeg, kend, slab_id;
-    int tile_c;
-    if (g.split) {
-        slab_id = outer;
-        tile_r = inner / g.tiles_c;
-        tile_c = inner % g.tiles_c;
-        kbeg = slab_id * g.slab;
-        kend = kbeg + g.slab < g.Kc ? kbeg + g.slab : g.Kc;
-    } else {
-        slab_id = 0;
-        tile_r = outer;
-        tile_c = inner;
-        kbeg = 0;
-        kend = g.Kc;
-    }
-    const int64_t r0 = tile_r * kTile, c0 = (int64_t)tile_c * kTile;
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wr = wave >> 1, wc = wave & 1;       // 2 x 2 wavefronts, 64 x 64 each
-    const int h = lane >> 5, l32 = lane & 31;
-
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-    float bsum[2] = {0.f, 0.f};
-
-    TileMover<A_COL, VEC, GATE_A, BF16> ma;
-    TileMover<B_COL, VEC, GATE_B, BF16> mb;
-    ma.init(g.a, r0, g.R);
-    mb.init(g.b, c0, g.C);
-    if (kbeg < kend) {
-        ma.fetch(kbeg, kend);
-        mb.fetch(kbeg, kend);
-        ma.stage(lds_a[0], kbeg, kend);
-        mb.stage(lds_b[0], kbeg, kend);
-        __syncthreads();
-    }
-    int buf = 0;
-    for (int64_t k0 = kbeg; k0 < kend; k0 += kStep) {
-        const bool more = k0 + kStep < kend;
-        if (more) {                                // next stage's global loads fly during the MFMAs
-            ma.fetch(k0 + kStep, kend);
-            mb.fetch(k0 + kStep, kend);
-        }
-        const int64_t left = kend - k0;
-        mma_stage<A_COL, B_COL, COLSUM>(lds_a[buf], lds_b[buf], left >= kStep ? kStep / 8 : (int)((left + 7) / 8), wr,
-                                        wc, l32, h, acc, bsum);
-        if (kBuffers == 1) __syncthreads();
-        const int nb = kBuffers == 1 ? 0 : buf ^ 1;
-        if (more) {
-            ma.stage(lds_a[nb], k0 + kStep, kend);
-            mb.stage(lds_b[nb], k0 + kStep, kend);
-        }
-        __syncthreads();
-        buf = nb;
-    }
-
-    // Accumulator element e of lane (h, l32) is row 8*(e/4) + 4*h + e%4, column l32 of its 32 x 32 tile.
     const int64_t row0 = r0 + wr * 64 + 4 * h, col0 = c0 + wc * 64 + l32;
-    // Y and dH of a bf16 call are bf16; slab partials are always fp32.  Y and dH leave with streaming
-    // stores; slab partials are re-read at once.
-    constexpr bool OUT_BF16 = BF16 && !COLSUM, STREAM = !COLSUM;
     typedef typename QuadBits<OUT_BF16>::elem OutT;
     OutT *cb = static_cast<OutT *>(g.c) + slab_id * g.c_slab + row0 * g.ldc + col0;
     const bool relu = g.relu != 0;
@@ -377,12 +202,290 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                 }
         }
     }
-    if (COLSUM && tile_r == 0 && wr == 0) {
+}
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kPairStride = kTile + 8;                        // dwords between pairs of a "col" plane
+constexpr int kPlaneBytes = (kStep / 2) * kPairStride * 4;    // >= kTile * 32, the "row" plane
+static_assert(kPlaneBytes >= kTile * 32 && kStep == 16, "plane size");
+
+__device__ __forceinline__ int row_swizzle(int o) { return ((o >> 2) ^ (o >> 3)) & 1; }
+
+// Planes of the pair (x0, x1), packed as two bf16 per dword (x0 in the low half).
+template <int PLANES>
+__device__ __forceinline__ void split_pair(float x0, float x1, uint32_t (&w)[PLANES])
+{
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const float s = bsum[j] + __shfl_xor(bsum[j], 32);
-            const int64_t col = c0 + wc * 64 + j * 32 + l32;
-            if (h == 0 && col < g.C) g.colsum[slab_id * g.colsum_slab + col] = s;
+    for (int p = 0; p < PLANES; ++p) {
+        const bf16x2 b = {(__bf16)x0, (__bf16)x1};
+        w[p] = __builtin_bit_cast(uint32_t, b);
+        if (p + 1 < PLANES) {
+            x0 -= __uint_as_float(w[p] << 16);
+            x1 -= __uint_as_float(w[p] & 0xFFFF0000u);
+        }
+    }
+}
+
+// One 128 (out) x 16 (contracted) operand tile: global -> registers (fetch), registers -> bf16
+// planes in LDS (stage).  "row": lane t holds contracted 4(t%4)..+3 of out indices t/4 and t/4 + 64;
+// "col": lane t holds out indices 4(t%32)..+3 of contracted 2(t/32) and 2(t/32) + 1.  SUM keeps a
+// running sum per held out index of everything staged ("col" only).  MASK = false is for whole steps of tiles that lie
+// inside the matrices: no lane masks at all.
+template <bool COL, bool VEC, bool GATE, bool BF16, int PLANES, bool SUM>
+struct PlaneMover {
+    typedef typename QuadBits<BF16>::elem E;
+    Quad<GATE, BF16> r[2];      // [slot]
+    uint32_t off[2];
+    int nv_out;             // row: bit s set if slot s is an existing out index; col: quad elements in range
+    int64_t ld, o0;
+    const E *p, *gate;
+    float sum[SUM ? 4 : 1];
+
+    __device__ __forceinline__ void init(const Operand &op, int64_t o0_, int64_t omax)
+    {
+        static_assert(!SUM || COL, "running sums are kept for col operands");
+        const int t = threadIdx.x;
+        ld = op.ld; o0 = o0_; p = static_cast<const E *>(op.p); gate = static_cast<const E *>(op.gate);
+        nv_out = 0;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            if (!COL) {
+                const int dr = t / 4 + 64 * s;
+                off[s] = (uint32_t)dr * (uint32_t)ld + 4u * (t % 4);
+                if (o0 + dr < omax) nv_out |= 1 << s;
+            } else {
+                off[s] = (uint32_t)(2 * (t >> 5) + s) * (uint32_t)ld + 4u * (t & 31);
+            }
+        }
+        if (COL) nv_out = clamp4(omax - (o0 + 4 * (t & 31)));
+#pragma unroll
+        for (int j = 0; j < (SUM ? 4 : 1); ++j) sum[j] = 0.f;
+    }
+
+    template <bool MASK>
+    __device__ __forceinline__ int nvalid(int s, int64_t k0, int64_t kend) const
+    {
+        if (!MASK) return 4;
+        const int t = threadIdx.x;
+        if (!COL) return (nv_out >> s) & 1 ? clamp4(kend - (k0 + 4 * (t % 4))) : 0;
+        return k0 + 2 * (t >> 5) + s < kend ? nv_out : 0;
+    }
+
+    template <bool MASK>
+    __device__ __forceinline__ void fetch(int64_t k0, int64_t kend)
+    {
+        // A step beyond kend has no element; its (masked) loads go to the first element of the tile's
+        // first step, which the host guarantees to be readable.
+        const int64_t kf = k0 < kend ? k0 : 0;                         // uniform
+        const int64_t origin = COL ? kf * ld + o0 : o0 * ld + kf;      // uniform
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+            load_quad<VEC, GATE, BF16>(p + origin, GATE ? gate + origin : nullptr, off[s],
+                                       nvalid<MASK>(s, k0, kend), r[s]);
+    }
+
+    // (k0, kend) must be those of the fetch that filled the register set.
+    template <bool MASK>
+    __device__ __forceinline__ void stage(char *lds, int64_t k0, int64_t kend)
+    {
+        const int t = threadIdx.x;
+        const float4 v0 = mask_quad<GATE, BF16>(r[0], nvalid<MASK>(0, k0, kend));
+        const float4 v1 = mask_quad<GATE, BF16>(r[1], nvalid<MASK>(1, k0, kend));
+        if (!COL) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const float4 v = s == 0 ? v0 : v1;
+                const int o = t / 4 + 64 * s, kq = t % 4;
+                uint32_t lo[PLANES], hi[PLANES];
+                split_pair<PLANES>(v.x, v.y, lo);
+                split_pair<PLANES>(v.z, v.w, hi);
+                char *dst = lds + o * 32 + 16 * ((kq >> 1) ^ row_swizzle(o)) + 8 * (kq & 1);
+#pragma unroll
+                for (int pl = 0; pl < PLANES; ++pl)
+                    *reinterpret_cast<uint2 *>(dst + pl * kPlaneBytes) = make_uint2(lo[pl], hi[pl]);
+            }
+        } else {
+            uint32_t w[4][PLANES];
+            split_pair<PLANES>(v0.x, v1.x, w[0]);
+            split_pair<PLANES>(v0.y, v1.y, w[1]);
+            split_pair<PLANES>(v0.z, v1.z, w[2]);
+            split_pair<PLANES>(v0.w, v1.w, w[3]);
+            char *dst = lds + ((t >> 5) * kPairStride + 4 * (t & 31)) * 4;
+#pragma unroll
+            for (int pl = 0; pl < PLANES; ++pl)
+                *reinterpret_cast<uint4 *>(dst + pl * kPlaneBytes) = make_uint4(w[0][pl], w[1][pl], w[2][pl], w[3][pl]);
+            if (SUM) {
+                sum[0] += v0.x + v1.x;
+                sum[1] += v0.y + v1.y;
+                sum[2] += v0.z + v1.z;
+                sum[3] += v0.w + v1.w;
+            }
+        }
+    }
+};
+
+// The eight values (contracted indices 8h .. 8h+7) of out index o in one plane.
+template <bool COL>
+__device__ __forceinline__ uint4 read_plane(const char *plane, int o, int h)
+{
+    if (!COL) return *reinterpret_cast<const uint4 *>(plane + o * 32 + 16 * (h ^ row_swizzle(o)));
+    const uint32_t *q = reinterpret_cast<const uint32_t *>(plane) + 4 * h * kPairStride + o;
+    return make_uint4(q[0], q[kPairStride], q[2 * kPairStride], q[3 * kPairStride]);
+}
+
+// A wavefront's fragments of one step: [operand a / b][32-wide fragment][plane].
+template <int PLANES>
+struct Frags {
+    uint4 a[2][PLANES], b[2][PLANES];
+};
+
+template <bool A_COL, bool B_COL, int PLANES>
+__device__ __forceinline__ void read_frags(const char *la, const char *lb, int wr, int wc, int l32, int h,
+                                           Frags<PLANES> &f)
+{
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int pl = 0; pl < PLANES; ++pl) {
+            f.a[i][pl] = read_plane<A_COL>(la + pl * kPlaneBytes, wr * 64 + i * 32 + l32, h);
+            f.b[i][pl] = read_plane<B_COL>(lb + pl * kPlaneBytes, wc * 64 + i * 32 + l32, h);
+        }
+}
+
+// All MFMAs of one step; consecutive MFMAs go to different accumulators.
+template <int PLANES>
+__device__ __forceinline__ void mma_frags(const Frags<PLANES> &f, f32x16 (&acc)[2][2])
+{
+    constexpr int kTerms = PLANES == 3 ? 6 : 1;
+    constexpr int pa[6] = {0, 2, 1, 0, 1, 0}, pb[6] = {2, 0, 1, 1, 0, 0};
+#pragma unroll
+    for (int t = 0; t < kTerms; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int x = PLANES == 3 ? pa[t] : 0, y = PLANES == 3 ? pb[t] : 0;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i][x]),
+                                                                   __builtin_bit_cast(bf16x8, f.b[j][y]), acc[i][j], 0, 0, 0);
+            }
+}
+
+// One step of the contracted range: the loads of the next step are issued, this step is multiplied
+// out of LDS buffer `cur`, and the next one is split into the other buffer.  No branch inside.
+template <bool MASK, bool A_COL, bool B_COL, int PLANES, class MoverA, class MoverB>
+__device__ __forceinline__ void one_step(MoverA &ma, MoverB &mb, char *la, char *lb, int cur, int operand_bytes,
+                                         int64_t k0, int64_t kend, int wr, int wc, int l32, int h,
+                                         f32x16 (&acc)[2][2])
+{
+    ma.template fetch<MASK>(k0 + kStep, kend);
+    mb.template fetch<MASK>(k0 + kStep, kend);
+    __builtin_amdgcn_sched_barrier(0);       // the loads stay ahead of the step's other work
+    Frags<PLANES> f;
+    read_frags<A_COL, B_COL, PLANES>(la + cur * operand_bytes, lb + cur * operand_bytes, wr, wc, l32, h, f);
+    mma_frags<PLANES>(f, acc);
+    ma.template stage<MASK>(la + (cur ^ 1) * operand_bytes, k0 + kStep, kend);
+    mb.template stage<MASK>(lb + (cur ^ 1) * operand_bytes, k0 + kStep, kend);
+    __syncthreads();
+}
+
+// The contracted range [kbeg, kend) of one result tile.  The first n_plain steps touch nothing but
+// whole steps of a tile that lies inside both operands (a step also loads and converts the one after
+// it) and run without lane masks; the others, at least one, mask what does not exist - a step beyond
+// kend is a step of zeros.  The MFMAs are not behind any condition other than the two loop counts:
+// accumulators that can reach the end by a path without MFMAs are given a second set of registers
+// by the compiler.
+template <bool A_COL, bool B_COL, int PLANES, class MoverA, class MoverB>
+__device__ __forceinline__ void run_steps(MoverA &ma, MoverB &mb, char *la, char *lb, int operand_bytes, int64_t kbeg,
+                                          int64_t kend, bool inside, int wr, int wc, int l32, int h,
+                                          f32x16 (&acc)[2][2])
+{
+    const int64_t len = kend > kbeg ? kend - kbeg : 0;
+    const int64_t nstep = len > 0 ? (len + kStep - 1) / kStep : 1;
+    int64_t n_plain = inside ? len / kStep - 1 : 0;
+    n_plain = n_plain < 0 ? 0 : (n_plain > nstep - 1 ? nstep - 1 : n_plain);
+    ma.template fetch<true>(kbeg, kend);
+    mb.template fetch<true>(kbeg, kend);
+    ma.template stage<true>(la, kbeg, kend);
+    mb.template stage<true>(lb, kbeg, kend);
+    __syncthreads();
+    int64_t k0 = kbeg;
+    int cur = 0;
+    for (int64_t i = 0; i < n_plain; ++i, k0 += kStep, cur ^= 1)
+        one_step<false, A_COL, B_COL, PLANES>(ma, mb, la, lb, cur, operand_bytes, k0, kend, wr, wc, l32, h, acc);
+    int64_t i = n_plain;
+    do {
+        one_step<true, A_COL, B_COL, PLANES>(ma, mb, la, lb, cur, operand_bytes, k0, kend, wr, wc, l32, h, acc);
+        k0 += kStep;
+        cur ^= 1;
+    } while (++i < nstep);
+}
+
+template <bool A_COL, bool B_COL, bool COLSUM, bool VEC, bool GATE_A, bool GATE_B, bool BF16>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_update_gemm(const GemmArgs g)
+{
+    constexpr int PLANES = BF16 ? 1 : 3;
+    constexpr int kOperandBytes = PLANES * kPlaneBytes;
+    __shared__ __attribute__((aligned(16))) char lds_a[2][kOperandBytes];
+    __shared__ __attribute__((aligned(16))) char lds_b[2][kOperandBytes];
+
+    const int64_t bid = blockIdx.x;
+    const int xcd = (int)(bid % kXcds);
+    const int64_t q = bid / kXcds;
+    const int n_inner = g.split ? g.tiles_r * g.tiles_c : g.tiles_c;
+    const int inner = (int)(q % n_inner);
+    const int64_t outer = (q / n_inner) * kXcds + xcd;
+    if (outer >= g.n_outer) return;
+    int64_t tile_r, kbeg, kend, slab_id;
+    int tile_c;
+    if (g.split) {
+        slab_id = outer;
+        tile_r = inner / g.tiles_c;
+        tile_c = inner % g.tiles_c;
+        kbeg = slab_id * g.slab;
+        kend = kbeg + g.slab < g.Kc ? kbeg + g.slab : g.Kc;
+    } else {
+        slab_id = 0;
+        tile_r = outer;
+        tile_c = inner;
+        kbeg = 0;
+        kend = g.Kc;
+    }
+    const int64_t r0 = tile_r * kTile, c0 = (int64_t)tile_c * kTile;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wr = wave >> 1, wc = wave & 1;       // 2 x 2 wavefronts, 64 x 64 each
+    const int h = lane >> 5, l32 = lane & 31;
+
+    const bool inside = VEC && r0 + kTile <= g.R && c0 + kTile <= g.C;   // uniform
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    PlaneMover<A_COL, VEC, GATE_A, BF16, PLANES, false> ma;
+    PlaneMover<B_COL, VEC, GATE_B, BF16, PLANES, COLSUM> mb;
+    ma.init(g.a, r0, g.R);
+    mb.init(g.b, c0, g.C);
+    run_steps<A_COL, B_COL, PLANES>(ma, mb, lds_a[0], lds_b[0], kOperandBytes, kbeg, kend, inside, wr, wc, l32, h, acc);
+    write_tile<BF16 && !COLSUM, !COLSUM>(g, acc, r0, c0, slab_id, wr, wc, h, l32);
+    if (COLSUM && tile_r == 0) {
+        // Every barrier above has been passed by all lanes, so the LDS is free: add up the eight
+        // running sums of each column in a fixed order.
+        float *red = reinterpret_cast<float *>(lds_b[0]);
+        const int t = threadIdx.x;
+        *reinterpret_cast<float4 *>(red + (t >> 5) * kTile + 4 * (t & 31)) =
+            make_float4(mb.sum[0], mb.sum[1], mb.sum[2], mb.sum[3]);
+        __syncthreads();
+        if (t < kTile) {
+            float s = red[t];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) s += red[i * kTile + t];
+            if (c0 + t < g.C) g.colsum[slab_id * g.colsum_slab + c0 + t] = s;
         }
     }
 }
@@ -465,6 +568,11 @@ fastgl_status launch_gemm(GemmArgs &g, bool bf16, hipStream_t s, const char *wha
     if (g.R == 0) {            // operand a has no elements: give its (all masked) loads a readable address
         g.a.p = g.b.p;
         g.a.gate = nullptr;
+        vec = false;
+    }
+    if (g.Kc == 0) {           // nothing to contract: the same for both operands (the result exists)
+        g.a.p = g.b.p = g.c;
+        g.a.gate = g.b.gate = nullptr;
         vec = false;
     }
     const unsigned nb = (unsigned)blocks;

@@ -1,14 +1,17 @@
 """GPU parity of the update phase (paper Section 2.1, Eq. 2: Y = act(H W + b) and its gradients)
 against the CPU oracle, through the C ABI.
 
-Tolerance (derived from the arithmetic, not tuned): the kernels multiply and accumulate in fp32 on
-the matrix cores; the oracle sums in fp64 and rounds once.  For a chain of L fp32 accumulations
-the textbook bound is |err| <= (L+2) u sum_k |a_k b_k| + u |ref| with u = 2^-24, whatever the
-order of the sum.  L is the contracted length (K for Y, N for dH) and the slab height for dW / db,
-whose slab partials are added in fp64.  That bound is checked element by element; because it is
-loose (it is a worst case), the root-mean-square error is also checked against the random-walk
-estimate 2 u sqrt(L) s, s = the larger of rms(ref) and rms(sum|terms|)/sqrt(L) (the size of the
-partial sums), which a wrong or dropped term breaks by orders of magnitude."""
+Tolerance (derived from the arithmetic, not tuned): the kernels form every product a*b of fp32
+elements from bf16 pieces on the matrix cores (each element is the exact sum of three pieces; six of
+the nine piece products are kept, the dropped ones are at most 2 u |a b| together, u = 2^-24) and
+accumulate in fp32; the oracle sums in fp64 and rounds once.  For a chain of L fp32 accumulations
+the textbook bound is |err| <= (L+2) u sum_k |a_k b_k| + u |ref|, whatever the order of the sum;
+with the dropped piece products |err| <= (L+4) u sum_k |a_k b_k| + u |ref|.  L is the contracted
+length (K for Y, N for dH) and the slab height for dW / db, whose slab partials are added in fp64.
+That bound is checked element by element; because it is loose (it is a worst case), the
+root-mean-square error is also checked against the random-walk estimate 2 u sqrt(L) s, s = the
+larger of rms(ref) and rms(sum|terms|)/sqrt(L) (the size of the partial sums), which a wrong or
+dropped term breaks by orders of magnitude."""
 import numpy as np
 import pytest
 import torch
@@ -30,7 +33,7 @@ def check(got, ref, absprod, L, what):
     if ref.size == 0:
         return
     err = np.abs(got - ref)
-    lim = (L + 2) * U * absprod + U * np.abs(ref) + 1e-30
+    lim = (L + 4) * U * absprod + U * np.abs(ref) + 1e-30
     bad = err > lim
     if bad.any():
         i = np.unravel_index(np.argmax(err - lim), err.shape)
@@ -86,6 +89,35 @@ def run_case(M, K, N, relu, bias, seed, what):
 ])
 def test_update_parity(M, K, N, relu):
     run_case(M, K, N, relu, bias=(N % 2 == 0), seed=M + 7 * K + 13 * N, what="update")
+
+
+def test_update_single_products_of_awkward_elements():
+    """K = 1: every result is one product, so the error of a product formed from bf16 pieces shows
+    undiluted: at most 2 u |a b| from the dropped piece products plus the final rounding.  Elements
+    with all mantissa bits set, just above a power of two, with the two low bytes set, and spread
+    over 60 binades (the pieces of one element then differ by up to 2^-16 in size)."""
+    rng = np.random.default_rng(77)
+    bits = np.array([0x3FFFFFFF, 0x3F800001, 0x3F80FFFF, 0x3F7FFFFF, 0x3FFF0001, 0x3F808080, 0x3FAAAAAA,
+                     0x3FD55555], np.uint32)
+    M, N = 300, 136
+    H = bits[rng.integers(0, len(bits), (M, 1))].view(np.float32) * np.exp2(rng.integers(-30, 30, (M, 1))).astype(np.float32)
+    H *= rng.choice([-1.0, 1.0], (M, 1)).astype(np.float32)
+    W = bits[rng.integers(0, len(bits), (1, N))].view(np.float32) * np.exp2(rng.integers(-30, 30, (1, N))).astype(np.float32)
+    print("case update single products", flush=True)
+    Y = B.fastgl_update_fwd(dev(H), dev(W), None, False)
+    torch.cuda.synchronize()
+    ref = H.astype(np.float64) @ W.astype(np.float64)
+    err = np.abs(Y.cpu().numpy().astype(np.float64) - ref)
+    assert (err <= 3 * U * np.abs(ref)).all(), (err / np.abs(ref)).max() / U
+    # random elements: same bound, and on average well inside it
+    H = rng.standard_normal((M, 1)).astype(np.float32)
+    W = rng.standard_normal((1, N)).astype(np.float32)
+    Y = B.fastgl_update_fwd(dev(H), dev(W), None, False)
+    torch.cuda.synchronize()
+    ref = H.astype(np.float64) @ W.astype(np.float64)
+    err = np.abs(Y.cpu().numpy().astype(np.float64) - ref)
+    assert (err <= 3 * U * np.abs(ref)).all(), (err / np.abs(ref)).max() / U
+    assert (err / np.abs(ref)).mean() <= U
 
 
 def test_update_degenerate():
