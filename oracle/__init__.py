@@ -81,6 +81,10 @@ def lib():
         L.fastgl_oracle_edge_softmax_fwd.restype = i32
         L.fastgl_oracle_edge_softmax_bwd.argtypes = [p, i64, p, p, p]
         L.fastgl_oracle_edge_softmax_bwd.restype = i32
+        L.fastgl_oracle_edge_score_fwd.argtypes = [p, p, i64, i64, p, p, ctypes.c_double, p]
+        L.fastgl_oracle_edge_score_fwd.restype = i32
+        L.fastgl_oracle_edge_score_bwd.argtypes = [p, p, i64, i64, p, p, ctypes.c_double, p, p, p, p]
+        L.fastgl_oracle_edge_score_bwd.restype = i32
         L.fastgl_oracle_match.argtypes = [p, i64, p, i64, p, p, p]
         L.fastgl_oracle_match.restype = i64
         L.fastgl_oracle_overlap.argtypes = [p, i64, p, i64]
@@ -368,6 +372,27 @@ def edge_softmax_bwd(indptr, alpha, grad_alpha):
                                             _ptr(out)):
         raise RuntimeError("oracle failed")
     return out
+
+
+def edge_score_fwd(indptr, indices, el, er, slope):
+    """Attention logits of a GAT head: LeakyReLU(el[u] + er[v]) for every edge (u, v)."""
+    indptr, indices, el, er = _i32(indptr), _i32(indices), _f32(el), _f32(er)
+    assert el.shape[0] == indptr.shape[0] - 1
+    score = np.zeros(indices.shape[0], np.float32)
+    if lib().fastgl_oracle_edge_score_fwd(_ptr(indptr), _ptr(indices), el.shape[0], er.shape[0], _ptr(el), _ptr(er), float(slope), _ptr(score)):
+        raise RuntimeError("oracle failed")
+    return score
+
+
+def edge_score_bwd(indptr, indices, el, er, slope, grad_score):
+    """(grad_el, grad_er) of the attention logits."""
+    indptr, indices, el, er, grad_score = _i32(indptr), _i32(indices), _f32(el), _f32(er), _f32(grad_score)
+    g_el, g_er = np.zeros(el.shape[0], np.float32), np.zeros(er.shape[0], np.float32)
+    acc = np.zeros(max(er.shape[0], 1), np.float64)
+    if lib().fastgl_oracle_edge_score_bwd(_ptr(indptr), _ptr(indices), el.shape[0], er.shape[0], _ptr(el), _ptr(er),
+                                          float(slope), _ptr(grad_score), _ptr(acc), _ptr(g_el), _ptr(g_er)):
+        raise RuntimeError("oracle failed")
+    return g_el, g_er
 
 
 def update_fwd_bf16(H, W, b, relu):

@@ -15,6 +15,14 @@
  *   m_u = the row's largest score (the shift changes nothing mathematically)
  * and its backward pass
  *   dscore_e = alpha_e * (dalpha_e - sum over e' in row u of alpha_e' dalpha_e').
+ * The per-edge score of a GAT head (the paper evaluates GAT but does not print
+ * its formula; this is the definition of the model itself): with el_u, er_v the
+ * projections of the transformed features of target and neighbour on the two
+ * halves of the attention vector,
+ *   score_e = LeakyReLU(el_u + er_v),  LeakyReLU(x) = x for x > 0, slope * x otherwise
+ * and by the chain rule, with g_e = dscore_e * (1 if el_u + er_v > 0 else slope),
+ *   del_u = sum over the incoming edges of u of g_e
+ *   der_v = sum over the edges whose neighbour is v of g_e.
  * All sums in fp64 in edge order, one rounding to fp32.  Rows without edges
  * produce nothing.
  *
@@ -22,7 +30,10 @@
  * the pinned aggregation oracle (the loss is linear in w, so a central
  * difference is exact up to rounding), the dense form G X^T read at the edges,
  * hand-worked softmax values, rows that sum to 1, shift invariance, the
- * softmax Jacobian written out densely, finite differences of the softmax.
+ * softmax Jacobian written out densely, finite differences of the softmax;
+ * for the scores: hand-worked values, slope 1 (the identity, whose gradients
+ * are the degree-weighted sums), the dense form of el 1^T + 1 er^T read at the
+ * edges, finite differences.
  */
 #include <math.h>
 #include <stdint.h>
@@ -95,5 +106,44 @@ int fastgl_oracle_edge_softmax_bwd(const int32_t *indptr, int64_t num_dst, const
         for (int64_t k = indptr[u]; k < indptr[u + 1]; ++k)
             grad_score[k] = (float)((double)alpha[k] * ((double)grad_alpha[k] - s));
     }
+    return 0;
+}
+
+/* score[e] = LeakyReLU(el[u] + er[indices[e]]) for every edge e of row u. */
+int fastgl_oracle_edge_score_fwd(const int32_t *indptr, const int32_t *indices, int64_t num_dst, int64_t num_src,
+                                 const float *el, const float *er, double slope, float *score)
+{
+    if (num_dst < 0 || num_src < 0) return 1;
+    for (int64_t u = 0; u < num_dst; ++u)
+        for (int64_t e = indptr[u]; e < indptr[u + 1]; ++e) {
+            const int64_t v = indices[e];
+            if (v < 0 || v >= num_src) return 2;
+            const double x = (double)el[u] + (double)er[v];
+            score[e] = (float)(x > 0.0 ? x : slope * x);
+        }
+    return 0;
+}
+
+/* grad_el [num_dst], grad_er [num_src] from grad_score [E]; either may be NULL. */
+int fastgl_oracle_edge_score_bwd(const int32_t *indptr, const int32_t *indices, int64_t num_dst, int64_t num_src,
+                                 const float *el, const float *er, double slope, const float *grad_score,
+                                 double *acc_src, float *grad_el, float *grad_er)
+{
+    if (num_dst < 0 || num_src < 0) return 1;
+    for (int64_t v = 0; v < num_src; ++v) acc_src[v] = 0.0;
+    for (int64_t u = 0; u < num_dst; ++u) {
+        double acc = 0.0;
+        for (int64_t e = indptr[u]; e < indptr[u + 1]; ++e) {
+            const int64_t v = indices[e];
+            if (v < 0 || v >= num_src) return 2;
+            const double x = (double)el[u] + (double)er[v];
+            const double g = (double)grad_score[e] * (x > 0.0 ? 1.0 : slope);
+            acc += g;
+            acc_src[v] += g;
+        }
+        if (grad_el) grad_el[u] = (float)acc;
+    }
+    if (grad_er)
+        for (int64_t v = 0; v < num_src; ++v) grad_er[v] = (float)acc_src[v];
     return 0;
 }

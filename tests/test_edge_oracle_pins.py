@@ -116,3 +116,55 @@ def test_e6_softmax_backward_finite_differences():
         sp[k] += 1e-5
         sm[k] -= 1e-5
         assert abs((loss(sp) - loss(sm)) / 2e-5 - ds[k]) < 1e-5, k
+
+
+def test_e7_attention_logits_hand_worked():
+    # rows: u0 <- {v0, v2}, u1 <- {}, u2 <- {v1}; el = (1, 5, -3), er = (0.5, 1, -4); slope 0.2
+    indptr, indices = np.array([0, 2, 2, 3], np.int32), np.array([0, 2, 1], np.int32)
+    el, er = np.array([1, 5, -3], np.float32), np.array([0.5, 1, -4], np.float32)
+    s = oracle.edge_score_fwd(indptr, indices, el, er, 0.2)
+    # 1 + 0.5 = 1.5;  1 - 4 = -3 -> 0.2 * -3 = -0.6;  -3 + 1 = -2 -> -0.4
+    assert np.array_equal(s, np.array([1.5, np.float32(0.2 * -3.0), np.float32(0.2 * -2.0)], np.float32))
+    ds = np.array([10, 100, 1000], np.float32)
+    g_el, g_er = oracle.edge_score_bwd(indptr, indices, el, er, 0.2, ds)
+    # g = (10, 0.2 * 100, 0.2 * 1000) = (10, 20, 200)
+    assert np.allclose(g_el, [30, 0, 200], rtol=1e-7) and np.allclose(g_er, [10, 200, 20], rtol=1e-7)
+
+
+def test_e8_attention_logits_dense_form_and_slope_one():
+    blk = small_block(11, nd=13, ns=21)
+    rng = np.random.default_rng(12)
+    el, er = rng.standard_normal(blk.num_dst).astype(np.float32), rng.standard_normal(blk.num_src).astype(np.float32)
+    rows = np.repeat(np.arange(blk.num_dst), np.diff(blk.indptr))
+    dense = el.astype(np.float64)[:, None] + er.astype(np.float64)[None, :]
+    for slope in (0.2, 0.0, 1.0):
+        s = oracle.edge_score_fwd(blk.indptr, blk.indices, el, er, slope)
+        ref = dense[rows, blk.indices]
+        ref = np.where(ref > 0, ref, slope * ref)
+        assert np.array_equal(s, ref.astype(np.float32)), slope
+    # slope 1: the identity, so the gradients are plain sums of grad_score over rows / over neighbours
+    ds = rng.standard_normal(blk.num_edges).astype(np.float32)
+    g_el, g_er = oracle.edge_score_bwd(blk.indptr, blk.indices, el, er, 1.0, ds)
+    assert np.allclose(g_el, np.bincount(rows, ds.astype(np.float64), blk.num_dst), rtol=1e-6, atol=1e-7)
+    assert np.allclose(g_er, np.bincount(blk.indices, ds.astype(np.float64), blk.num_src), rtol=1e-6, atol=1e-7)
+
+
+def test_e9_attention_logits_finite_differences():
+    blk = small_block(13, nd=10, ns=15)
+    rng = np.random.default_rng(14)
+    el, er = rng.standard_normal(blk.num_dst).astype(np.float32), rng.standard_normal(blk.num_src).astype(np.float32)
+    ds = rng.standard_normal(blk.num_edges).astype(np.float32)
+    g_el, g_er = oracle.edge_score_bwd(blk.indptr, blk.indices, el, er, 0.2, ds)
+    rows = np.repeat(np.arange(blk.num_dst), np.diff(blk.indptr))
+
+    def loss(a, b):         # an fp64 LeakyReLU written here; piecewise linear, so a small step is exact off the kinks
+        x = a[rows] + b[blk.indices]
+        return float((np.where(x > 0, x, 0.2 * x) * ds).sum())
+    a0, b0 = el.astype(np.float64), er.astype(np.float64)
+    h = 1e-6
+    for u in range(blk.num_dst):
+        d = np.zeros_like(a0); d[u] = h
+        assert abs((loss(a0 + d, b0) - loss(a0 - d, b0)) / (2 * h) - g_el[u]) <= 1e-4 * (1 + abs(g_el[u])), u
+    for v in range(blk.num_src):
+        d = np.zeros_like(b0); d[v] = h
+        assert abs((loss(a0, b0 + d) - loss(a0, b0 - d)) / (2 * h) - g_er[v]) <= 1e-4 * (1 + abs(g_er[v])), v
