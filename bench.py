@@ -195,14 +195,18 @@ def match_leg(args, w, B, bg, torch, np, with_cpu=False):
 
 def edge_leg(args, w, layers, workspace, B, torch, np, with_cpu=False):
     """Extra leg (not the headline metric): one attention-style pass over the input-layer block with
-    learned edge weights - softmax of per-edge scores over every destination's incoming edges, the
-    aggregation weighted by it (SUM mode), and the backward pass: dL/dw per edge (sampled dot
-    products), the softmax backward, the weighted backward aggregation."""
+    learned edge weights - the attention logits of a GAT head from per-node terms, their softmax over
+    every destination's incoming edges, the aggregation weighted by it (SUM mode), and the backward
+    pass: dL/dw per edge (sampled dot products), the softmax backward, the gradients of the per-node
+    terms, the weighted backward aggregation."""
     L = layers[0]
     blk, feat, dev = L["blk"], L["feat"], L["X"].device
     g = torch.Generator(device="cuda")
     g.manual_seed(w.seed + 3)
-    score = torch.randn(blk.num_edges, generator=g, device=dev)
+    el = torch.randn(blk.num_dst, generator=g, device=dev)
+    er = torch.randn(blk.num_src, generator=g, device=dev)
+    score = torch.empty(blk.num_edges, device=dev)
+    g_el, g_er = torch.empty_like(el), torch.empty_like(er)
     alpha, gw, gs = torch.empty_like(score), torch.empty_like(score), torch.empty_like(score)
     ews = torch.empty(B.fastgl_edge_workspace_bytes(blk.num_dst, blk.num_edges), dtype=torch.uint8, device=dev)
     plan = B.fastgl_block_plan_create(L["indptr"], L["indices"], blk.num_src, B.PLAN_ALL | B.PLAN_PERM)
@@ -220,12 +224,15 @@ def edge_leg(args, w, layers, workspace, B, torch, np, with_cpu=False):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps
     t = {
+        "score_fwd": timed(lambda: B.fastgl_edge_score_fwd(L["indptr"], L["indices"], el, er, 0.2, score)),
         "softmax_fwd": timed(lambda: B.fastgl_edge_softmax_fwd(L["indptr"], score, alpha, ews)),
         "aggregate_fwd_weighted": timed(lambda: B.fastgl_block_aggregate_fwd(
             L["indptr"], L["indices"], alpha, blk.num_src, "sum", L["X"], out=L["out"], plan=plan, workspace=workspace)),
         "edge_weight_grad": timed(lambda: B.fastgl_edge_weight_grad(
             L["indptr"], L["indices"], blk.num_src, "sum", L["X"], L["G"], grad_w=gw, workspace=ews)),
         "softmax_bwd": timed(lambda: B.fastgl_edge_softmax_bwd(L["indptr"], alpha, gw, gs, ews)),
+        "score_bwd": timed(lambda: B.fastgl_edge_score_bwd(L["indptr"], L["indices"], el, er, 0.2, gs, plan=plan,
+                                                               grad_el=g_el, grad_er=g_er)),
         "aggregate_bwd_weighted": timed(lambda: B.fastgl_block_aggregate_bwd(
             L["indptr"], L["indices"], alpha, blk.num_src, "sum", L["G"], grad_X=L["dX"], plan=plan, workspace=workspace)),
     }
@@ -246,7 +253,7 @@ def edge_leg(args, w, layers, workspace, B, torch, np, with_cpu=False):
                "sample": f"weight gradient + softmax forward over the first {rows} rows ({ne} edges), {dt:.2f} s"}
     return {"cpu_oracle": cpu, "what": f"input-layer block (E={blk.num_edges}, F={feat}, f32), SUM mode with learned weights",
             "ms": {k: round(v, 4) for k, v in t.items()}, "total_ms": round(sum(t.values()), 4),
-            "gedges_per_s": round(5 * blk.num_edges / sum(t.values()) / 1e6, 3),
+            "gedges_per_s": round(len(t) * blk.num_edges / sum(t.values()) / 1e6, 3),
             "roofline": {"bound": "hbm", "kernel": "k_edge_dot (dL/dw per edge)", "achieved": round(ach, 1),
                          "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None,
                          "launch_ms": round(t["edge_weight_grad"], 4), "algorithmic_bytes": int(byt)}}

@@ -12,6 +12,15 @@
  *                 scale factors of the aggregation mode, 1 for SUM)
  *   alpha_e     = exp(score_e - m_u) / sum_row exp(score - m_u)
  *   dscore_e    = alpha_e * (dalpha_e - sum_row alpha * dalpha)
+ * and, for the score itself, what the GAT model defines (the paper evaluates
+ * GAT without printing its formula):
+ *   score_e     = LeakyReLU(el_u + er_v)            (el_u, er_v: projections of
+ *                 the transformed features of target and neighbour on the two
+ *                 halves of the head's attention vector)
+ *   del_u       = sum over row u of g_e,  der_v = sum over the edges with
+ *                 neighbour v of g_e,  g_e = dscore_e * (1 or the slope)
+ * Several heads are several calls on head-major arrays ([head][node][...],
+ * [head][edge]): every array of one head is then contiguous.
  * Blocks are the CSR-by-destination blocks of fastgl_agg.h (indptr int32
  * [num_dst+1], indices int32 [E]); per-edge arrays are fp32 [E] in edge order.
  * Conventions are those of fastgl_agg.h: caller-owned DEVICE memory, caller
@@ -51,6 +60,25 @@ fastgl_status fastgl_edge_softmax_fwd(const int32_t *indptr, int64_t num_dst, in
 fastgl_status fastgl_edge_softmax_bwd(const int32_t *indptr, int64_t num_dst, int64_t num_edges,
                                       const float *alpha, const float *grad_alpha, float *grad_score,
                                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* score[e] = LeakyReLU(el[u] + er[indices[e]]) for every edge e of every row u;
+ * LeakyReLU(x) = x for x > 0 and slope * x otherwise (slope finite; 0.2 in the
+ * GAT model).  el fp32 [num_dst], er fp32 [num_src], score fp32 [num_edges].
+ * The sum is formed exactly (fp64) and the result rounded once. */
+fastgl_status fastgl_edge_score_fwd(const int32_t *indptr, const int32_t *indices, int64_t num_dst,
+                                    int64_t num_src, int64_t num_edges, const float *el, const float *er,
+                                    float slope, float *score, void *stream);
+
+/* grad_el[u] = sum over row u of g_e and grad_er[v] = sum over the edges with
+ * indices[e] == v of g_e, g_e = grad_score[e] * (el[u] + er[v] > 0 ? 1 : slope);
+ * fp64 sums, one rounding, every entry written (0 for nodes without edges).
+ * Either result may be NULL.  grad_er walks the transposed block and needs a
+ * plan of this block built with FASTGL_PLAN_BWD | FASTGL_PLAN_PERM; grad_el
+ * alone takes plan = NULL. */
+fastgl_status fastgl_edge_score_bwd(const int32_t *indptr, const int32_t *indices, int64_t num_dst,
+                                    int64_t num_src, int64_t num_edges, const float *el, const float *er,
+                                    float slope, const float *grad_score, const fastgl_plan *plan,
+                                    float *grad_el, float *grad_er, void *stream);
 
 /* Rows with more edges than this are handed to whole workgroups by the softmax calls. */
 int32_t fastgl_edge_softmax_long_row(void);

@@ -375,7 +375,9 @@ def edge_softmax_bwd(indptr, alpha, grad_alpha):
 
 
 def edge_score_fwd(indptr, indices, el, er, slope):
-    """Attention logits of a GAT head: LeakyReLU(el[u] + er[v]) for every edge (u, v)."""
+    """Attention logits of a GAT head: LeakyReLU(el[u] + er[v]) for every edge (u, v).  The slope is an
+    fp32 parameter of the layer, like el and er: it is rounded to fp32 before use."""
+    slope = float(np.float32(slope))
     indptr, indices, el, er = _i32(indptr), _i32(indices), _f32(el), _f32(er)
     assert el.shape[0] == indptr.shape[0] - 1
     score = np.zeros(indices.shape[0], np.float32)
@@ -385,7 +387,8 @@ def edge_score_fwd(indptr, indices, el, er, slope):
 
 
 def edge_score_bwd(indptr, indices, el, er, slope, grad_score):
-    """(grad_el, grad_er) of the attention logits."""
+    """(grad_el, grad_er) of the attention logits (slope rounded to fp32 as in the forward pass)."""
+    slope = float(np.float32(slope))
     indptr, indices, el, er, grad_score = _i32(indptr), _i32(indices), _f32(el), _f32(er), _f32(grad_score)
     g_el, g_er = np.zeros(el.shape[0], np.float32), np.zeros(er.shape[0], np.float32)
     acc = np.zeros(max(er.shape[0], 1), np.float64)

@@ -31,7 +31,7 @@ EXPORTS = [
     "fastgl_match", "fastgl_match_workspace_bytes", "fastgl_assemble_rows", "fastgl_overlap_counts",
     "fastgl_overlap_workspace_bytes", "fastgl_greedy_reorder",
     "fastgl_edge_workspace_bytes", "fastgl_edge_weight_grad", "fastgl_edge_softmax_fwd", "fastgl_edge_softmax_bwd",
-    "fastgl_edge_softmax_long_row",
+    "fastgl_edge_softmax_long_row", "fastgl_edge_score_fwd", "fastgl_edge_score_bwd",
 ]
 MAX_REORDER_BATCHES = 64
 IDMAP_MODES = {"ordered": 0, "fused": 1}
@@ -103,6 +103,8 @@ def lib() -> ctypes.CDLL:
         L.fastgl_edge_softmax_fwd.argtypes = [p, i64, i64, p, p, p, sz, p]
         L.fastgl_edge_softmax_bwd.argtypes = [p, i64, i64, p, p, p, p, sz, p]
         L.fastgl_edge_softmax_long_row.restype = ctypes.c_int32
+        L.fastgl_edge_score_fwd.argtypes = [p, p, i64, i64, i64, p, p, ctypes.c_float, p, p]
+        L.fastgl_edge_score_bwd.argtypes = [p, p, i64, i64, i64, p, p, ctypes.c_float, p, p, p, p, p]
         L.fastgl_idmap_table_slots.argtypes = [i64]
         L.fastgl_idmap_table_slots.restype = i64
         L.fastgl_idmap_workspace_bytes.argtypes = [i64, i64]
@@ -533,3 +535,48 @@ def fastgl_edge_softmax_bwd(indptr, alpha: torch.Tensor, grad_alpha: torch.Tenso
                                          _ptr(grad_alpha), _ptr(grad_score), _ptr(workspace), workspace.numel(),
                                          _stream()))
     return grad_score
+
+
+def fastgl_edge_score_fwd(indptr, indices, el: torch.Tensor, er: torch.Tensor, slope: float,
+                          score: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    _dev(el, torch.float32, "el")
+    _dev(er, torch.float32, "er")
+    num_dst, num_edges = indptr.numel() - 1, indices.numel()
+    if el.numel() != num_dst:
+        raise ValueError("el must have one entry per destination node")
+    if score is None:
+        score = torch.empty(num_edges, dtype=torch.float32, device=el.device)
+    _dev(score, torch.float32, "score")
+    if score.numel() != num_edges:
+        raise ValueError("score must have one entry per edge")
+    _check(lib().fastgl_edge_score_fwd(_ptr(indptr), _ptr(indices), num_dst, er.numel(), num_edges, _ptr(el), _ptr(er),
+                                       float(slope), _ptr(score), _stream()))
+    return score
+
+
+def fastgl_edge_score_bwd(indptr, indices, el: torch.Tensor, er: torch.Tensor, slope: float, grad_score: torch.Tensor,
+                          plan: Optional[Plan] = None, want=("el", "er"), grad_el: Optional[torch.Tensor] = None,
+                          grad_er: Optional[torch.Tensor] = None):
+    """(grad_el, grad_er); `want` selects which are computed when no array is passed in (the other is
+    None).  grad_er needs a plan built with PLAN_BWD | PLAN_PERM."""
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    _dev(el, torch.float32, "el")
+    _dev(er, torch.float32, "er")
+    _dev(grad_score, torch.float32, "grad_score")
+    num_dst, num_edges = indptr.numel() - 1, indices.numel()
+    if el.numel() != num_dst or grad_score.numel() != num_edges:
+        raise ValueError("el must have one entry per destination node, grad_score one per edge")
+    g_el = grad_el if grad_el is not None else (torch.empty_like(el) if "el" in want else None)
+    g_er = grad_er if grad_er is not None else (torch.empty_like(er) if "er" in want else None)
+    for name, g, ref in (("grad_el", g_el, el), ("grad_er", g_er, er)):
+        if g is not None:
+            _dev(g, torch.float32, name)
+            if g.numel() != ref.numel():
+                raise ValueError(f"{name} must have one entry per node")
+    _check(lib().fastgl_edge_score_bwd(_ptr(indptr), _ptr(indices), num_dst, er.numel(), num_edges, _ptr(el), _ptr(er),
+                                       float(slope), _ptr(grad_score), plan.handle if plan is not None else None,
+                                       _ptr(g_el), _ptr(g_er), _stream()))
+    return g_el, g_er

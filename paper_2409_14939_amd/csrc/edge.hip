@@ -397,6 +397,78 @@ fastgl_status softmax(bool backward, const int32_t *indptr, int64_t num_dst, int
     return FASTGL_OK;
 }
 
+
+// ---------------------------------------------------------------- attention logits of a GAT head
+// score_e = LeakyReLU(el[u] + er[v]) and the sums of its gradient over rows.  The same kernels run on
+// the block's CSR (rows = destinations, col = neighbours) and on its transpose (rows = neighbours,
+// col = destinations, eid = original edge ids): `row_val` belongs to the row index, `col_val` to col.
+struct ScoreArgs {
+    const int32_t *rowptr, *col, *eid;     // eid NULL: the edge id is the position
+    int64_t num_rows;
+    const float *row_val, *col_val;
+    const float *grad_score;               // backward only
+    float *out;                            // forward: [E] scores; backward: [num_rows] sums
+    double slope;
+};
+
+template <int lanes, bool BACKWARD>
+__global__ __launch_bounds__(256) void k_edge_score(const ScoreArgs a)
+{
+    const int64_t r = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / lanes;
+    const int l = threadIdx.x % lanes;
+    int b = 0, e = 0;
+    double mine = 0.0;
+    if (r < a.num_rows) {
+        b = a.rowptr[r];
+        e = a.rowptr[r + 1];
+        mine = (double)a.row_val[r];
+    }
+    double acc = 0.0;
+    for (int k = b + l; k < e; k += lanes) {
+        const double x = mine + (double)a.col_val[a.col[k]];      // exact: both are fp32
+        if (!BACKWARD)
+            a.out[k] = (float)(x > 0.0 ? x : a.slope * x);
+        else
+            acc += (double)a.grad_score[a.eid ? a.eid[k] : k] * (x > 0.0 ? 1.0 : a.slope);
+    }
+    if (BACKWARD) {
+        acc = group_sum<double>(acc, lanes);       // every lane of the group takes part
+        if (l == 0 && r < a.num_rows) a.out[r] = (float)acc;
+    }
+}
+
+template <bool BACKWARD>
+void launch_score(const ScoreArgs &a, int64_t nnz, hipStream_t s)
+{
+    const int64_t mean = nnz / (a.num_rows > 0 ? a.num_rows : 1);
+    if (mean < 24)
+        hipLaunchKernelGGL((k_edge_score<8, BACKWARD>), dim3((unsigned)ceil_div(a.num_rows * 8, 256)), dim3(256), 0, s, a);
+    else if (mean < 96)
+        hipLaunchKernelGGL((k_edge_score<32, BACKWARD>), dim3((unsigned)ceil_div(a.num_rows * 32, 256)), dim3(256), 0, s, a);
+    else
+        hipLaunchKernelGGL((k_edge_score<64, BACKWARD>), dim3((unsigned)ceil_div(a.num_rows * 64, 256)), dim3(256), 0, s, a);
+}
+
+fastgl_status check_score_args(const int32_t *indptr, const int32_t *indices, int64_t num_dst, int64_t num_src,
+                               int64_t E, const float *el, const float *er, float slope)
+{
+    fastgl_status st = check_csr(indptr, num_dst, E);
+    if (st != FASTGL_OK) return st;
+    if (num_src < 0 || num_src >= INT32_MAX) {
+        set_error("num_src out of range");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    if (!(slope == slope) || slope - slope != 0.f) {
+        set_error("slope must be finite");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    if (E > 0 && (!indices || !el || !er || num_src == 0 || (((uintptr_t)indices | (uintptr_t)el | (uintptr_t)er) & 3))) {
+        set_error("NULL or misaligned array (indices, el or er), or no source nodes");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    return FASTGL_OK;
+}
+
 }  // namespace
 }  // namespace fastgl
 
@@ -501,6 +573,62 @@ fastgl_status fastgl_edge_softmax_bwd(const int32_t *indptr, int64_t num_dst, in
 {
     return softmax(true, indptr, num_dst, num_edges, alpha, grad_alpha, grad_score, workspace, workspace_bytes,
                    stream);
+}
+
+fastgl_status fastgl_edge_score_fwd(const int32_t *indptr, const int32_t *indices, int64_t num_dst, int64_t num_src,
+                                    int64_t num_edges, const float *el, const float *er, float slope, float *score,
+                                    void *stream)
+{
+    fastgl_status st = check_score_args(indptr, indices, num_dst, num_src, num_edges, el, er, slope);
+    if (st != FASTGL_OK) return st;
+    if (num_edges == 0) return FASTGL_OK;
+    if (!score || ((uintptr_t)score & 3)) {
+        set_error("score is NULL or misaligned");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    ScoreArgs a = {};
+    a.rowptr = indptr; a.col = indices; a.num_rows = num_dst;
+    a.row_val = el; a.col_val = er; a.out = score; a.slope = (double)slope;
+    launch_score<false>(a, num_edges, (hipStream_t)stream);
+    FASTGL_LAUNCH_CHECK("fastgl_edge_score_fwd");
+    return FASTGL_OK;
+}
+
+fastgl_status fastgl_edge_score_bwd(const int32_t *indptr, const int32_t *indices, int64_t num_dst, int64_t num_src,
+                                    int64_t num_edges, const float *el, const float *er, float slope,
+                                    const float *grad_score, const fastgl_plan *plan, float *grad_el, float *grad_er,
+                                    void *stream)
+{
+    fastgl_status st = check_score_args(indptr, indices, num_dst, num_src, num_edges, el, er, slope);
+    if (st != FASTGL_OK) return st;
+    if ((((uintptr_t)grad_score | (uintptr_t)grad_el | (uintptr_t)grad_er) & 3) || (num_edges > 0 && !grad_score)) {
+        set_error("grad_score is NULL, or a gradient array is misaligned");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (grad_el && num_dst > 0) {
+        if (!el && num_edges == 0) el = grad_el;       // rows without edges read nothing but their own value
+        ScoreArgs a = {};
+        a.rowptr = indptr; a.col = indices; a.num_rows = num_dst;
+        a.row_val = el; a.col_val = er; a.grad_score = grad_score; a.out = grad_el; a.slope = (double)slope;
+        launch_score<true>(a, num_edges, s);
+        FASTGL_LAUNCH_CHECK("fastgl_edge_score_bwd (grad_el)");
+    }
+    if (grad_er && num_src > 0) {
+        const int need = FASTGL_PLAN_BWD | FASTGL_PLAN_PERM;
+        if (!plan || plan->indptr != indptr || plan->indices != indices || plan->num_dst != num_dst ||
+            plan->num_src != num_src || plan->num_edges != num_edges || (plan->parts & need) != need) {
+            set_error("grad_er needs a plan of this block built with FASTGL_PLAN_BWD | FASTGL_PLAN_PERM");
+            return FASTGL_ERR_INVALID_ARG;
+        }
+        if (!er && num_edges == 0) er = grad_er;
+        ScoreArgs a = {};
+        a.rowptr = plan->indptr_T; a.col = plan->indices_T; a.eid = plan->perm; a.num_rows = num_src;
+        a.row_val = er; a.col_val = el; a.grad_score = grad_score; a.out = grad_er; a.slope = (double)slope;
+        launch_score<true>(a, num_edges, s);
+        FASTGL_LAUNCH_CHECK("fastgl_edge_score_bwd (grad_er)");
+    }
+    return FASTGL_OK;
 }
 
 }  // extern "C"

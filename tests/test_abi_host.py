@@ -193,3 +193,15 @@ def test_edge_argument_checks():
     b = L.fastgl_edge_softmax_bwd
     assert b(FAKE, 4, 4, FAKE, None, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
     assert b(FAKE, 4, 0, None, None, None, None, 0, None) == B.FASTGL_OK
+    s = L.fastgl_edge_score_fwd
+    nan = float("nan")
+    assert s(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, None, None) == B.FASTGL_ERR_INVALID_ARG       # no score array
+    assert s(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, nan, FAKE, None) == B.FASTGL_ERR_INVALID_ARG and "slope" in B.fastgl_last_error()
+    assert s(FAKE, FAKE, 4, 4, 4, None, FAKE, 0.2, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert s(FAKE, FAKE, 4, -1, 4, FAKE, FAKE, 0.2, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert s(FAKE, None, 4, 4, 0, None, None, 0.2, None, None) == B.FASTGL_OK                     # no edges
+    sb = L.fastgl_edge_score_bwd
+    assert sb(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, None, None, FAKE, None, None) == B.FASTGL_ERR_INVALID_ARG   # grad_score
+    assert sb(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, FAKE, None, None, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "FASTGL_PLAN_PERM" in B.fastgl_last_error()                                                 # grad_er needs the plan
+    assert sb(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, FAKE, None, None, None, None) == B.FASTGL_OK      # nothing asked for

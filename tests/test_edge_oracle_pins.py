@@ -140,7 +140,7 @@ def test_e8_attention_logits_dense_form_and_slope_one():
     for slope in (0.2, 0.0, 1.0):
         s = oracle.edge_score_fwd(blk.indptr, blk.indices, el, er, slope)
         ref = dense[rows, blk.indices]
-        ref = np.where(ref > 0, ref, slope * ref)
+        ref = np.where(ref > 0, ref, float(np.float32(slope)) * ref)      # the slope is an fp32 parameter
         assert np.array_equal(s, ref.astype(np.float32)), slope
     # slope 1: the identity, so the gradients are plain sums of grad_score over rows / over neighbours
     ds = rng.standard_normal(blk.num_edges).astype(np.float32)

@@ -36,7 +36,10 @@ def test_update_idmap_match_edge_capture_and_replay():
         src_row=i32(1500), load_pos=i32(1500), load_gid=torch.empty(1500, dtype=torch.int64, device="cuda"), mres=i32(2),
         X_new=torch.empty(1500, feat, device="cuda"),
         alpha=torch.empty(E, device="cuda"), gw=torch.empty(E, device="cuda"), gs=torch.empty(E, device="cuda"),
+        sc=torch.empty(E, device="cuda"), g_el=torch.empty(nd, device="cuda"), g_er=torch.empty(ns, device="cuda"),
     )
+    el, er = f32(nd), f32(ns)
+    plan = B.fastgl_block_plan_create(ip, ix, ns, B.PLAN_ALL | B.PLAN_PERM)
     ws_u, ws_i = u8(B.fastgl_update_bwd_workspace_bytes(nd, feat, N)), u8(B.fastgl_idmap_workspace_bytes(nd, E))
     ws_m, ws_e = u8(B.fastgl_match_workspace_bytes(1800, 1500)), u8(B.fastgl_edge_workspace_bytes(nd, E))
     # the number of rows Match asks to load is fixed by the inputs; learn it once, eagerly
@@ -52,8 +55,12 @@ def test_update_idmap_match_edge_capture_and_replay():
         B.fastgl_edge_softmax_fwd(ip, score, O["alpha"], ws_e)
         B.fastgl_edge_weight_grad(ip, ix, ns, "sum", X, G, grad_w=O["gw"], workspace=ws_e)
         B.fastgl_edge_softmax_bwd(ip, O["alpha"], O["gw"], O["gs"], ws_e)
+        B.fastgl_edge_score_fwd(ip, ix, el, er, 0.2, O["sc"])
+        B.fastgl_edge_score_bwd(ip, ix, el, er, 0.2, O["gs"], plan=plan, grad_el=O["g_el"], grad_er=O["g_er"])
 
-    outs = ["Y", "dH", "dW", "db", "local", "res", "src_row", "load_pos", "mres", "X_new", "alpha", "gw", "gs"]
+    outs = ["Y", "dH", "dW", "db", "local", "res", "src_row", "load_pos", "mres", "X_new", "alpha", "gw", "gs", "sc", "g_el", "g_er"]
+    for k in outs:                                       # entries no call writes (the tail of load_pos) compare as zeros
+        O[k].zero_()
     step()
     torch.cuda.synchronize()
     ref = {k: O[k].clone() for k in outs}
