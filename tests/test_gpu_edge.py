@@ -115,6 +115,7 @@ def test_edge_paths_on_the_sampled_workload():
     close(gw.cpu().numpy(), oracle.edge_weight_grad(blk.indptr, blk.indices, blk.num_src, "gcn", "f32", X, G),
           1e-5, 1e-6, "grad_w")
     softmax_case(blk, 5, "config2 input layer")
+    score_case(blk, 6, 0.2, "config2 input layer")
 
 
 def test_edge_random_block_sweep():
