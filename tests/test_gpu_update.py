@@ -120,6 +120,15 @@ def test_update_single_products_of_awkward_elements():
     assert (err / np.abs(ref)).mean() <= U
 
 
+def test_update_long_extents():
+    """Extents far from the benchmark's: a very wide result (32 768 column tiles, a leading dimension of
+    2^22 elements in the 32-bit lane offsets) and a very long contracted range (262 144 steps in one
+    workgroup; 4 096 slabs for dW)."""
+    run_case(3, 5, 1 << 22, True, bias=True, seed=901, what="wide N")
+    run_case(2, 1 << 22, 3, False, bias=False, seed=902, what="long K")
+    run_case((1 << 22) + 3, 2, 3, True, bias=True, seed=903, what="tall M")
+
+
 def test_update_degenerate():
     # K = 0: Y = act(b); M = 0: gradients of the weights are zero; N = 0: dH is zero
     b = np.array([-1.0, 2.0, 0.5], np.float32)
