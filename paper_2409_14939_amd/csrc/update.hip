@@ -232,8 +232,8 @@ __device__ __forceinline__ void split_pair(float x0, float x1, uint32_t (&w)[PLA
 // One 128 (out) x 16 (contracted) operand tile: global -> registers (fetch), registers -> bf16
 // planes in LDS (stage).  "row": lane t holds contracted 4(t%4)..+3 of out indices t/4 and t/4 + 64;
 // "col": lane t holds out indices 4(t%32)..+3 of contracted 2(t/32) and 2(t/32) + 1.  SUM keeps a
-// running sum per held out index of everything staged ("col" only).  MASK = false is for whole steps of tiles that lie
-// inside the matrices: no lane masks at all.
+// running sum per held out index of everything staged ("col" only).  MASK = false is for whole steps
+// of tiles that lie inside the matrices: no lane masks at all.
 template <bool COL, bool VEC, bool GATE, bool BF16, int PLANES, bool SUM>
 struct PlaneMover {
     typedef typename QuadBits<BF16>::elem E;
@@ -277,8 +277,9 @@ struct PlaneMover {
     template <bool MASK>
     __device__ __forceinline__ void fetch(int64_t k0, int64_t kend)
     {
-        // A step beyond kend has no element; its (masked) loads go to the first element of the tile's
-        // first step, which the host guarantees to be readable.
+        // A step beyond kend has no element; its (all masked) loads go to contracted index 0 of the
+        // tile's first out index, an element that exists whenever the operand has any (the host
+        // substitutes a readable pointer when it has none).
         const int64_t kf = k0 < kend ? k0 : 0;                         // uniform
         const int64_t origin = COL ? kf * ld + o0 : o0 * ld + kf;      // uniform
 #pragma unroll
