@@ -259,6 +259,47 @@ def edge_leg(args, w, layers, workspace, B, torch, np, with_cpu=False):
                          "launch_ms": round(t["edge_weight_grad"], 4), "algorithmic_bytes": int(byt)}}
 
 
+def locality_leg(args, w, layers, workspace, B, bg, torch, np):
+    """Extra leg (not the headline metric): the input-layer block with the same sizes and row lengths
+    but its neighbours re-drawn inside a band around the diagonal (blockgen.banded_like), i.e. a block
+    with the locality that a graph with community structure has under a locality-preserving node
+    order.  Same kernels, same launch shapes; shows what the aggregation reaches when the gathered
+    rows can be reused out of L2, which the Chung-Lu workload cannot offer."""
+    L = layers[0]
+    blk, feat, dev = L["blk"], L["feat"], L["X"].device
+    elem = L["X"].element_size()
+    res = {"what": f"input-layer block, neighbours re-drawn within a band of W source rows (E={blk.num_edges}, F={feat})",
+           "bands": []}
+    reps = max(5, args.steps // 2)
+    for window in (1024, 16384, 262144):
+        bb = bg.banded_like(blk, window, w.seed + 17)
+        ip, ix = torch.from_numpy(bb.indptr).to(dev), torch.from_numpy(bb.indices).to(dev)
+        dout = np.bincount(bb.indices, minlength=bb.num_src)
+        byt_f = compulsory_bytes(bb.num_dst, bb.num_edges, int((dout > 0).sum()), bb.num_dst, feat, elem)
+        byt_b = compulsory_bytes(bb.num_src, bb.num_edges, int((np.diff(bb.indptr) > 0).sum()), bb.num_src, feat, elem)
+        plan = B.fastgl_block_plan_create(ip, ix, bb.num_src, B.PLAN_ALL, L["plan_mem"])
+
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        f = timed(lambda: B.fastgl_block_aggregate_fwd(ip, ix, None, bb.num_src, w.mode, L["X"], out=L["out"], plan=plan,
+                                                       workspace=workspace))
+        b = timed(lambda: B.fastgl_block_aggregate_bwd(ip, ix, None, bb.num_src, w.mode, L["G"], grad_X=L["dX"], plan=plan,
+                                                       workspace=workspace))
+        res["bands"].append({"W": window, "unique_src_rows": int((dout > 0).sum()), "fwd_ms": round(f, 4), "bwd_ms": round(b, 4),
+                             "fwd_gbps_compulsory": round(byt_f / f / 1e6, 1), "fwd_frac_of_peak": round(byt_f / f / 1e6 / HBM_PEAK_GBPS, 4),
+                             "bwd_gbps_compulsory": round(byt_b / b / 1e6, 1), "bwd_frac_of_peak": round(byt_b / b / 1e6 / HBM_PEAK_GBPS, 4)})
+    return res
+
+
 def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=False):
     """Extra leg (not the headline metric): one training step of the whole sampled GCN on the same
     mini-batch - per layer aggregate (Eq. 1) then update (Eq. 2, Y = act(H W + b)), ReLU between
@@ -416,6 +457,9 @@ def main() -> int:
     ap.add_argument("--match-batches", type=int, default=4)
     ap.add_argument("--no-edge", action="store_true",
                     help="skip the extra leg that times the learned-edge-weight path (edge softmax, weight gradient)")
+    ap.add_argument("--locality", action="store_true",
+                    help="also run the aggregation on banded copies of the input-layer block (neighbours re-drawn "
+                         "near the diagonal): what the kernels reach when gathered rows can be reused out of L2")
     ap.add_argument("--no-gcn-step", action="store_true",
                     help="skip the extra leg that times the whole sampled GCN (aggregation + update phase)")
     ap.add_argument("--verbose", action="store_true")
@@ -606,6 +650,8 @@ def main() -> int:
     if not args.no_edge and w.dtype == "f32":
         result["edge_weights"] = edge_leg(args, w, layers, workspace, B, torch, np,
                                           with_cpu=not args.no_cpu_baseline)
+    if args.locality and args.config == 2:
+        result["locality_probe"] = locality_leg(args, w, layers, workspace, B, bg, torch, np)
     if not args.no_gcn_step and len(layers) > 1:
         result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np,
                                           with_cpu=not args.no_cpu_baseline)

@@ -379,6 +379,21 @@ def random_block(rng: np.random.Generator, num_dst: int, num_src: int, avg_deg: 
     return blk
 
 
+def banded_like(blk: Block, window: int, seed: int) -> Block:
+    """A block with the row lengths of `blk` whose neighbours are re-drawn near the diagonal:
+    row u takes its neighbours uniformly from the `window` source rows around u * num_src / num_dst.
+    Same sizes and degree sequence as `blk`, but with the locality a graph with community structure
+    has after a locality-preserving node ordering (which a Chung-Lu graph cannot offer)."""
+    rng = np.random.default_rng(seed)
+    rows = np.repeat(np.arange(blk.num_dst, dtype=np.int64), np.diff(blk.indptr))
+    centre = rows * blk.num_src // max(blk.num_dst, 1)
+    idx = centre + rng.integers(-(window // 2), window // 2 + 1, size=rows.shape[0])
+    idx = np.clip(idx, 0, blk.num_src - 1)
+    out = Block(blk.indptr.copy(), idx.astype(np.int32), blk.num_dst, blk.num_src)
+    out.check()
+    return out
+
+
 def minibatch_node_sets(n_batches: int, seed: int, n: int = 2_400_000, avg: float = 50.0, gamma: float = 2.1,
                         n_seeds: int = 8000, fanouts: Sequence[int] = (15, 10, 5)):
     """Node sets of several mini-batches sampled from ONE graph (the products-shaped Chung-Lu graph
