@@ -55,3 +55,15 @@ def test_chung_lu_calibration():
     assert np.all(np.diff(w) <= 0)
     gid = g.global_id(r)
     assert np.unique(gid).shape[0] == g.n
+
+
+def test_banded_copy_keeps_sizes_and_stays_near_the_diagonal():
+    blk = bg.random_block(np.random.default_rng(3), 500, 1300, 4.0, empty_frac=0.2, hub_rows=2, hub_deg=300)
+    band = bg.banded_like(blk, 64, 9)
+    assert band.num_dst == blk.num_dst and band.num_src == blk.num_src
+    assert np.array_equal(band.indptr, blk.indptr)
+    rows = np.repeat(np.arange(blk.num_dst), np.diff(blk.indptr))
+    centre = rows * blk.num_src // blk.num_dst
+    assert (np.abs(band.indices.astype(np.int64) - centre) <= 32).all()
+    assert np.array_equal(band.indices, bg.banded_like(blk, 64, 9).indices)          # same seed, same block
+    assert not np.array_equal(band.indices, bg.banded_like(blk, 64, 10).indices)
