@@ -31,9 +31,10 @@ namespace {
 
 constexpr int kTile = 128;              // rows and columns of a workgroup's result tile
 constexpr int kStep = 16;               // contracted indices per LDS stage
-constexpr int kMaxSlabRows = 1024;      // most rows of H per dW / db partial
-constexpr int kMinSlabRows = 128;
-constexpr int kSlabFill = 640;          // workgroups wanted before slabs stop shrinking
+constexpr int kMaxSlabRows = 2048;      // most rows of H per dW / db partial
+constexpr int kMinSlabRows = 32;
+constexpr int kSlabRowStep = 32;        // slab heights considered: 32, 64, ..., 2048
+constexpr int kRoundSlots = 768;        // workgroups the device this is tuned for holds at once (256 CUs x 3)
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -602,12 +603,26 @@ fastgl_status check_dims(int64_t M, int64_t K, int64_t N)
 }
 
 // Rows per slab: a function of the shape alone, so results do not depend on the device or the run.
+// The height that minimises a model of the launch: the (slab, tile) workgroups run in rounds of
+// kRoundSlots, a workgroup costs its steps plus a fixed part, and every slab adds a partial result
+// that is written once and read once by the reduction.  Integer arithmetic (picoseconds).
 int64_t slab_rows(int64_t M, int64_t K, int64_t N)
 {
     const int64_t tiles = (K > 0 ? ceil_div(K, kTile) : 1) * ceil_div(N, kTile);
-    int64_t rows = kMaxSlabRows;
-    while (rows > kMinSlabRows && ceil_div(M, rows) * tiles < kSlabFill) rows /= 2;
-    return rows;
+    const int64_t partial = K * N + N;                 // floats per slab
+    int64_t best = kMinSlabRows, best_cost = INT64_MAX;
+    for (int64_t rows = kMinSlabRows; rows <= kMaxSlabRows; rows += kSlabRowStep) {
+        const int64_t nslab = ceil_div(M > 0 ? M : 1, rows);
+        const int64_t rounds = ceil_div(nslab * tiles, kRoundSlots);
+        // 2.5 us per step of 16 rows with three workgroups on a CU, 8 steps' worth of prologue and
+        // epilogue; 8 bytes of traffic per float of a partial at 4 TB/s
+        const int64_t cost = rounds * (rows * 156250 + 20000000) + nslab * partial * 2;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = rows;
+        }
+    }
+    return best;
 }
 
 size_t bwd_workspace(int64_t M, int64_t K, int64_t N)

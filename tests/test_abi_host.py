@@ -85,7 +85,8 @@ def test_update_argument_checks():
     L = B.lib()
     big = B.fastgl_update_slab_rows(512345, 100, 256)
     assert B.fastgl_update_slab_rows(-1, 4, 4) == 0
-    assert 128 <= B.fastgl_update_slab_rows(100, 100, 256) <= B.fastgl_update_slab_rows(91331, 256, 256) <= big <= 1024
+    assert 32 <= B.fastgl_update_slab_rows(100, 100, 256) <= B.fastgl_update_slab_rows(91331, 256, 256) <= big <= 2048
+    assert all(B.fastgl_update_slab_rows(m, 100, 256) % 32 == 0 for m in (1, 77, 5000, 512345))
     assert B.fastgl_update_bwd_workspace_bytes(-1, 4, 4) == 0
     nslab = -(-512345 // big)
     assert B.fastgl_update_bwd_workspace_bytes(512345, 100, 256) >= 4 * nslab * (100 * 256 + 256)

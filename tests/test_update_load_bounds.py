@@ -17,10 +17,14 @@ def clamp4(n):
 
 def slab_rows(M, K, N):
     tiles = (max((K + 127) // 128, 1) if K > 0 else 1) * ((N + 127) // 128)
-    rows = 1024
-    while rows > 128 and ((M + rows - 1) // rows) * tiles < 640:
-        rows //= 2
-    return rows
+    best, best_cost = 32, None
+    for rows in range(32, 2049, 32):
+        nslab = (max(M, 1) + rows - 1) // rows
+        rounds = (nslab * tiles + 767) // 768
+        cost = rounds * (rows * 156250 + 20000000) + nslab * (K * N + N) * 2
+        if best_cost is None or cost < best_cost:
+            best, best_cost = rows, cost
+    return best
 
 
 def operand_in_bounds(col, vec, numel, ld, o0, omax, kbeg, kend, inside, origin_of_missing_step=0):
