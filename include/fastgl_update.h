@@ -74,7 +74,7 @@ fastgl_status fastgl_update_bwd_bf16(const uint16_t *H, const uint16_t *W, const
 
 /* Rows of H per dW/db slab for this shape (the length of the longest fp32
  * accumulation chain of the backward pass): a function of M, K, N alone,
- * between 128 and 1024; 0 for negative sizes. */
+ * a multiple of 32 between 32 and 2048; 0 for negative sizes. */
 int32_t fastgl_update_slab_rows(int64_t M, int64_t K, int64_t N);
 
 #ifdef __cplusplus
