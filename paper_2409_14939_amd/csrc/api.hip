@@ -33,8 +33,11 @@ static fastgl_status check_block(const int32_t *indptr, const int32_t *indices, 
                   (long long)num_src, (long long)num_edges);
         return FASTGL_ERR_INVALID_ARG;
     }
-    if (num_dst >= INT32_MAX || num_src >= INT32_MAX || num_edges >= INT32_MAX) {
-        set_error("sizes must stay below 2^31-1 (int32 indices)");
+    // the kernels look a few hundred positions ahead of the last edge / row in 32-bit arithmetic
+    // (column ids two chunks ahead, the end of a long-row chunk), so the sizes keep that distance
+    // from the top of the int32 range
+    if (num_dst > kMaxIndex || num_src > kMaxIndex || num_edges > kMaxIndex) {
+        set_error("sizes must not exceed 2^31-1-%d (int32 indices with look-ahead)", INT32_MAX - kMaxIndex);
         return FASTGL_ERR_UNSUPPORTED;
     }
     if (!indptr) {

@@ -326,8 +326,8 @@ fastgl_status check_csr(const int32_t *indptr, int64_t num_dst, int64_t E)
         set_error("negative size (num_dst=%lld num_edges=%lld)", (long long)num_dst, (long long)E);
         return FASTGL_ERR_INVALID_ARG;
     }
-    if (num_dst >= INT32_MAX || E >= INT32_MAX) {
-        set_error("sizes must stay below 2^31-1 (int32 indices)");
+    if (num_dst > kMaxIndex || E > kMaxIndex) {
+        set_error("sizes must not exceed 2^31-1-1024 (int32 indices with look-ahead)");
         return FASTGL_ERR_UNSUPPORTED;
     }
     if (!indptr || ((uintptr_t)indptr & 3)) {
@@ -606,6 +606,14 @@ fastgl_status fastgl_edge_score_bwd(const int32_t *indptr, const int32_t *indice
         return FASTGL_ERR_INVALID_ARG;
     }
     hipStream_t s = (hipStream_t)stream;
+    if (grad_er && num_src > 0) {   // checked before the first launch: a refused call leaves nothing on the stream
+        const int need = FASTGL_PLAN_BWD | FASTGL_PLAN_PERM;
+        if (!plan || plan->indptr != indptr || plan->indices != indices || plan->num_dst != num_dst ||
+            plan->num_src != num_src || plan->num_edges != num_edges || (plan->parts & need) != need) {
+            set_error("grad_er needs a plan of this block built with FASTGL_PLAN_BWD | FASTGL_PLAN_PERM");
+            return FASTGL_ERR_INVALID_ARG;
+        }
+    }
     if (grad_el && num_dst > 0) {
         if (!el && num_edges == 0) el = grad_el;       // rows without edges read nothing but their own value
         ScoreArgs a = {};
@@ -615,12 +623,6 @@ fastgl_status fastgl_edge_score_bwd(const int32_t *indptr, const int32_t *indice
         FASTGL_LAUNCH_CHECK("fastgl_edge_score_bwd (grad_el)");
     }
     if (grad_er && num_src > 0) {
-        const int need = FASTGL_PLAN_BWD | FASTGL_PLAN_PERM;
-        if (!plan || plan->indptr != indptr || plan->indices != indices || plan->num_dst != num_dst ||
-            plan->num_src != num_src || plan->num_edges != num_edges || (plan->parts & need) != need) {
-            set_error("grad_er needs a plan of this block built with FASTGL_PLAN_BWD | FASTGL_PLAN_PERM");
-            return FASTGL_ERR_INVALID_ARG;
-        }
         if (!er && num_edges == 0) er = grad_er;
         ScoreArgs a = {};
         a.rowptr = plan->indptr_T; a.col = plan->indices_T; a.eid = plan->perm; a.num_rows = num_src;

@@ -16,6 +16,7 @@ constexpr int kWorkPerGroup = 16;      // edges + rows per fine row set (a lane 
 constexpr int kMaxScanBlocks = 1024;   // blocks of a two-kernel scan / compaction
 constexpr int kRadixBits = 8;
 constexpr int kRadixBins = 1 << kRadixBits;
+constexpr int64_t kMaxIndex = INT32_MAX - 1024;   // largest num_dst / num_src / num_edges accepted
 constexpr int kXcds = 8;               // workgroups are dealt round-robin to 8 L2 domains
 
 void set_error(const char *fmt, ...);

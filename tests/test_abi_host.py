@@ -58,6 +58,7 @@ def fwd(indptr=FAKE, indices=FAKE, w=None, nd=4, ns=4, ne=4, feat=8, mode=0, dt=
     (dict(ws=ctypes.c_void_p(0x1010)), B.FASTGL_ERR_INVALID_ARG, "workspace"),
     (dict(wsb=16), B.FASTGL_ERR_WORKSPACE, "too small"),
     (dict(ns=2 ** 31), B.FASTGL_ERR_UNSUPPORTED, "2^31"),
+    (dict(ne=2 ** 31 - 200), B.FASTGL_ERR_UNSUPPORTED, "look-ahead"),      # the kernels read ahead in int32
     (dict(nd=0, ne=3), B.FASTGL_ERR_INVALID_ARG, "at least one"),
 ])
 def test_bad_arguments_are_refused_before_launch(kw, status, text):
@@ -205,4 +206,7 @@ def test_edge_argument_checks():
     assert sb(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, None, None, FAKE, None, None) == B.FASTGL_ERR_INVALID_ARG   # grad_score
     assert sb(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, FAKE, None, None, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
     assert "FASTGL_PLAN_PERM" in B.fastgl_last_error()                                                 # grad_er needs the plan
+    # both gradients asked for, plan missing: refused before the grad_el kernel is enqueued
+    assert sb(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, FAKE, None, FAKE, FAKE, None) == B.FASTGL_ERR_INVALID_ARG
+    assert "FASTGL_PLAN_PERM" in B.fastgl_last_error()
     assert sb(FAKE, FAKE, 4, 4, 4, FAKE, FAKE, 0.2, FAKE, None, None, None, None) == B.FASTGL_OK      # nothing asked for
