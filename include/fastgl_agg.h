@@ -129,6 +129,28 @@ fastgl_status fastgl_block_aggregate_bwd(
     const void *grad_out, void *grad_X,
     const fastgl_plan *plan, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Forward aggregation for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, checks, kernels and results as fastgl_block_aggregate_fwd with plan == NULL; the
+ * scratch (forward bookkeeping of the block + partial sums of long rows) sits in a static device
+ * array of FASTGL_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process
+ * ends.  The call allocates and frees nothing (no hipMalloc, no hipFree, no allocating library
+ * routine).  Work is enqueued on `stream`, which must belong to the CURRENT device (the array of
+ * that device is used); the first call on a device looks up the array's address (a symbol lookup,
+ * no allocation) - make that call once before capturing a graph.
+ * Limit: a block whose scratch need - roughly 12 num_dst + 8 num_src + (num_dst + num_edges) / 4 +
+ * (num_edges / 85) * feat * (8 for f32, 4 for bf16) bytes - exceeds the array is refused with
+ * FASTGL_ERR_WORKSPACE before anything is launched; fastgl_last_error() states both numbers.
+ * All calls on one GPU share that GPU's array and it keeps the last call's contents: calls must
+ * be ordered (one stream, or events); calls that overlap on one GPU race.  Nothing in the array
+ * needs clearing between calls: every value is written by the call before the call reads it. */
+#define FASTGL_STATIC_SCRATCH_BYTES (64u << 20)
+fastgl_status fastgl_block_aggregate_fwd_static(
+    const int32_t *indptr, const int32_t *indices, const float *edge_w,
+    int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+    fastgl_agg_mode mode, fastgl_dtype dtype,
+    const void *X, void *out, void *stream);
+
 /* Bytes of device memory a plan needs (includes sort scratch). */
 size_t fastgl_block_plan_bytes(int64_t num_dst, int64_t num_src, int64_t num_edges);
 

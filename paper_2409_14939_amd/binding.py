@@ -21,7 +21,8 @@ DTYPES = {"f32": 0, "bf16": 1}
 PLAN_FWD, PLAN_BWD, PLAN_ALL, PLAN_SRC_DEG, PLAN_PERM = 1, 2, 3, 4, 8
 
 EXPORTS = [
-    "fastgl_block_aggregate_fwd", "fastgl_block_aggregate_bwd", "fastgl_block_plan_bytes",
+    "fastgl_block_aggregate_fwd", "fastgl_block_aggregate_bwd", "fastgl_block_aggregate_fwd_static",
+    "fastgl_block_plan_bytes",
     "fastgl_block_plan_create", "fastgl_block_plan_create_many", "fastgl_block_plan_export", "fastgl_block_plan_destroy",
     "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk", "fastgl_work_per_group",
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
@@ -68,6 +69,7 @@ def lib() -> ctypes.CDLL:
         agg = [p, p, p, i64, i64, i64, i64, i32, i32, p, p, p, p, sz, p]
         L.fastgl_block_aggregate_fwd.argtypes = agg
         L.fastgl_block_aggregate_bwd.argtypes = agg
+        L.fastgl_block_aggregate_fwd_static.argtypes = [p, p, p, i64, i64, i64, i64, i32, i32, p, p, p]
         L.fastgl_block_plan_bytes.argtypes = [i64, i64, i64]
         L.fastgl_block_plan_bytes.restype = sz
         L.fastgl_block_plan_create.argtypes = [p, p, i64, i64, i64, i32, p, sz, p, ctypes.POINTER(p)]
@@ -251,6 +253,28 @@ def fastgl_block_aggregate_fwd(indptr, indices, edge_w, num_src: int, mode: str,
         raise ValueError("out must be [num_dst, feat]")
     return _aggregate(lib().fastgl_block_aggregate_fwd, indptr, indices, edge_w, num_src, mode, X, out,
                       plan, workspace)
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def fastgl_block_aggregate_fwd_static(indptr, indices, edge_w, num_src: int, mode: str, X: torch.Tensor,
+                                      out: torch.Tensor) -> torch.Tensor:
+    """The forward aggregation on the library's static scratch array: no plan, no workspace, and this
+    wrapper allocates nothing either (the caller passes `out`)."""
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    if edge_w is not None:
+        _dev(edge_w, torch.float32, "edge_w")
+    dt = _feat_dtype(X)
+    _dev(X, X.dtype, "X")
+    _dev(out, X.dtype, "out")
+    num_dst, num_edges, feat = indptr.numel() - 1, indices.numel(), X.shape[1]
+    if X.shape[0] != num_src or out.shape != (num_dst, feat):
+        raise ValueError("X must be [num_src, feat] and out [num_dst, feat]")
+    _check(lib().fastgl_block_aggregate_fwd_static(_ptr(indptr), _ptr(indices), _ptr(edge_w), num_dst, num_src,
+                                                   num_edges, feat, MODES[mode], dt, _ptr(X), _ptr(out), _stream()))
+    return out
 
 
 def fastgl_block_aggregate_bwd(indptr, indices, edge_w, num_src: int, mode: str, grad_out: torch.Tensor,

@@ -7,7 +7,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libfastgl_agg.so")
-SOURCES = ["api.hip", "bookkeeping.hip", "aggregate.hip", "update.hip", "idmap.hip", "match.hip", "edge.hip"]
+SOURCES = ["api.hip", "bookkeeping.hip", "aggregate.hip", "update.hip", "idmap.hip", "match.hip", "edge.hip",
+           "static_scratch.hip"]
 
 
 def build_library(verbose: bool = False) -> str:

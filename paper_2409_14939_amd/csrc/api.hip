@@ -64,11 +64,12 @@ static size_t partial_bytes(int64_t num_edges, int64_t feat, fastgl_dtype dtype)
     return align_up((size_t)cap_chunks(num_edges) * (size_t)feat * (dtype == FASTGL_F32 ? 8 : 4), 256);
 }
 
-static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32_t *indices,
-                               const float *edge_w, int64_t num_dst, int64_t num_src, int64_t num_edges,
-                               int64_t feat, fastgl_agg_mode mode, fastgl_dtype dtype, const void *in,
-                               void *out, const fastgl_plan *plan, void *workspace, size_t workspace_bytes,
-                               void *stream)
+// Host-side checks of a forward / backward call; nothing is launched.  *need = bytes of workspace the
+// call takes (partial sums of long rows, plus the bookkeeping when no plan is passed).
+fastgl_status aggregate_check(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                              int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                              fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                              const fastgl_plan *plan, size_t *need)
 {
     fastgl_status st = check_block(indptr, indices, num_dst, num_src, num_edges);
     if (st != FASTGL_OK) return st;
@@ -98,16 +99,9 @@ static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32
         set_error("feat too large (%lld)", (long long)feat);
         return FASTGL_ERR_UNSUPPORTED;
     }
-    if (!workspace || ((uintptr_t)workspace & 255)) {
-        set_error("workspace must be a 256-byte aligned device buffer");
-        return FASTGL_ERR_INVALID_ARG;
-    }
-    const size_t pbytes = partial_bytes(num_edges, feat, dtype);
-    const int need_parts = backward ? (FASTGL_PLAN_ALL | (edge_w ? FASTGL_PLAN_PERM : 0)) : FASTGL_PLAN_FWD;
-    hipStream_t s = (hipStream_t)stream;
-    fastgl_plan local;
-    const fastgl_plan *pl = plan;
+    *need = partial_bytes(num_edges, feat, dtype);
     if (plan) {
+        const int need_parts = backward ? (FASTGL_PLAN_ALL | (edge_w ? FASTGL_PLAN_PERM : 0)) : FASTGL_PLAN_FWD;
         if (plan->indptr != indptr || plan->indices != indices || plan->num_dst != num_dst ||
             plan->num_src != num_src || plan->num_edges != num_edges) {
             set_error("plan was built for a different block");
@@ -117,26 +111,35 @@ static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32
             set_error("plan lacks the parts this pass needs (has %d, needs %d)", plan->parts, need_parts);
             return FASTGL_ERR_INVALID_ARG;
         }
-        if (workspace_bytes < pbytes) {
-            set_error("workspace too small: %zu < %zu bytes", workspace_bytes, pbytes);
-            return FASTGL_ERR_WORKSPACE;
+        if (mode == FASTGL_AGG_GCN && !backward && !(plan->parts & (FASTGL_PLAN_BWD | FASTGL_PLAN_SRC_DEG))) {
+            set_error("GCN forward needs a plan with source degrees (FASTGL_PLAN_SRC_DEG or FASTGL_PLAN_BWD)");
+            return FASTGL_ERR_INVALID_ARG;
         }
     } else {
-        const size_t plan_b = plan_layout(nullptr, nullptr, num_dst, num_src, num_edges);
-        if (workspace_bytes < pbytes + plan_b) {
-            set_error("workspace too small: %zu < %zu bytes", workspace_bytes, pbytes + plan_b);
-            return FASTGL_ERR_WORKSPACE;
-        }
+        // a forward pass needs no transpose: its bookkeeping takes a fraction of a whole plan's room
+        *need += plan_layout(nullptr, nullptr, num_dst, num_src, num_edges, !backward);
+    }
+    return FASTGL_OK;
+}
+
+// The launches of a call that passed aggregate_check; workspace holds at least the bytes it asked for.
+fastgl_status aggregate_run(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                            int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                            fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                            const fastgl_plan *plan, void *workspace, void *stream)
+{
+    hipStream_t s = (hipStream_t)stream;
+    fastgl_plan local;
+    const fastgl_plan *pl = plan;
+    if (!plan) {
+        const int need_parts = backward ? (FASTGL_PLAN_ALL | (edge_w ? FASTGL_PLAN_PERM : 0)) : FASTGL_PLAN_FWD;
         local.num_dst = num_dst; local.num_src = num_src; local.num_edges = num_edges;
         local.indptr = indptr; local.indices = indices;
-        plan_layout(&local, (char *)workspace + pbytes, num_dst, num_src, num_edges);
-        st = plan_build(&local, need_parts, mode == FASTGL_AGG_GCN, s);
+        plan_layout(&local, (char *)workspace + partial_bytes(num_edges, feat, dtype), num_dst, num_src, num_edges,
+                    !backward);
+        fastgl_status st = plan_build(&local, need_parts, mode == FASTGL_AGG_GCN, s);
         if (st != FASTGL_OK) return st;
         pl = &local;
-    }
-    if (mode == FASTGL_AGG_GCN && !backward && !(pl->parts & (FASTGL_PLAN_BWD | FASTGL_PLAN_SRC_DEG)) && plan) {
-        set_error("GCN forward needs a plan with source degrees (FASTGL_PLAN_SRC_DEG or FASTGL_PLAN_BWD)");
-        return FASTGL_ERR_INVALID_ARG;
     }
 
     PullDesc d;
@@ -165,6 +168,27 @@ static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32
         d.split = pl->split_src; d.nsets = num_row_sets(num_src, num_edges);
     }
     return launch_pull(d, s);
+}
+
+static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                               int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                               fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                               const fastgl_plan *plan, void *workspace, size_t workspace_bytes, void *stream)
+{
+    size_t need = 0;
+    fastgl_status st = aggregate_check(backward, indptr, indices, edge_w, num_dst, num_src, num_edges, feat, mode,
+                                       dtype, in, out, plan, &need);
+    if (st != FASTGL_OK) return st;
+    if (!workspace || ((uintptr_t)workspace & 255)) {
+        set_error("workspace must be a 256-byte aligned device buffer");
+        return FASTGL_ERR_INVALID_ARG;
+    }
+    if (workspace_bytes < need) {
+        set_error("workspace too small: %zu < %zu bytes", workspace_bytes, need);
+        return FASTGL_ERR_WORKSPACE;
+    }
+    return aggregate_run(backward, indptr, indices, edge_w, num_dst, num_src, num_edges, feat, mode, dtype, in, out,
+                         plan, workspace, stream);
 }
 
 }  // namespace fastgl

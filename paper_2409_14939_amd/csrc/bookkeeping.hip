@@ -495,7 +495,8 @@ static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, fl
     return A;
 }
 
-size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges)
+size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges,
+                   bool fwd_only)
 {
     size_t off = 0;
     char *b = (char *)base;
@@ -504,29 +505,31 @@ size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src,
         off += align_up(bytes ? bytes : 4, 256);
         return (void *)q;
     };
+    // arrays that only the transpose (a backward plan) needs take no room in a forward-only layout
+    auto take_bwd = [&](size_t bytes) { return fwd_only ? nullptr : take(bytes); };
     const int64_t cl = cap_long_rows(num_edges);
     fastgl_plan tmp;
     fastgl_plan *q = p ? p : &tmp;
     q->din = (int32_t *)take(4 * (size_t)num_dst);
     q->dout = (int32_t *)take(4 * (size_t)num_src);
-    q->indptr_T = (int32_t *)take(4 * ((size_t)num_src + 1));
-    q->indices_T = (int32_t *)take(4 * (size_t)num_edges);
-    q->perm = (int32_t *)take(4 * (size_t)num_edges);
+    q->indptr_T = (int32_t *)take_bwd(4 * ((size_t)num_src + 1));
+    q->indices_T = (int32_t *)take_bwd(4 * (size_t)num_edges);
+    q->perm = (int32_t *)take_bwd(4 * (size_t)num_edges);
     q->dst_inv = (float *)take(4 * (size_t)num_dst);
     q->dst_rsqrt = (float *)take(4 * (size_t)num_dst);
     q->src_rsqrt = (float *)take(4 * (size_t)num_src);
     q->long_dst = (int32_t *)take(4 * (size_t)cl);
     q->chunk_ptr_dst = (int32_t *)take(4 * ((size_t)cl + 1));
-    q->long_src = (int32_t *)take(4 * (size_t)cl);
-    q->chunk_ptr_src = (int32_t *)take(4 * ((size_t)cl + 1));
+    q->long_src = (int32_t *)take_bwd(4 * (size_t)cl);
+    q->chunk_ptr_src = (int32_t *)take_bwd(4 * ((size_t)cl + 1));
     q->split_dst = (int32_t *)take(4 * ((size_t)num_row_sets(num_dst, num_edges) + 1));
-    q->split_src = (int32_t *)take(4 * ((size_t)num_row_sets(num_src, num_edges) + 1));
+    q->split_src = (int32_t *)take_bwd(4 * ((size_t)num_row_sets(num_src, num_edges) + 1));
     q->counters = (int32_t *)take(4 * 4);
-    for (int i = 0; i < 6; ++i) q->sort_buf[i] = (int32_t *)take(4 * (size_t)num_edges);
-    q->edge_dst = (int32_t *)take(4 * (size_t)num_edges);
-    q->radix_cnt = (int32_t *)take(4 * (size_t)kRadixBins * kMaxSortBlocks);
+    for (int i = 0; i < 6; ++i) q->sort_buf[i] = (int32_t *)take_bwd(4 * (size_t)num_edges);
+    q->edge_dst = (int32_t *)take_bwd(4 * (size_t)num_edges);
+    q->radix_cnt = (int32_t *)take_bwd(4 * (size_t)kRadixBins * kMaxSortBlocks);
     q->block_sums = (int32_t *)take(4 * 2 * (size_t)kMaxScanBlocks);
-    q->block_sums2 = (int32_t *)take(4 * 2 * (size_t)kMaxScanBlocks);
+    q->block_sums2 = (int32_t *)take_bwd(4 * 2 * (size_t)kMaxScanBlocks);
     return off;
 }
 

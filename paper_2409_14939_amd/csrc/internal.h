@@ -64,7 +64,11 @@ struct fastgl_plan {
 
 namespace fastgl {
 
-size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges);
+// Carves a plan's arrays out of `base` (NULL: only the size is wanted).  fwd_only: room for what a
+// forward pass without a caller's plan needs (degrees, scale factors, destination-side buckets and
+// row sets); every transpose-side pointer is NULL then.
+size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges,
+                   bool fwd_only = false);
 fastgl_status plan_build(fastgl_plan *p, int parts, bool need_src_degrees, hipStream_t s);
 fastgl_status plans_build(fastgl_plan *const *plans, const int *parts, const bool *src_deg, int n, hipStream_t s);
 
@@ -91,6 +95,18 @@ struct PullDesc {
 };
 
 fastgl_status launch_pull(const PullDesc &d, hipStream_t s);
+
+// The two halves of fastgl_block_aggregate_fwd / _bwd.  aggregate_check: every host-side check, no
+// HIP call; *need = workspace bytes the call takes.  aggregate_run: bookkeeping (when plan is NULL)
+// and the aggregation launches, for a call that passed the check, on a workspace of >= *need bytes.
+fastgl_status aggregate_check(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                              int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                              fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                              const fastgl_plan *plan, size_t *need);
+fastgl_status aggregate_run(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                            int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                            fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                            const fastgl_plan *plan, void *workspace, void *stream);
 fastgl_status launch_gather_rows(const void *table, const int64_t *ids, int64_t n, int64_t feat,
                                  fastgl_dtype dtype, void *out, hipStream_t s);
 fastgl_status validate_block(const int32_t *indptr, const int32_t *indices, int64_t num_dst,

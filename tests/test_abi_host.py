@@ -66,6 +66,21 @@ def test_bad_arguments_are_refused_before_launch(kw, status, text):
     assert text in B.fastgl_last_error()
 
 
+def test_static_scratch_entry_point_checks_on_the_host():
+    f = B.lib().fastgl_block_aggregate_fwd_static
+
+    def call(indptr=FAKE, indices=FAKE, w=None, nd=4, ns=4, ne=4, feat=8, mode=0, dt=0, X=FAKE, out=FAKE):
+        return f(indptr, indices, w, nd, ns, ne, feat, mode, dt, X, out, None)
+    assert call(nd=-1) == B.FASTGL_ERR_INVALID_ARG and "negative" in B.fastgl_last_error()
+    assert call(feat=0) == B.FASTGL_ERR_INVALID_ARG
+    assert call(X=None) == B.FASTGL_ERR_INVALID_ARG
+    assert call(mode=7) == B.FASTGL_ERR_INVALID_ARG
+    # sizes beyond the array: refused with both numbers in the text, before any HIP call
+    assert call(nd=6_000_000, ns=1, ne=0) == B.FASTGL_ERR_WORKSPACE
+    assert "static scratch" in B.fastgl_last_error() and str(B.STATIC_SCRATCH_BYTES) in B.fastgl_last_error()
+    assert call(nd=1000, ns=1000, ne=90_000_000, feat=256) == B.FASTGL_ERR_WORKSPACE
+
+
 def test_plan_and_gather_argument_checks():
     L = B.lib()
     out = ctypes.c_void_p()
