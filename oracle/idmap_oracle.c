@@ -83,39 +83,42 @@ int64_t fastgl_oracle_idmap(const int64_t *dst_gid, int64_t n_dst, const int64_t
     return status;
 }
 
-/* Algorithm 2, one thread.  key[] / value[] have table_size entries and are
- * initialised here (-1 / 0).  local[i] receives the local ID of ids[i], read
- * back from the table after all insertions (the paper's second kernel).
- * Returns LocalID (the number of distinct IDs), or -1 if the table is full. */
+/* Where `id` sits in an open-addressing table with linear probing that wraps
+ * past the last slot (Section 4.3): the first slot, starting at id mod
+ * table_size (the hash of the paper's worked example), that holds `id` or is
+ * still empty (-1).  Returns -1 when every slot holds another ID. */
+static int64_t find_slot(const int64_t *key, int64_t table_size, int64_t id)
+{
+    int64_t s = id % table_size;
+    if (s < 0) s += table_size;
+    for (int64_t tried = 0; tried < table_size; ++tried) {
+        if (key[s] == id || key[s] == -1) return s;
+        s = (s + 1) % table_size;
+    }
+    return -1;
+}
+
+/* The Fused-Map of Section 4.3 (Algorithm 2) as ONE thread runs it: IDs are
+ * inserted in input order; an ID that was not in the table yet claims its slot
+ * and is numbered with the running count of distinct IDs; afterwards every ID
+ * is looked up again to read its number.  With one thread the compare-and-swap
+ * of the parallel version is just "write the ID if the slot is empty".
+ * key[] / value[] have table_size entries and are initialised here (-1 / 0).
+ * Returns the number of distinct IDs, or -1 if the table is full. */
 int64_t fastgl_oracle_fused_map_seq(const int64_t *ids, int64_t n, int64_t table_size, int64_t *key,
                                     int64_t *value, int64_t *local)
 {
     if (n < 0 || table_size <= 0) return -1;
     for (int64_t s = 0; s < table_size; ++s) { key[s] = -1; value[s] = 0; }
-    int64_t LocalID = 0;
+    int64_t distinct = 0;
     for (int64_t i = 0; i < n; ++i) {
-        const int64_t GlobalID = ids[i];
-        int64_t HashIndex = GlobalID % table_size;          /* HashFunction of the paper's example */
-        if (HashIndex < 0) HashIndex += table_size;
-        int Flag = 0;
-        int64_t probes = 0;
-        for (;;) {                                          /* InsertID */
-            const int64_t Val = key[HashIndex];             /* atomicCAS(HashIndex, -1, GlobalID) ... */
-            if (Val == -1) key[HashIndex] = GlobalID;       /* ... in one thread */
-            if (Val == GlobalID || Val == -1) { Flag = (Val != -1); break; }
-            HashIndex = HashIndex + 1 == table_size ? 0 : HashIndex + 1;    /* linear probing, wrapping */
-            if (++probes >= table_size) return -1;
-        }
-        if (!Flag) {                                        /* a new node: it takes the current LocalID */
-            value[HashIndex] = LocalID;
-            LocalID += 1;
+        const int64_t s = find_slot(key, table_size, ids[i]);
+        if (s < 0) return -1;
+        if (key[s] == -1) {                 /* first time this ID is seen */
+            key[s] = ids[i];
+            value[s] = distinct++;
         }
     }
-    for (int64_t i = 0; i < n; ++i) {                       /* transform global IDs to local IDs */
-        int64_t HashIndex = ids[i] % table_size;
-        if (HashIndex < 0) HashIndex += table_size;
-        while (key[HashIndex] != ids[i]) HashIndex = HashIndex + 1 == table_size ? 0 : HashIndex + 1;
-        local[i] = value[HashIndex];
-    }
-    return LocalID;
+    for (int64_t i = 0; i < n; ++i) local[i] = value[find_slot(key, table_size, ids[i])];
+    return distinct;
 }

@@ -299,38 +299,83 @@ def test_config5_skew_stress():
     check_block(blk, w.mode, w.dtype, 256, False, True, w.seed, w.name)
 
 
-def test_config4_papers_shaped_table_gather():
-    """bf16 feature table of the full 111M x 128 shape lives on the device; the
-    sampled source rows are gathered by global id, then aggregated layer by layer."""
-    w = bg.make_config(4)
-    n, feat = w.table_rows, w.widths[0]
-    print(f"filling {n} x {feat} bf16 table", flush=True)
-    table = torch.empty((n, feat), dtype=torch.bfloat16, device="cuda")
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(w.seed)
-    step = 8_000_000
+# ---- closed-form feature tables: any row can be recomputed on the host ---------------------
+# Element (row, col) of a table is a bit pattern that is a function of (row, col) in plain integer
+# arithmetic (below 2^63, so torch's and numpy's int64 agree): sign, an exponent within 2^-7..2^7,
+# mantissa bits from a multiplicative mix.  The device fills the whole table from arange; the host
+# evaluates the same formula for the rows it needs and hands THEM to the oracle.
+def pattern_bits(rows, cols, dtype, xp):
+    h = rows * 2654435761 + cols * 2246822519 + (rows >> 9) * 40503
+    h = h ^ (h >> 15)
+    sign, expo = (h >> 3) & 1, 120 + (h >> 5) % 15
+    if dtype == "bf16":
+        return (sign << 15) | (expo << 7) | ((h >> 11) & 0x7F)
+    return (sign << 31) | (expo << 23) | ((h >> 11) & 0x7FFFFF)
+
+
+def fill_table(n, feat, dtype):
+    tdt, idt = (torch.bfloat16, torch.int16) if dtype == "bf16" else (torch.float32, torch.int32)
+    table = torch.empty((n, feat), dtype=tdt, device="cuda")
+    cols = torch.arange(feat, device="cuda", dtype=torch.int64).view(1, -1)
+    step = 4_000_000
     for lo in range(0, n, step):
         hi = min(n, lo + step)
-        table[lo:hi] = torch.randn((hi - lo, feat), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-    gid = torch.from_numpy(w.src_gid).cuda()
-    X0 = B.fastgl_gather_rows(table, gid)
+        rows = torch.arange(lo, hi, device="cuda", dtype=torch.int64).view(-1, 1)
+        bits = pattern_bits(rows, cols, dtype, torch)
+        # int64 -> the signed type of the element's width keeps the low bits
+        table[lo:hi] = (bits.to(torch.int16) if dtype == "bf16" else bits.to(torch.int32)).view(tdt)
+    return table
+
+
+def host_rows(row_ids, feat, dtype):
+    rows = np.asarray(row_ids, np.int64).reshape(-1, 1)
+    bits = pattern_bits(rows, np.arange(feat, dtype=np.int64).reshape(1, -1), dtype, np)
+    return bits.astype(np.uint16) if dtype == "bf16" else bits.astype(np.uint32).view(np.float32)
+
+
+def check_table_gather(table, gid_host, feat, dtype, what):
+    """fastgl_gather_rows on the full table against oracle.gather_rows on the compact host table of
+    the referenced rows (ids remapped), bit for bit; torch's index_select as a second opinion."""
+    print(f"gather {what}: {gid_host.size} rows of {feat} x {dtype} from a table of {table.shape[0]} rows "
+          f"({table.numel() * table.element_size() / 2**30:.1f} GiB)", flush=True)
+    gid = torch.from_numpy(gid_host).cuda()
+    got = B.fastgl_gather_rows(table, gid)
     torch.cuda.synchronize()
-    ref_rows = table.index_select(0, gid)          # library path, independent of the kernel under test
-    assert torch.equal(X0.view(torch.int16), ref_rows.view(torch.int16))
-    X0_host = host_feat(X0, "bf16")
+    uniq, inv = np.unique(gid_host, return_inverse=True)
+    ref = oracle.gather_rows(host_rows(uniq, feat, dtype), inv.astype(np.int64), dtype)
+    got_host = host_feat(got, dtype)
+    assert np.array_equal(got_host.view(np.uint16 if dtype == "bf16" else np.uint32),
+                          ref.view(np.uint16 if dtype == "bf16" else np.uint32)), what
+    idt = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(got.view(idt), table.index_select(0, gid).view(idt))
+    return got, ref
+
+
+def test_gather_rows_f32_table_beyond_4_gib():
+    """f32 rows of 400 bytes: byte offsets pass 2^32 from row 10.7 M on."""
+    n, feat = 12_000_000, 100
+    table = fill_table(n, feat, "f32")
+    rng = np.random.default_rng(41)
+    gid = np.concatenate([rng.integers(0, n, size=200_000), [0, n - 1, (1 << 32) // 400, (1 << 32) // 400 + 1],
+                          rng.integers(n - 1_000_000, n, size=50_000)]).astype(np.int64)
+    check_table_gather(table, gid, feat, "f32", "f32 table > 4 GiB")
+
+
+def test_config4_papers_shaped_table_gather():
+    """bf16 feature table of the full 111M x 128 shape lives on the device (28 GB: byte offsets far
+    beyond 2^32); the sampled source rows are gathered by global id and checked against the oracle's
+    gather, then aggregated layer by layer."""
+    w = bg.make_config(4)
+    n, feat = w.table_rows, w.widths[0]
+    table = fill_table(n, feat, "bf16")
+    assert int(w.src_gid.max()) * feat * 2 > 2 ** 32
+    X0, X0_ref = check_table_gather(table, w.src_gid, feat, "bf16", "config 4 source rows")
     del table
     blk = w.blocks[0]
-    rng = np.random.default_rng(w.seed)
     ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
     out = B.fastgl_block_aggregate_fwd(ip, ix, None, blk.num_src, w.mode, X0)
     torch.cuda.synchronize()
     assert_close(host_feat(out, "bf16"),
-                 oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, "bf16", X0_host),
-                 "bf16", "config4 layer 0 fwd from gathered table rows")
-    G = make_inputs(rng, blk.num_dst, feat, "bf16")
-    dX = B.fastgl_block_aggregate_bwd(ip, ix, None, blk.num_src, w.mode, dev_feat(G, "bf16"))
-    torch.cuda.synchronize()
-    assert_close(host_feat(dX, "bf16"),
-                 oracle.aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, "bf16", G),
-                 "bf16", "config4 layer 0 bwd")
-    check_workload(w, layers=[1, 2])
+                 oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, "bf16", X0_ref),
+                 "bf16", "config4 layer 0 fwd: GPU gather + aggregation against oracle gather + aggregation")
+    check_workload(w)          # every layer with N(0,1) features, bookkeeping included
