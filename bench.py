@@ -6,11 +6,19 @@ mini-batch's blocks, run the forward aggregation of every layer, then the
 backward aggregation of every layer in reverse order.  All inputs are synthetic, seeded
 and already resident in HBM when the timed region starts.
 
+Timing: every step is bracketed by a pair of HIP events on the launch stream; `ms_per_step` is
+the median of the timed steps (>= 50 by default), `ms_per_step_wall` the wall-clock mean of the
+same steps between two device synchronisations.  Repetitions are cache-cold: a workload whose
+buffers (features, outputs, gradients) take less than 512 MB (twice the 256 MB Infinity Cache)
+rotates over up to 8 independent copies of them, and if that is still less it runs an untimed
+512 MB fill between the steps.
+
 Prints ONE JSON line:
   value     aggregated GEdges/s = 2 * sum(E_layer) / step time (plan build included)
   roofline  achieved HBM GB/s of the dominant kernel from compulsory bytes
             (indptr + indices + unique source rows + output) against 8 TB/s
   cpu_baseline  the CPU oracle's parallel variant timed on the host cores
+  other_configs  the same measurement, shorter, for the other four workloads
 """
 from __future__ import annotations
 
@@ -27,12 +35,28 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 METRIC = "aggregated GEdges/s (fwd+bwd) and achieved HBM GB/s vs peak, 1 MI355X"
 
-# HBM-side bytes per launch of the dominant kernel, from two rocprofv3 --pmc runs
-# of this file (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter
-# reads for a plain 1 GiB copy (`--calibrate`): FETCH_SIZE counts 2 KiB units,
-# WRITE_SIZE 1 KiB units on this stack.  Summary: profiles/pull_rows_config2_traffic.md.
-# Key: (config, direction, layer).  Re-measure when the kernel's access pattern changes.
-MEASURED_TRAFFIC_BYTES = {(2, "fwd", 0): int(632334.8 * 2048 + 208647.1 * 1024)}
+# HBM-side bytes per launch are not measured in this run (byte counters need rocprofv3): they are
+# read from a tracked table of earlier rocprofv3 --pmc runs of this file (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the same counter reads for a plain 1 GiB copy, `--calibrate`).
+# A launch without an entry reports null.  Re-measure when a kernel's access pattern changes.
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "traffic_counters.txt")
+FETCH_UNIT, WRITE_UNIT = 2048, 1024     # bytes per count of FETCH_SIZE / WRITE_SIZE on this stack
+
+
+def load_traffic_table():
+    """Lines: config width layer direction FETCH_SIZE WRITE_SIZE (counter means per dispatch)."""
+    table = {}
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                line = line.split("#", 1)[0].split()
+                if len(line) == 6:
+                    cfg, width, layer, direction, fetch, write = line
+                    table[(int(cfg), int(width), int(layer), direction)] = int(float(fetch) * FETCH_UNIT +
+                                                                               float(write) * WRITE_UNIT)
+    except OSError:
+        pass
+    return table
 
 
 def compulsory_bytes(rowptr_rows, nnz, used_in_rows, out_rows, feat, elem):
@@ -441,10 +465,279 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=
     }
 
 
+def measure_copy_gbps(torch):
+    """Plain device copy of 1 GiB (read + write), the practical streaming ceiling of this GPU."""
+    src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(7)]
+    for a, b in ev:
+        a.record()
+        dst.copy_(src)
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in ev)[len(ev) // 2]
+    return 2.0 * src.numel() * 4 / (ms * 1e-3) / 1e9
+
+
+class Workload:
+    """Device buffers of one configuration: index arrays, plan memory, and `nsets` independent
+    copies of (X, G, out, dX) per layer that the timed loops rotate over."""
+
+    def __init__(self, cfg, width, fanout_order, B, bg, torch, np, max_sets=8):
+        self.cfg, self.width = cfg, width
+        t0 = time.time()
+        self.w = w = bg.make_config(cfg, fanout_order=fanout_order, width=width)
+        self.gen_s = time.time() - t0
+        dev = torch.device("cuda:0")
+        self.tdt = tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+        self.elem = elem = 4 if w.dtype == "f32" else 2
+        foot = sum((2 * b.num_src + 2 * b.num_dst) * f * elem for b, f in zip(w.blocks, w.widths))
+        self.footprint = foot
+        self.nsets = nsets = max(1, min(max_sets, -(-(512 << 20) // foot)))
+        self.flush = torch.empty(512 << 20, dtype=torch.uint8, device=dev) if nsets * foot < (512 << 20) else None
+        g = torch.Generator(device="cuda")
+        g.manual_seed(w.seed)
+        self.layers, ws_bytes = [], 0
+        for blk, feat in zip(w.blocks, w.widths):
+            L = dict(blk=blk, feat=feat)
+            L["indptr"] = torch.from_numpy(blk.indptr).to(dev)
+            L["indices"] = torch.from_numpy(blk.indices).to(dev)
+            L["Xs"] = [torch.randn((blk.num_src, feat), generator=g, device=dev, dtype=torch.float32).to(tdt)
+                       for _ in range(nsets)]
+            L["Gs"] = [torch.randn((blk.num_dst, feat), generator=g, device=dev, dtype=torch.float32).to(tdt)
+                       for _ in range(nsets)]
+            L["outs"] = [torch.empty((blk.num_dst, feat), device=dev, dtype=tdt) for _ in range(nsets)]
+            L["dXs"] = [torch.empty((blk.num_src, feat), device=dev, dtype=tdt) for _ in range(nsets)]
+            L["X"], L["G"], L["out"], L["dX"] = L["Xs"][0], L["Gs"][0], L["outs"][0], L["dXs"][0]
+            L["plan_mem"] = torch.empty(B.fastgl_block_plan_bytes(blk.num_dst, blk.num_src, blk.num_edges),
+                                        dtype=torch.uint8, device=dev)
+            ws_bytes = max(ws_bytes, B.fastgl_block_workspace_bytes(blk.num_dst, blk.num_src, blk.num_edges,
+                                                                    feat, w.dtype))
+            din = np.diff(blk.indptr)
+            dout = np.bincount(blk.indices, minlength=blk.num_src)
+            L["bytes_fwd"] = compulsory_bytes(blk.num_dst, blk.num_edges, int((dout > 0).sum()), blk.num_dst, feat, elem)
+            L["bytes_bwd"] = compulsory_bytes(blk.num_src, blk.num_edges, int((din > 0).sum()), blk.num_src, feat, elem)
+            # L2-level demand: every gathered row + every output row (indices apart)
+            L["gathered_fwd"] = (blk.num_edges + blk.num_dst) * feat * elem
+            L["gathered_bwd"] = (blk.num_edges + blk.num_src) * feat * elem
+            self.layers.append(L)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.table = self.gid = None
+        self.gather_bytes = 0
+        if w.src_gid is not None:
+            # config 4: the raw features sit in a device-resident table and are gathered by global id
+            feat0 = w.widths[0]
+            self.table = torch.empty((w.table_rows, feat0), dtype=tdt, device=dev)
+            for lo in range(0, w.table_rows, 8_000_000):
+                hi = min(w.table_rows, lo + 8_000_000)
+                self.table[lo:hi] = torch.randn((hi - lo, feat0), generator=g, device=dev, dtype=torch.float32).to(tdt)
+            self.gid = torch.from_numpy(w.src_gid).to(dev)
+            self.gather_bytes = 8 * self.gid.numel() + 2 * self.gid.numel() * feat0 * elem
+        self.total_edges = w.total_edges()
+        self.bytes_step = sum(L["bytes_fwd"] + L["bytes_bwd"] for L in self.layers) + self.gather_bytes
+        self.gathered_step = sum(L["gathered_fwd"] + L["gathered_bwd"] for L in self.layers) + self.gather_bytes
+        self.B, self.torch = B, torch
+
+    def make_plans(self):
+        """Bookkeeping of every block of the mini-batch (transpose CSR, degrees, scale
+        factors, degree buckets), built together: each stage is one launch for all layers."""
+        B = self.B
+        # sampled blocks (configs 1-4): the fan-out bounds every destination row far below the long-row
+        # threshold, which the sampler knows and passes on as a hint; config 5 takes all neighbours
+        parts = B.PLAN_ALL | (B.PLAN_SHORT_DST_ROWS if self.cfg != 5 else 0)
+        return B.fastgl_block_plan_create_many([(L["indptr"], L["indices"], L["blk"].num_src) for L in self.layers],
+                                               parts, [L["plan_mem"] for L in self.layers])
+
+    def fwd(self, L, plan, k=0):
+        self.B.fastgl_block_aggregate_fwd(L["indptr"], L["indices"], None, L["blk"].num_src, self.w.mode, L["Xs"][k],
+                                          out=L["outs"][k], plan=plan, workspace=self.workspace)
+
+    def bwd(self, L, plan, k=0):
+        self.B.fastgl_block_aggregate_bwd(L["indptr"], L["indices"], None, L["blk"].num_src, self.w.mode, L["Gs"][k],
+                                          grad_X=L["dXs"][k], plan=plan, workspace=self.workspace)
+
+    def cold(self):
+        """Between timed repetitions of a workload too small to rotate out of the cache."""
+        if self.flush is not None:
+            self.flush.fill_(1)
+
+
+def median_ms(pairs):
+    t = sorted(a.elapsed_time(b) for a, b in pairs)
+    return float(t[len(t) // 2])
+
+
+def headline(W, steps, warmup, np, traffic_table, copy_gbps, per_layer_reps):
+    """Timed steps of one workload (plans + forward + backward of all layers) and its breakdown."""
+    torch, layers, w = W.torch, W.layers, W.w
+    dom = max(range(len(layers)), key=lambda i: layers[i]["bytes_fwd"])
+    dom_ev, step_ev = [], []
+
+    def step(i, timed=False):
+        k = i % W.nsets
+        if timed:
+            W.cold()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        if W.table is not None:
+            W.B.fastgl_gather_rows(W.table, W.gid, out=layers[0]["Xs"][k])
+        plans = W.make_plans()
+        for j, L in enumerate(layers):
+            if timed and j == dom:
+                d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                d0.record()
+                W.fwd(L, plans[j], k)
+                d1.record()
+                dom_ev.append((d0, d1))
+            else:
+                W.fwd(L, plans[j], k)
+        for L, p in zip(reversed(layers), reversed(plans)):
+            W.bwd(L, p, k)
+        if timed:
+            e1.record()
+            step_ev.append((e0, e1))
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i, timed=True)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms_step = median_ms(step_ev)
+    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in dom_ev]))
+
+    # breakdown (not part of the headline): plan / forward / backward, every layer and pass
+    def timed(fn, reps):
+        ev = []
+        for i in range(reps):
+            W.cold()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn(i % W.nsets)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        return median_ms(ev)
+
+    reps = per_layer_reps
+    plans = W.make_plans()
+    plan_ms = timed(lambda k: W.make_plans(), reps)
+    fwd_ms = timed(lambda k: [W.fwd(L, p, k) for L, p in zip(layers, plans)], reps)
+    bwd_ms = timed(lambda k: [W.bwd(L, p, k) for L, p in zip(reversed(layers), reversed(plans))], reps)
+    per_layer = []
+    for i, (L, p) in enumerate(zip(layers, plans)):
+        f = timed(lambda k: W.fwd(L, p, k), reps)
+        b = timed(lambda k: W.bwd(L, p, k), reps)
+        rec = dict(layer=i, num_dst=L["blk"].num_dst, num_src=L["blk"].num_src, E=L["blk"].num_edges, feat=L["feat"])
+        for name, ms, byt, gat in (("fwd", f, L["bytes_fwd"], L["gathered_fwd"]), ("bwd", b, L["bytes_bwd"], L["gathered_bwd"])):
+            gbps = byt / ms / 1e6
+            rec[name] = {"ms": round(ms, 4), "compulsory_bytes": int(byt), "gbps_compulsory": round(gbps, 1),
+                         "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                         "frac_of_copy_bw": round(gbps / copy_gbps, 4),
+                         "gbps_gathered": round(gat / ms / 1e6, 1),
+                         "traffic_bytes": traffic_table.get((W.cfg, L["feat"], i, name))}
+        per_layer.append(rec)
+    gather_ms = None
+    if W.table is not None:
+        gather_ms = timed(lambda k: W.B.fastgl_gather_rows(W.table, W.gid, out=layers[0]["Xs"][k]), reps)
+
+    value = 2.0 * W.total_edges / (ms_step * 1e-3) / 1e9
+    domL = layers[dom]
+    achieved = domL["bytes_fwd"] / (dom_ms * 1e-3) / 1e9
+    gbps_step = W.bytes_step / (ms_step * 1e-3) / 1e9
+    cached = fwd_ms + bwd_ms + (gather_ms or 0.0)
+    res = {
+        "value": round(value, 4),
+        "ms_per_step": round(ms_step, 4),
+        "ms_per_step_wall": round(wall_ms, 4),
+        "timing": f"median of {steps} steps, each between two HIP events on the launch stream; wall = mean of the "
+                  f"same steps between two device synchronisations; cold cache by "
+                  + (f"rotating {W.nsets} copies of the feature / gradient buffers" if W.nsets > 1 else
+                     "the step's own footprint") + (" and an untimed 512 MB fill before every step" if W.flush is not None else ""),
+        "config": {"workload": w.name, "config_id": W.cfg, "seed": w.seed, "mode": w.mode, "widths": w.widths,
+                   "total_edges": W.total_edges, "accumulate": "f64" if w.dtype == "f32" else "f32",
+                   "buffer_footprint_bytes": int(W.footprint), "buffer_sets": W.nsets,
+                   "step": ("table gather; " if W.table is not None else "") +
+                           "plans of all layers (one batched call); forward per layer; backward per layer (reverse)"},
+        "dtype": "f32" if w.dtype == "f32" else "bf16",
+        "hbm_gbps_compulsory": round(gbps_step, 1),
+        "hbm_frac_of_peak": round(gbps_step / HBM_PEAK_GBPS, 4),
+        "frac_of_copy_bw": round(gbps_step / copy_gbps, 4),
+        "gathered_gbps": round(W.gathered_step / (ms_step * 1e-3) / 1e9, 1),
+        "compulsory_bytes_per_step": int(W.bytes_step),
+        "breakdown_ms": {"plan": round(plan_ms, 4), "fwd": round(fwd_ms, 4), "bwd": round(bwd_ms, 4),
+                         "table_gather": None if gather_ms is None else round(gather_ms, 4),
+                         "cached_plan_step": round(cached, 4)},
+        "value_cached_plan": round(2.0 * W.total_edges / (cached * 1e-3) / 1e9, 4),
+        "hbm_frac_cached_plan": round(W.bytes_step / (cached * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "layers": per_layer,
+        "roofline": {"bound": "hbm", "kernel": f"forward aggregation call, layer {dom} (k_pull_rows)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic_table.get((W.cfg, domL["feat"], dom, "fwd")),
+                     "traffic_source": "profiles/traffic_counters.txt (rocprofv3 --pmc runs of this file; not measured in this run)",
+                     "frac_of_copy_bw": round(achieved / copy_gbps, 4),
+                     "launch_ms": round(dom_ms, 4), "algorithmic_bytes": int(domL["bytes_fwd"])},
+        "gen_seconds": round(W.gen_s, 2),
+    }
+    return res
+
+
+def cpu_baseline(W, np, budget_s=12.0, single_budget_s=5.0):
+    """The oracle on the host cores, on a bounded sample of the same workload: the parallel variant
+    (fp32 accumulate, OpenMP over rows, -O3 -march=native build) for about budget_s seconds, and the
+    single-thread fp64 definitional oracle (the one parity is checked against) on the smallest layers."""
+    import oracle
+    torch, layers, w = W.torch, W.layers, W.w
+    host = []
+    for L in layers:
+        if w.dtype == "f32":
+            host.append((L["X"].cpu().numpy(), L["G"].cpu().numpy()))
+        else:
+            host.append((L["X"].view(torch.int16).cpu().numpy().view(np.uint16),
+                         L["G"].view(torch.int16).cpu().numpy().view(np.uint16)))
+    oracle.timed_lib()                      # compiled before the clock starts
+    spent, edges_done, passes = 0.0, 0, 0
+    while spent < budget_s:
+        for L, (Xh, Gh) in zip(layers, host):
+            blk = L["blk"]
+            t0 = time.perf_counter()
+            oracle.par_aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Xh, timed=True)
+            oracle.par_aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Gh, timed=True)
+            spent += time.perf_counter() - t0
+            edges_done += 2 * blk.num_edges
+        passes += 1
+    res = {"value": round(edges_done / spent / 1e9, 5), "unit": "GEdges/s",
+           "cores": oracle.num_threads(), "kind": "oracle",
+           "sample": f"parallel oracle variant (fp32 accumulate, OpenMP over rows, backward through its own "
+                     f"transpose; gcc {' '.join(oracle.TIMED_FLAGS)}): {passes} full fwd+bwd passes over all "
+                     f"{len(layers)} layers of the same workload, {spent:.1f} s"}
+    # the definitional oracle, one thread, smallest layers first until its budget is used
+    spent1, edges1, done = 0.0, 0, []
+    for i in sorted(range(len(layers)), key=lambda i: layers[i]["blk"].num_edges * layers[i]["feat"]):
+        blk, (Xh, Gh) = layers[i]["blk"], host[i]
+        if done and spent1 + 2.5e-9 * blk.num_edges * layers[i]["feat"] * 2 > single_budget_s:
+            break
+        t0 = time.perf_counter()
+        oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Xh)
+        oracle.aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Gh)
+        spent1 += time.perf_counter() - t0
+        edges1 += 2 * blk.num_edges
+        done.append(i)
+    res["single_thread_definitional"] = {
+        "value": round(edges1 / spent1 / 1e9, 5), "unit": "GEdges/s", "cores": 1,
+        "sample": f"fp64 definitional oracle (the parity reference), one fwd+bwd pass over layer(s) {sorted(done)}, {spent1:.2f} s"}
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (2 = the headline)")
     ap.add_argument("--width", type=int, default=32, help="feature width of config 5")
@@ -462,10 +755,18 @@ def main() -> int:
                          "near the diagonal): what the kernels reach when gathered rows can be reused out of L2")
     ap.add_argument("--no-gcn-step", action="store_true",
                     help="skip the extra leg that times the whole sampled GCN (aggregation + update phase)")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the shorter runs of the other four workloads (object `other_configs`)")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="the timed steps and their breakdown only: no extra legs, no CPU baseline, no other workloads "
+                         "(what the rocprofv3 summaries under profiles/ are taken from)")
     ap.add_argument("--verbose", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for rocprofv3 byte counters)")
     args = ap.parse_args()
+    if args.only_headline:
+        args.no_cpu_baseline = args.no_idmap = args.no_match = args.no_edge = args.no_gcn_step = True
+        args.no_other_configs = True
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU; --gpus must be 1 "
               "(data-parallel training gives every GPU its own mini-batch and needs no "
@@ -492,156 +793,30 @@ def main() -> int:
         print(json.dumps({"calibrate": "4 device copies of 1 GiB (1073741824 bytes read and written each)"}))
         return 0
 
-    t0 = time.time()
-    w = bg.make_config(args.config, fanout_order=args.fanout_order, width=args.width)
-    gen_s = time.time() - t0
-    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    elem = 4 if w.dtype == "f32" else 2
-
-    layers = []
-    g = torch.Generator(device="cuda")
-    g.manual_seed(w.seed)
-    ws_bytes = 0
-    for blk, feat in zip(w.blocks, w.widths):
-        L = dict(blk=blk, feat=feat)
-        L["indptr"] = torch.from_numpy(blk.indptr).to(dev)
-        L["indices"] = torch.from_numpy(blk.indices).to(dev)
-        L["X"] = torch.randn((blk.num_src, feat), generator=g, device=dev, dtype=torch.float32).to(tdt)
-        L["G"] = torch.randn((blk.num_dst, feat), generator=g, device=dev, dtype=torch.float32).to(tdt)
-        L["out"] = torch.empty((blk.num_dst, feat), device=dev, dtype=tdt)
-        L["dX"] = torch.empty((blk.num_src, feat), device=dev, dtype=tdt)
-        L["plan_mem"] = torch.empty(B.fastgl_block_plan_bytes(blk.num_dst, blk.num_src, blk.num_edges),
-                                    dtype=torch.uint8, device=dev)
-        ws_bytes = max(ws_bytes, B.fastgl_block_workspace_bytes(blk.num_dst, blk.num_src, blk.num_edges,
-                                                                feat, w.dtype))
-        din = np.diff(blk.indptr)
-        dout = np.bincount(blk.indices, minlength=blk.num_src)
-        L["bytes_fwd"] = compulsory_bytes(blk.num_dst, blk.num_edges, int((dout > 0).sum()), blk.num_dst, feat, elem)
-        L["bytes_bwd"] = compulsory_bytes(blk.num_src, blk.num_edges, int((din > 0).sum()), blk.num_src, feat, elem)
-        layers.append(L)
-    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    table = gid = None
-    gather_bytes = 0
-    if w.src_gid is not None:
-        # config 4: the raw features sit in a device-resident table and are gathered by global id
-        feat0 = w.widths[0]
-        table = torch.empty((w.table_rows, feat0), dtype=tdt, device=dev)
-        for lo in range(0, w.table_rows, 8_000_000):
-            hi = min(w.table_rows, lo + 8_000_000)
-            table[lo:hi] = torch.randn((hi - lo, feat0), generator=g, device=dev, dtype=torch.float32).to(tdt)
-        gid = torch.from_numpy(w.src_gid).to(dev)
-        gather_bytes = 8 * gid.numel() + 2 * gid.numel() * feat0 * elem
-    total_edges = w.total_edges()
-    bytes_step = sum(L["bytes_fwd"] + L["bytes_bwd"] for L in layers) + gather_bytes
-
-    def make_plans():
-        """Bookkeeping of every block of the mini-batch (transpose CSR, degrees, scale
-        factors, degree buckets), built together: each stage is one launch for all layers."""
-        return B.fastgl_block_plan_create_many([(L["indptr"], L["indices"], L["blk"].num_src) for L in layers],
-                                               B.PLAN_ALL, [L["plan_mem"] for L in layers])
-
-    def fwd(L, plan):
-        B.fastgl_block_aggregate_fwd(L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, L["X"],
-                                     out=L["out"], plan=plan, workspace=workspace)
-
-    def bwd(L, plan):
-        B.fastgl_block_aggregate_bwd(L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, L["G"],
-                                     grad_X=L["dX"], plan=plan, workspace=workspace)
-
-    # the dominant kernel: forward pull over the input-layer block
-    dom = max(range(len(layers)), key=lambda i: layers[i]["bytes_fwd"])
-    dom_ev = []
-
-    def step(timed_dom=False):
-        if table is not None:
-            B.fastgl_gather_rows(table, gid, out=layers[0]["X"])
-        plans = make_plans()
-        for i, L in enumerate(layers):
-            if timed_dom and i == dom:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                fwd(L, plans[i])
-                e1.record()
-                dom_ev.append((e0, e1))
-            else:
-                fwd(L, plans[i])
-        for L, p in zip(reversed(layers), reversed(plans)):
-            bwd(L, p)
-        return plans
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(timed_dom=True)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_step = wall * 1e3 / args.steps
-    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in dom_ev]))
-
-    # breakdown (not part of the headline): plan / forward / backward, and a step
-    # with plans built once ("cached plan")
-    def timed(fn, reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-
-    reps = max(5, args.steps // 2)
-    plans = make_plans()
-    plan_ms = timed(make_plans, reps)
-    fwd_ms = timed(lambda: [fwd(L, p) for L, p in zip(layers, plans)], reps)
-    bwd_ms = timed(lambda: [bwd(L, p) for L, p in zip(reversed(layers), reversed(plans))], reps)
-    per_layer = []
-    for i, (L, p) in enumerate(zip(layers, plans)):
-        f = timed(lambda: fwd(L, p), reps)
-        b = timed(lambda: bwd(L, p), reps)
-        per_layer.append(dict(layer=i, num_dst=L["blk"].num_dst, num_src=L["blk"].num_src,
-                              E=L["blk"].num_edges, feat=L["feat"],
-                              fwd_ms=round(f, 4), bwd_ms=round(b, 4),
-                              fwd_gbps=round(L["bytes_fwd"] / f / 1e6, 1),
-                              bwd_gbps=round(L["bytes_bwd"] / b / 1e6, 1)))
-
-    value = 2.0 * total_edges / (ms_step * 1e-3) / 1e9
-    domL = layers[dom]
-    achieved = domL["bytes_fwd"] / (dom_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.config, "fwd", dom))
+    traffic_table = load_traffic_table()
+    copy_gbps = measure_copy_gbps(torch)
+    W = Workload(args.config, args.width, args.fanout_order, B, bg, torch, np)
+    w, layers, workspace = W.w, W.layers, W.workspace
+    head = headline(W, args.steps, args.warmup, np, traffic_table, copy_gbps, per_layer_reps=max(20, args.steps))
+    head["config"]["fanout_order"] = args.fanout_order
     result = {
         "metric": METRIC,
-        "value": round(value, 4),
+        "value": head.pop("value"),
         "unit": "GEdges/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_step, 4),
+        "ms_per_step": head.pop("ms_per_step"),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if w.dtype == "f32" else "bf16",
+        "dtype": head.pop("dtype"),
         "data": "synthetic",
-        "config": {"workload": w.name, "config_id": args.config, "seed": w.seed,
-                   "fanout_order": args.fanout_order, "mode": w.mode, "widths": w.widths,
-                   "total_edges": total_edges, "accumulate": "f64" if w.dtype == "f32" else "f32",
-                   "step": "plans of all layers (one batched call); forward per layer; backward per layer (reverse)"},
-        "hbm_gbps_compulsory": round(bytes_step / (ms_step * 1e-3) / 1e9, 1),
-        "hbm_frac_of_peak": round(bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "compulsory_bytes_per_step": int(bytes_step),
-        "breakdown_ms": {"plan": round(plan_ms, 4), "fwd": round(fwd_ms, 4), "bwd": round(bwd_ms, 4),
-                         "cached_plan_step": round(fwd_ms + bwd_ms, 4)},
-        "value_cached_plan": round(2.0 * total_edges / ((fwd_ms + bwd_ms) * 1e-3) / 1e9, 4),
-        "hbm_frac_cached_plan": round(bytes_step / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-        "layers": per_layer,
-        "roofline": {"bound": "hbm", "kernel": f"forward aggregation call, layer {dom} (k_pull_rows)",
-                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-                     "launch_ms": round(dom_ms, 4), "algorithmic_bytes": int(domL["bytes_fwd"])},
-        "gen_seconds": round(gen_s, 2),
+        "config": head.pop("config"),
+        "copy_gbps_measured": round(copy_gbps, 1),
     }
+    result.update(head)
+    make_plans = W.make_plans
 
     if not args.no_idmap:
         result["idmap"] = idmap_leg(args, w, B, bg, torch, np, with_cpu=not args.no_cpu_baseline)
@@ -655,35 +830,26 @@ def main() -> int:
     if not args.no_gcn_step and len(layers) > 1:
         result["gcn_step"] = gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np,
                                           with_cpu=not args.no_cpu_baseline)
-
     if not args.no_cpu_baseline:
-        import oracle
-        # bounded sample: whole passes over the same workload, layer by layer, repeated
-        # until about 12 s of CPU work (at least one full pass over every layer)
-        budget, spent, edges_done, passes = 12.0, 0.0, 0, 0
-        host = []
-        for L in layers:
-            if w.dtype == "f32":
-                host.append((L["X"].cpu().numpy(), L["G"].cpu().numpy()))
-            else:
-                host.append((L["X"].view(torch.int16).cpu().numpy().view(np.uint16),
-                             L["G"].view(torch.int16).cpu().numpy().view(np.uint16)))
-        while spent < budget:
-            for L, (Xh, Gh) in zip(layers, host):
-                blk = L["blk"]
-                t0 = time.perf_counter()
-                oracle.par_aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Xh)
-                oracle.par_aggregate_bwd(blk.indptr, blk.indices, None, blk.num_src, w.mode, w.dtype, Gh)
-                spent += time.perf_counter() - t0
-                edges_done += 2 * blk.num_edges
-            passes += 1
-        sample = f"{passes} full fwd+bwd passes over all {len(layers)} layers"
-        result["cpu_baseline"] = {
-            "value": round(edges_done / spent / 1e9, 5), "unit": "GEdges/s",
-            "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"parallel oracle variant (fp32 accumulate, OpenMP over rows, backward through its own "
-                      f"transpose): {sample} of the same workload, {spent:.1f} s of CPU time",
-        }
+        result["cpu_baseline"] = cpu_baseline(W, np)
+
+    if not args.no_other_configs:
+        # the other workloads, same measurement with fewer repetitions (their own invocation,
+        # `--config N [--width 256]`, gives the full record)
+        del W, layers, workspace, head
+        torch.cuda.empty_cache()
+        others = []
+        for cfg, width in ((1, 32), (3, 32), (4, 32), (5, 32), (5, 256)):
+            if cfg == args.config and (cfg != 5 or width == args.width):
+                continue
+            Wo = Workload(cfg, width, args.fanout_order, B, bg, torch, np)
+            r = headline(Wo, max(50, args.steps), args.warmup, np, traffic_table, copy_gbps, per_layer_reps=20)
+            r["unit"] = "GEdges/s"
+            others.append(r)
+            del Wo
+            torch.cuda.empty_cache()
+        result["other_configs"] = others
+
     if args.verbose:
         print(json.dumps(result, indent=1), file=sys.stderr)
     print(json.dumps(result))

@@ -67,10 +67,19 @@ enum {
     FASTGL_PLAN_ALL = 3,
     FASTGL_PLAN_PERM = 8,   /* with FASTGL_PLAN_BWD: also keep `perm`, the original edge id of every
                                transposed edge.  Only a backward pass WITH edge_w reads it. */
-    FASTGL_PLAN_SRC_DEG = 4 /* with FASTGL_PLAN_FWD only: out-degrees and their scale factors by a
+    FASTGL_PLAN_SRC_DEG = 4, /* with FASTGL_PLAN_FWD only: out-degrees and their scale factors by a
                                histogram, which is all a GCN-normalised FORWARD pass needs beyond
                                FASTGL_PLAN_FWD.  Lets the forward pass start before the transpose
                                (built in another plan, possibly on another stream) is ready. */
+    FASTGL_PLAN_SHORT_DST_ROWS = 16 /* a hint that may be or-ed to any of the above: the caller states that
+                               no destination row has more than fastgl_long_row_threshold() edges,
+                               which a sampler with a fan-out below that knows for free (Section 2.2:
+                               every target samples a fixed number of neighbours).  The degrees live in
+                               device memory, so without the hint every forward pass has to launch the
+                               long-row reduction kernel just to find that it has nothing to do; with
+                               it that launch is skipped.  Only speed depends on the hint: a row that
+                               is longer after all is still aggregated correctly, by one lane group
+                               alone.  The backward pass (rows = sources) is not affected. */
 };
 
 /* Opaque host-side handle; points into the caller's device buffer. */

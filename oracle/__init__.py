@@ -40,6 +40,60 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+_LIB_TIMED = os.path.join(_HERE, "libfastgl_oracle_timed.so")
+TIMED_FLAGS = ["-O3", "-march=native", "-fopenmp"]
+
+
+def _host_signature() -> str:
+    """What -march=native depends on: the CPU model and its feature flags."""
+    model = flags = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name") and not model:
+                    model = line.split(":", 1)[1].strip()
+                elif line.startswith("flags") and not flags:
+                    flags = line.split(":", 1)[1].strip()
+                if model and flags:
+                    break
+    except OSError:
+        pass
+    import hashlib
+    return model + " " + hashlib.sha1(flags.encode()).hexdigest()[:12]
+
+
+def build_timed(force: bool = False) -> str:
+    """The same source (fastgl_oracle.c: the parallel variant and the transpose it uses) compiled for
+    the benchmark's cpu_baseline leg with TIMED_FLAGS.  -march=native binds the library to the host
+    it was compiled on, so it is rebuilt whenever the host differs from the one recorded next to it.
+    Parity tests never load this library."""
+    stamp = _LIB_TIMED + ".host"
+    sig = _host_signature()
+    stale = (force or not os.path.exists(_LIB_TIMED) or not os.path.exists(stamp)
+             or open(stamp).read() != sig or os.path.getmtime(_LIB_TIMED) < os.path.getmtime(_SRC))
+    if stale:
+        subprocess.run(["gcc", *TIMED_FLAGS, "-std=c11", "-fPIC", "-shared", "-o", _LIB_TIMED, _SRC, "-lm"], check=True)
+        with open(stamp, "w") as f:
+            f.write(sig)
+    return _LIB_TIMED
+
+
+_lib_timed = None
+
+
+def timed_lib():
+    global _lib_timed
+    if _lib_timed is None:
+        L = ctypes.CDLL(build_timed())
+        p, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+        for name in ("fastgl_oracle_par_aggregate_fwd", "fastgl_oracle_par_aggregate_bwd"):
+            getattr(L, name).argtypes = [p, p, p, i64, i64, i64, i64, i32, i32, p, p]
+            getattr(L, name).restype = i32
+        L.fastgl_oracle_num_threads.restype = i32
+        _lib_timed = L
+    return _lib_timed
+
+
 _lib = None
 
 
@@ -143,13 +197,17 @@ def aggregate_bwd(indptr, indices, edge_w, num_src, mode, dtype, G):
                       mode, dtype, G, num_src)
 
 
-def par_aggregate_fwd(indptr, indices, edge_w, num_src, mode, dtype, X):
-    return _aggregate(lib().fastgl_oracle_par_aggregate_fwd, indptr, indices, edge_w, num_src,
+def par_aggregate_fwd(indptr, indices, edge_w, num_src, mode, dtype, X, timed=False):
+    """timed=True: the build with TIMED_FLAGS (what the benchmark times); same source, same result
+    up to fp32 contraction."""
+    L = timed_lib() if timed else lib()
+    return _aggregate(L.fastgl_oracle_par_aggregate_fwd, indptr, indices, edge_w, num_src,
                       mode, dtype, X, len(indptr) - 1)
 
 
-def par_aggregate_bwd(indptr, indices, edge_w, num_src, mode, dtype, G):
-    return _aggregate(lib().fastgl_oracle_par_aggregate_bwd, indptr, indices, edge_w, num_src,
+def par_aggregate_bwd(indptr, indices, edge_w, num_src, mode, dtype, G, timed=False):
+    L = timed_lib() if timed else lib()
+    return _aggregate(L.fastgl_oracle_par_aggregate_bwd, indptr, indices, edge_w, num_src,
                       mode, dtype, G, num_src)
 
 

@@ -18,7 +18,7 @@ FASTGL_OK = 0
 FASTGL_ERR_INVALID_ARG, FASTGL_ERR_UNSUPPORTED, FASTGL_ERR_WORKSPACE, FASTGL_ERR_HIP = 1, 2, 3, 4
 MODES = {"sum": 0, "mean": 1, "gcn": 2}
 DTYPES = {"f32": 0, "bf16": 1}
-PLAN_FWD, PLAN_BWD, PLAN_ALL, PLAN_SRC_DEG, PLAN_PERM = 1, 2, 3, 4, 8
+PLAN_FWD, PLAN_BWD, PLAN_ALL, PLAN_SRC_DEG, PLAN_PERM, PLAN_SHORT_DST_ROWS = 1, 2, 3, 4, 8, 16
 
 EXPORTS = [
     "fastgl_block_aggregate_fwd", "fastgl_block_aggregate_bwd", "fastgl_block_aggregate_fwd_static",

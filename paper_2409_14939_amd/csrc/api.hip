@@ -155,7 +155,10 @@ fastgl_status aggregate_run(bool backward, const int32_t *indptr, const int32_t 
         d.col_scale = mode == FASTGL_AGG_GCN ? pl->src_rsqrt : nullptr;
         d.row_mode = mode == FASTGL_AGG_MEAN ? 1 : mode == FASTGL_AGG_GCN ? 2 : 0;
         d.num_rows = num_dst; d.num_cols = num_src;
-        d.long_rows = pl->long_dst; d.chunk_ptr = pl->chunk_ptr_dst;
+        // a plan with the short-rows hint: no chunk phase, no reduction launch (rows that are long
+        // after all are walked like any other row)
+        const bool chunked = !(pl->parts & FASTGL_PLAN_SHORT_DST_ROWS);
+        d.long_rows = chunked ? pl->long_dst : nullptr; d.chunk_ptr = pl->chunk_ptr_dst;
         d.n_long = pl->counters; d.n_chunks = pl->counters + 1;
         d.split = pl->split_dst; d.nsets = num_row_sets(num_dst, num_edges);
     } else {
@@ -235,11 +238,13 @@ fastgl_status fastgl_block_plan_create_many(int n, const fastgl_block_desc *bloc
         const fastgl_block_desc &d = blocks[i];
         fastgl_status st = check_block(d.indptr, d.indices, d.num_dst, d.num_src, d.num_edges);
         if (st != FASTGL_OK) return st;
-        const int base = d.parts & ~FASTGL_PLAN_PERM;
-        const bool ok = d.parts == FASTGL_PLAN_FWD || d.parts == (FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG) ||
+        const int what = d.parts & ~FASTGL_PLAN_SHORT_DST_ROWS;      // the hint goes with any combination
+        const int base = what & ~FASTGL_PLAN_PERM;
+        const bool ok = what == FASTGL_PLAN_FWD || what == (FASTGL_PLAN_FWD | FASTGL_PLAN_SRC_DEG) ||
                         base == FASTGL_PLAN_BWD || base == FASTGL_PLAN_ALL;
-        if (!ok || d.parts < 0 || d.parts > 15) {
-            set_error("block %d: parts must be FWD, FWD|SRC_DEG, BWD[|PERM] or ALL[|PERM] (got %d)", i, d.parts);
+        if (!ok || d.parts < 0 || d.parts > 31) {
+            set_error("block %d: parts must be FWD, FWD|SRC_DEG, BWD[|PERM] or ALL[|PERM], each optionally "
+                      "|SHORT_DST_ROWS (got %d)", i, d.parts);
             return FASTGL_ERR_INVALID_ARG;
         }
         if (!d.plan_mem || ((uintptr_t)d.plan_mem & 255)) {
@@ -254,7 +259,7 @@ fastgl_status fastgl_block_plan_create_many(int n, const fastgl_block_desc *bloc
     }
     fastgl_plan *plans[FASTGL_MAX_PLAN_BATCH];
     int parts[FASTGL_MAX_PLAN_BATCH];
-    bool src_deg[FASTGL_MAX_PLAN_BATCH];
+    bool src_deg[FASTGL_MAX_PLAN_BATCH], short_dst[FASTGL_MAX_PLAN_BATCH];
     fastgl_status st = FASTGL_OK;
     int made = 0;
     for (; made < n; ++made) {
@@ -272,13 +277,17 @@ fastgl_status fastgl_block_plan_create_many(int n, const fastgl_block_desc *bloc
         // a backward plan also carries what the forward pass of the same block needs
         parts[made] = (d.parts & FASTGL_PLAN_BWD) ? (FASTGL_PLAN_ALL | (d.parts & FASTGL_PLAN_PERM)) : FASTGL_PLAN_FWD;
         src_deg[made] = (d.parts & FASTGL_PLAN_SRC_DEG) != 0;
+        short_dst[made] = (d.parts & FASTGL_PLAN_SHORT_DST_ROWS) != 0;
     }
     if (st == FASTGL_OK) st = plans_build(plans, parts, src_deg, n, (hipStream_t)stream);
     if (st != FASTGL_OK) {
         for (int i = 0; i < made; ++i) delete plans[i];
         return st;
     }
-    for (int i = 0; i < n; ++i) out[i] = plans[i];
+    for (int i = 0; i < n; ++i) {
+        if (short_dst[i]) plans[i]->parts |= FASTGL_PLAN_SHORT_DST_ROWS;
+        out[i] = plans[i];
+    }
     return FASTGL_OK;
 }
 

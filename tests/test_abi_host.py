@@ -84,7 +84,7 @@ def test_static_scratch_entry_point_checks_on_the_host():
 def test_plan_and_gather_argument_checks():
     L = B.lib()
     out = ctypes.c_void_p()
-    for bad in (0, 4, 6, 7, 9, 13, 16, -1):
+    for bad in (0, 4, 6, 7, 9, 13, 16, 20, 32, 33, -1):      # 16 is the short-rows hint: it needs a part to go with
         assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, bad, FAKE, 1 << 30, None, ctypes.byref(out)) == B.FASTGL_ERR_INVALID_ARG, bad
     assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 3, FAKE, 8, None, ctypes.byref(out)) == B.FASTGL_ERR_WORKSPACE
     assert L.fastgl_block_plan_create(FAKE, FAKE, 4, 4, 4, 3, None, 1 << 30, None, ctypes.byref(out)) == B.FASTGL_ERR_INVALID_ARG

@@ -204,6 +204,30 @@ def test_deterministic_bitwise():
     assert a[0].tobytes() == b[0].tobytes() and a[1].tobytes() == b[1].tobytes()
 
 
+def test_short_rows_hint_only_changes_the_launches():
+    """FASTGL_PLAN_SHORT_DST_ROWS is a statement about speed: with it the forward pass leaves out the
+    long-row chunks and their reduction launch.  Given to a block that does have long rows (the hint
+    is wrong here on purpose) the result must still match the oracle; given to a block without them
+    it must equal the result without the hint bit for bit."""
+    rng = np.random.default_rng(31)
+    for blk, what in ((ragged_block(), "long rows present"),
+                      (bg.random_block(rng, 900, 2000, 9.0, empty_frac=0.1), "no long rows")):
+        ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
+        for dtype, feat, mode in (("f32", 100, "gcn"), ("bf16", 64, "mean")):
+            X = make_inputs(rng, blk.num_src, feat, dtype)
+            print(f"case short-rows hint ({what}) dtype={dtype} F={feat} mode={mode}", flush=True)
+            hinted = B.fastgl_block_plan_create(ip, ix, blk.num_src, B.PLAN_ALL | B.PLAN_SHORT_DST_ROWS)
+            plain = B.fastgl_block_plan_create(ip, ix, blk.num_src, B.PLAN_ALL)
+            a = B.fastgl_block_aggregate_fwd(ip, ix, None, blk.num_src, mode, dev_feat(X, dtype), plan=hinted)
+            b = B.fastgl_block_aggregate_fwd(ip, ix, None, blk.num_src, mode, dev_feat(X, dtype), plan=plain)
+            torch.cuda.synchronize()
+            assert_close(host_feat(a, dtype), oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, mode, dtype, X),
+                         dtype, what)
+            if what == "no long rows":
+                assert torch.equal(a.view(torch.int16 if dtype == "bf16" else torch.int32),
+                                   b.view(torch.int16 if dtype == "bf16" else torch.int32))
+
+
 def test_gather_rows():
     rng = np.random.default_rng(4)
     for dtype, feat in (("bf16", 128), ("f32", 100), ("bf16", 7), ("f32", 602)):
