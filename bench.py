@@ -350,6 +350,7 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=
         p["ws"] = torch.empty(max(256, B.fastgl_update_bwd_workspace_bytes(M, K, N)), dtype=torch.uint8, device=dev)
         P.append(p)
     dlogits = torch.randn((P[-1]["M"], CLASSES), generator=g, device=dev).to(tdt)
+    fuse_last = B.fastgl_layer_fwd_fuses(P[-1]["K"], P[-1]["N"], "f32" if tdt == torch.float32 else "bf16")
     ev = {}
 
     def mark(key, fn, record):
@@ -372,10 +373,16 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=
         mark("plan", build, record)
         x = layers[0]["X"]
         for i, (L, p) in enumerate(zip(layers, P)):
-            mark(f"agg_fwd{i}", lambda: B.fastgl_block_aggregate_fwd(
-                L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, x, out=p["H"], plan=plans[i],
-                workspace=workspace), record)
-            mark(f"upd_fwd{i}", lambda: B.fastgl_update_fwd(p["H"], p["W"], p["b"], p["relu"], p["Y"]), record)
+            if fuse_last and i == n - 1:
+                # the class-score layer: aggregation and update in one kernel (H kept for the backward pass)
+                mark(f"layer_fwd{i}", lambda: B.fastgl_layer_fwd(
+                    L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, x, p["W"], p["b"], p["relu"],
+                    H=p["H"], Y=p["Y"], plan=plans[i], workspace=workspace), record)
+            else:
+                mark(f"agg_fwd{i}", lambda: B.fastgl_block_aggregate_fwd(
+                    L["indptr"], L["indices"], None, L["blk"].num_src, w.mode, x, out=p["H"], plan=plans[i],
+                    workspace=workspace), record)
+                mark(f"upd_fwd{i}", lambda: B.fastgl_update_fwd(p["H"], p["W"], p["b"], p["relu"], p["Y"]), record)
             x = p["Y"]
         grad = dlogits
         for i in reversed(range(n)):
@@ -430,7 +437,7 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=
     flops_fwd = [2.0 * p["M"] * p["K"] * p["N"] for p in P]
     flops = sum(flops_fwd) + sum(f * (2 if i > 0 else 1) for i, f in enumerate(flops_fwd))
     upd_ms = sum(v for k, v in parts.items() if k.startswith("upd"))
-    agg_ms = sum(v for k, v in parts.items() if k.startswith("agg"))
+    agg_ms = sum(v for k, v in parts.items() if k.startswith("agg") or k.startswith("layer"))
     dom_ms = parts["upd_fwd0"]
     ach = flops_fwd[0] / (dom_ms * 1e-3) / 1e12
     pieces = 1 if tdt == torch.bfloat16 else 6
@@ -448,7 +455,8 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=
         "cpu_oracle": cpu,
         "what": "plans + per layer [aggregate, act(H W + b)] forward, then backward (dW, db every layer; "
                 "dH and the backward aggregation for every layer but the input one); widths "
-                f"{[p['K'] for p in P]} -> {outs}",
+                f"{[p['K'] for p in P]} -> {outs}" + ("; the last layer's forward is one fused kernel "
+                                                      "(fastgl_layer_fwd, counted with the aggregation)" if fuse_last else ""),
         "ms_per_step": round(ms, 4),
         "ms_per_step_two_streams": round(ms_two, 4),
         "parts_ms": {k: round(v, 4) for k, v in parts.items()},

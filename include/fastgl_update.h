@@ -72,6 +72,30 @@ fastgl_status fastgl_update_bwd_bf16(const uint16_t *H, const uint16_t *W, const
                                      uint16_t *dH, float *dW, float *db,
                                      void *workspace, size_t workspace_bytes, void *stream);
 
+/* One layer in one call: aggregation (Eq. 1) followed by the update (Eq. 2),
+ *   H = aggregate(X)        [num_dst, K]   exactly what fastgl_block_aggregate_fwd writes
+ *   Y = act(H W + bias)     [num_dst, N]
+ * The graph arguments, edge_w, mode, plan and workspace are those of
+ * fastgl_block_aggregate_fwd with feat = K (workspace >= fastgl_block_workspace_bytes);
+ * W, bias, relu and Y are those of fastgl_update_fwd; X, W, H, Y are fp32 or, with
+ * dtype FASTGL_BF16, bf16 bit patterns (bias fp32 either way).
+ * For a narrow layer - fastgl_layer_fwd_fuses(K, N, dtype) != 0: fp32, K a multiple of 4 and at
+ * most 256, N at most 64, X and H 16-byte aligned; the class-score layer of a sampled GCN - both
+ * steps run in ONE kernel and the aggregated rows do not travel through memory: each is rounded to
+ * fp32 once, as the separate call would store it, and multiplied out of on-chip memory with fp32
+ * multiply-adds in ascending k (a chain of K + 1 roundings per element of Y).  H may then be NULL
+ * (inference); when given it is written as a by-product for the backward pass.  Every row is
+ * walked by one wavefront whatever its length: meant for sampled layers, whose rows are short.
+ * Any other shape runs the two kernels of the separate calls back to back and needs H. */
+fastgl_status fastgl_layer_fwd(const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                               int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t K,
+                               fastgl_agg_mode mode, fastgl_dtype dtype, const void *X,
+                               const void *W, const float *bias, int64_t N, int relu,
+                               void *H, void *Y,
+                               const fastgl_plan *plan, void *workspace, size_t workspace_bytes,
+                               void *stream);
+int fastgl_layer_fwd_fuses(int64_t K, int64_t N, fastgl_dtype dtype);
+
 /* Rows of H per dW/db slab for this shape (the length of the longest fp32
  * accumulation chain of the backward pass): a function of M, K, N alone,
  * a multiple of 32 between 32 and 2048; 0 for negative sizes. */

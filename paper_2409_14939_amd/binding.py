@@ -27,7 +27,7 @@ EXPORTS = [
     "fastgl_block_workspace_bytes", "fastgl_long_row_threshold", "fastgl_long_row_chunk", "fastgl_work_per_group",
     "fastgl_gather_rows", "fastgl_block_validate", "fastgl_last_error",
     "fastgl_update_fwd", "fastgl_update_bwd", "fastgl_update_bwd_workspace_bytes", "fastgl_update_slab_rows",
-    "fastgl_update_fwd_bf16", "fastgl_update_bwd_bf16",
+    "fastgl_update_fwd_bf16", "fastgl_update_bwd_bf16", "fastgl_layer_fwd", "fastgl_layer_fwd_fuses",
     "fastgl_idmap", "fastgl_idmap_table_slots", "fastgl_idmap_workspace_bytes",
     "fastgl_match", "fastgl_match_workspace_bytes", "fastgl_assemble_rows", "fastgl_overlap_counts",
     "fastgl_overlap_workspace_bytes", "fastgl_greedy_reorder",
@@ -113,6 +113,8 @@ def lib() -> ctypes.CDLL:
         L.fastgl_idmap_workspace_bytes.restype = sz
         L.fastgl_idmap.argtypes = [p, i64, p, i64, i32, p, p, p, p, sz, p]
         L.fastgl_update_bwd_bf16.argtypes = L.fastgl_update_bwd.argtypes
+        L.fastgl_layer_fwd.argtypes = [p, p, p, i64, i64, i64, i64, i32, i32, p, p, p, i64, i32, p, p, p, p, sz, p]
+        L.fastgl_layer_fwd_fuses.argtypes = [i64, i64, i32]
         L.fastgl_update_slab_rows.argtypes = [i64, i64, i64]
         L.fastgl_update_slab_rows.restype = ctypes.c_int32
         _lib = L
@@ -340,6 +342,45 @@ def fastgl_update_fwd(H: torch.Tensor, W: torch.Tensor, bias: Optional[torch.Ten
     fn = lib().fastgl_update_fwd if dt == torch.float32 else lib().fastgl_update_fwd_bf16
     _check(fn(_ptr(H), _ptr(W), _ptr(bias), M, K, N, int(bool(relu)), _ptr(Y), _stream()))
     return Y
+
+
+def fastgl_layer_fwd_fuses(K: int, N: int, dtype: str) -> bool:
+    return bool(lib().fastgl_layer_fwd_fuses(K, N, DTYPES[dtype]))
+
+
+def fastgl_layer_fwd(indptr, indices, edge_w, num_src: int, mode: str, X: torch.Tensor, W: torch.Tensor,
+                     bias: Optional[torch.Tensor], relu: bool, H: Optional[torch.Tensor] = None,
+                     Y: Optional[torch.Tensor] = None, want_H: bool = True, plan: Optional[Plan] = None,
+                     workspace: Optional[torch.Tensor] = None):
+    """Aggregation + update of one layer in one call; returns (H, Y).  want_H=False (and H None) leaves the
+    aggregated rows unwritten, which only shapes that fuse allow."""
+    _dev(indptr, torch.int32, "indptr")
+    _dev(indices, torch.int32, "indices")
+    if edge_w is not None:
+        _dev(edge_w, torch.float32, "edge_w")
+    dt = _feat_dtype(X)
+    _dev(X, X.dtype, "X")
+    _dev(W, X.dtype, "W")
+    num_dst, num_edges, K, N = indptr.numel() - 1, indices.numel(), X.shape[1], W.shape[1]
+    if X.shape[0] != num_src or W.shape[0] != K or (bias is not None and bias.shape != (N,)):
+        raise ValueError("X must be [num_src,K], W [K,N], bias [N]")
+    if bias is not None:
+        _dev(bias, torch.float32, "bias")
+    if H is None and want_H:
+        H = torch.empty((num_dst, K), dtype=X.dtype, device=X.device)
+    if Y is None:
+        Y = torch.empty((num_dst, N), dtype=X.dtype, device=X.device)
+    if H is not None:
+        _dev(H, X.dtype, "H")
+    _dev(Y, X.dtype, "Y")
+    if workspace is None:
+        nbytes = int(lib().fastgl_block_workspace_bytes(num_dst, num_src, num_edges, K, dt))
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=X.device)
+    _check(lib().fastgl_layer_fwd(_ptr(indptr), _ptr(indices), _ptr(edge_w), num_dst, num_src, num_edges, K,
+                                  MODES[mode], dt, _ptr(X), _ptr(W), _ptr(bias), N, int(bool(relu)), _ptr(H), _ptr(Y),
+                                  plan.handle if plan is not None else None, _ptr(workspace), workspace.numel(),
+                                  _stream()))
+    return H, Y
 
 
 def fastgl_update_bwd(H: torch.Tensor, W: torch.Tensor, Y: Optional[torch.Tensor], dY: torch.Tensor, relu: bool,

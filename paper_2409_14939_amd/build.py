@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libfastgl_agg.so")
 SOURCES = ["api.hip", "bookkeeping.hip", "aggregate.hip", "update.hip", "idmap.hip", "match.hip", "edge.hip",
-           "static_scratch.hip"]
+           "static_scratch.hip", "layer.hip"]
 
 
 def build_library(verbose: bool = False) -> str:

@@ -122,27 +122,29 @@ fastgl_status aggregate_check(bool backward, const int32_t *indptr, const int32_
     return FASTGL_OK;
 }
 
-// The launches of a call that passed aggregate_check; workspace holds at least the bytes it asked for.
-fastgl_status aggregate_run(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
-                            int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
-                            fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
-                            const fastgl_plan *plan, void *workspace, void *stream)
+// What a call that passed aggregate_check launches, short of the aggregation kernel itself: the
+// bookkeeping when no plan is passed (enqueued here, inside `workspace`), and the descriptor of the
+// pull.  *local is storage for the plan built here; it must live until the launches are enqueued.
+fastgl_status aggregate_prepare(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                                int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                                fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                                const fastgl_plan *plan, void *workspace, void *stream, fastgl_plan *local,
+                                PullDesc *desc)
 {
     hipStream_t s = (hipStream_t)stream;
-    fastgl_plan local;
     const fastgl_plan *pl = plan;
     if (!plan) {
         const int need_parts = backward ? (FASTGL_PLAN_ALL | (edge_w ? FASTGL_PLAN_PERM : 0)) : FASTGL_PLAN_FWD;
-        local.num_dst = num_dst; local.num_src = num_src; local.num_edges = num_edges;
-        local.indptr = indptr; local.indices = indices;
-        plan_layout(&local, (char *)workspace + partial_bytes(num_edges, feat, dtype), num_dst, num_src, num_edges,
+        local->num_dst = num_dst; local->num_src = num_src; local->num_edges = num_edges;
+        local->indptr = indptr; local->indices = indices;
+        plan_layout(local, (char *)workspace + partial_bytes(num_edges, feat, dtype), num_dst, num_src, num_edges,
                     !backward);
-        fastgl_status st = plan_build(&local, need_parts, mode == FASTGL_AGG_GCN, s);
+        fastgl_status st = plan_build(local, need_parts, mode == FASTGL_AGG_GCN, s);
         if (st != FASTGL_OK) return st;
-        pl = &local;
+        pl = local;
     }
 
-    PullDesc d;
+    PullDesc &d = *desc;
     d.edge_w = edge_w;
     d.feat = feat;
     d.dtype = dtype;
@@ -170,7 +172,21 @@ fastgl_status aggregate_run(bool backward, const int32_t *indptr, const int32_t 
         d.n_long = pl->counters + 2; d.n_chunks = pl->counters + 3;
         d.split = pl->split_src; d.nsets = num_row_sets(num_src, num_edges);
     }
-    return launch_pull(d, s);
+    return FASTGL_OK;
+}
+
+// The launches of a call that passed aggregate_check; workspace holds at least the bytes it asked for.
+fastgl_status aggregate_run(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                            int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                            fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                            const fastgl_plan *plan, void *workspace, void *stream)
+{
+    fastgl_plan local;
+    PullDesc d;
+    fastgl_status st = aggregate_prepare(backward, indptr, indices, edge_w, num_dst, num_src, num_edges, feat, mode,
+                                         dtype, in, out, plan, workspace, stream, &local, &d);
+    if (st != FASTGL_OK) return st;
+    return launch_pull(d, (hipStream_t)stream);
 }
 
 static fastgl_status aggregate(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,

@@ -96,13 +96,19 @@ struct PullDesc {
 
 fastgl_status launch_pull(const PullDesc &d, hipStream_t s);
 
-// The two halves of fastgl_block_aggregate_fwd / _bwd.  aggregate_check: every host-side check, no
-// HIP call; *need = workspace bytes the call takes.  aggregate_run: bookkeeping (when plan is NULL)
-// and the aggregation launches, for a call that passed the check, on a workspace of >= *need bytes.
+// The parts of fastgl_block_aggregate_fwd / _bwd.  aggregate_check: every host-side check, no HIP
+// call; *need = workspace bytes the call takes.  aggregate_prepare: bookkeeping (when plan is NULL)
+// and the descriptor of the pull; aggregate_run: that plus the aggregation launches - both for a call
+// that passed the check, on a workspace of >= *need bytes.
 fastgl_status aggregate_check(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
                               int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
                               fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
                               const fastgl_plan *plan, size_t *need);
+fastgl_status aggregate_prepare(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
+                                int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
+                                fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,
+                                const fastgl_plan *plan, void *workspace, void *stream, fastgl_plan *local,
+                                PullDesc *desc);
 fastgl_status aggregate_run(bool backward, const int32_t *indptr, const int32_t *indices, const float *edge_w,
                             int64_t num_dst, int64_t num_src, int64_t num_edges, int64_t feat,
                             fastgl_agg_mode mode, fastgl_dtype dtype, const void *in, void *out,

@@ -81,6 +81,24 @@ def test_static_scratch_entry_point_checks_on_the_host():
     assert call(nd=1000, ns=1000, ne=90_000_000, feat=256) == B.FASTGL_ERR_WORKSPACE
 
 
+def test_layer_entry_point_checks_on_the_host():
+    f = B.lib().fastgl_layer_fwd
+    assert B.fastgl_layer_fwd_fuses(256, 47, "f32") and B.fastgl_layer_fwd_fuses(4, 64, "f32")
+    assert not B.fastgl_layer_fwd_fuses(256, 65, "f32") and not B.fastgl_layer_fwd_fuses(260, 47, "f32")
+    assert not B.fastgl_layer_fwd_fuses(30, 16, "f32") and not B.fastgl_layer_fwd_fuses(256, 47, "bf16")
+
+    def call(nd=4, ns=4, ne=4, K=8, mode=0, dt=0, X=FAKE, W=FAKE, bias=None, N=4, H=FAKE, Y=FAKE, ws=FAKE, wsb=1 << 30):
+        return f(FAKE, FAKE, None, nd, ns, ne, K, mode, dt, X, W, bias, N, 0, H, Y, None, ws, wsb, None)
+    assert call(N=-1) == B.FASTGL_ERR_INVALID_ARG
+    assert call(K=0) == B.FASTGL_ERR_INVALID_ARG
+    assert call(X=None) == B.FASTGL_ERR_INVALID_ARG
+    assert call(W=None) == B.FASTGL_ERR_INVALID_ARG
+    assert call(ws=None) == B.FASTGL_ERR_INVALID_ARG
+    assert call(wsb=8) == B.FASTGL_ERR_WORKSPACE
+    assert call(K=602, H=None) == B.FASTGL_ERR_INVALID_ARG and "two kernels" in B.fastgl_last_error()
+    assert call(nd=0, ne=0) == B.FASTGL_OK                                   # no target nodes: nothing to do
+
+
 def test_plan_and_gather_argument_checks():
     L = B.lib()
     out = ctypes.c_void_p()
