@@ -30,11 +30,19 @@ MODES = {"sum": 0, "mean": 1, "gcn": 2}
 DTYPES = {"f32": 0, "bf16": 1}
 
 
+# FASTGL_ORACLE_UBSAN=1 in the environment: the same sources built with the undefined-behaviour
+# sanitizer (every finding aborts the process); tests/test_sanitizers.py runs the pin tests on it.
+_UBSAN = os.environ.get("FASTGL_ORACLE_UBSAN") == "1"
+if _UBSAN:
+    _LIB = os.path.join(_HERE, "libfastgl_oracle_ubsan.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (generic x86-64 so the .so runs on any host)."""
     if (force or not os.path.exists(_LIB)
             or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)):
-        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+        extra = ["-fsanitize=undefined", "-fno-sanitize-recover=all", "-g"] if _UBSAN else []
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off", *extra,
                "-Wall", "-Wextra", "-o", _LIB, *_SRCS, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
@@ -76,6 +84,16 @@ def build_timed(force: bool = False) -> str:
         with open(stamp, "w") as f:
             f.write(sig)
     return _LIB_TIMED
+
+
+def build_sanitize_check() -> str:
+    """oracle/sanitize_check.c (the driver of the sanitizer test) as a plain executable, so that the
+    build check covers every C file of this folder; tests/test_sanitizers.py builds its own copy with
+    the sanitizers on."""
+    exe = os.path.join(_HERE, "sanitize_check.bin")
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fopenmp", "-Wall", "-Wextra", "-o", exe,
+                    os.path.join(_HERE, "sanitize_check.c"), *_SRCS, "-lm"], check=True)
+    return exe
 
 
 _lib_timed = None
