@@ -83,7 +83,9 @@ def idmap_leg(args, w, B, bg, torch, np, with_cpu):
         h["uniq"] = torch.empty(n, dtype=torch.int64, device=dev)
         h["res"] = torch.empty(2, dtype=torch.int32, device=dev)
         # table fill + one entry touched per ID + IDs in + slot array out and in + indices out + source list out
-        h["bytes"] = 16 * B.fastgl_idmap_table_slots(n) + 16 * n + 8 * n + 8 * n + 4 * nbr.size + 8 * blk.num_src
+        # (entries: 16 bytes in the ordered mode, 8-byte key + 4-byte local ID in the fused one)
+        h["bytes"] = {mode: per * B.fastgl_idmap_table_slots(n) + per * n + 8 * n + 8 * n + 4 * nbr.size + 8 * blk.num_src
+                      for mode, per in (("ordered", 16), ("fused", 12))}
         hops.append(h)
     n_ids = sum(h["dst"].numel() + h["nbr"].numel() for h in hops)
     out = {"what": "global -> local IDs of every hop of the mini-batch (64-bit IDs, hash table with "
@@ -109,8 +111,8 @@ def idmap_leg(args, w, B, bg, torch, np, with_cpu):
             U, bad = (int(x) for x in h["res"].cpu().numpy())
             assert bad == 0 and U == h["blk"].num_src, (mode, U, bad)
         out[mode] = {"ms": round(ms, 4), "gids_per_s": round(n_ids / ms / 1e6, 3),
-                     "hbm_gbps_algorithmic": round(sum(h["bytes"] for h in hops) / ms / 1e6, 1),
-                     "hbm_frac_of_peak": round(sum(h["bytes"] for h in hops) / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+                     "hbm_gbps_algorithmic": round(sum(h["bytes"][mode] for h in hops) / ms / 1e6, 1),
+                     "hbm_frac_of_peak": round(sum(h["bytes"][mode] for h in hops) / ms / 1e6 / HBM_PEAK_GBPS, 4)}
     if with_cpu:
         import oracle
         t0 = time.perf_counter()

@@ -47,9 +47,10 @@ extern "C" {
 
 typedef enum { FASTGL_IDMAP_ORDERED = 0, FASTGL_IDMAP_FUSED = 1 } fastgl_idmap_mode;
 
-/* Slots of the hash table used for n_ids = n_dst + n_nbr global IDs: the power
- * of two >= 2 * n_ids (at least 1024), so linear probing always ends. 0 if
- * n_ids is negative or too large. */
+/* Slots of the hash table used for n_ids = n_dst + n_nbr global IDs: 1.5 per
+ * input ID (at least 1024).  At most n_ids keys ever enter it, so it keeps empty
+ * slots and linear probing always ends; a sampled hop, whose IDs mostly repeat,
+ * fills a quarter of it. 0 if n_ids is negative or too large. */
 int64_t fastgl_idmap_table_slots(int64_t n_ids);
 
 /* Bytes of device workspace (256-byte aligned) one call needs: the table

@@ -18,58 +18,73 @@ struct __attribute__((aligned(16))) Slot {
     int32_t lid;              // ID map, ordered: local ID.  (val, lid) together: 64-bit batch mask
 };
 
-// Capacity for n IDs: the power of two >= 2n (at least 1024), so a probe sequence always ends.
+// Capacity for n DISTINCT keys (Match, overlap counts): 2n slots (at least 1024), so the table is
+// never more than half full and a probe sequence always ends at an empty slot.
 inline int64_t table_slots(int64_t n)
 {
-    int64_t cap = 1024;
-    while (cap < 2 * n) cap *= 2;
-    return cap;
+    const int64_t cap = 2 * n;
+    return cap < 1024 ? 1024 : cap;
 }
 
-inline int table_shift(int64_t cap)          // 64 - log2(cap), for hash_slot
+// Capacity for the n input IDs of the ID map, most of which repeat (a sampled hop holds every hub
+// many times): 1.5 n slots.  The table can never fill up (there are at most n keys), a hop whose IDs
+// are all distinct loads it to two thirds, a typical one (a third to a half distinct) to a quarter.
+// Sized by the distinct IDs it would be smaller still, but their number is only known afterwards.
+inline int64_t idmap_slots(int64_t n)
 {
-    int lg = 0;
-    while (((int64_t)1 << lg) < cap) ++lg;
-    return 64 - lg;
+    const int64_t cap = n + n / 2;
+    return cap < 1024 ? 1024 : cap;
 }
 
-__device__ __forceinline__ uint32_t hash_slot(int64_t gid, int shift)
+// Slot of an ID in a table of `cap` slots (any size below 2^31, not only powers of two): the upper
+// half of a multiplicative hash scaled to [0, cap).
+__device__ __forceinline__ uint32_t hash_slot(int64_t gid, uint32_t cap)
 {
-    return (uint32_t)(((uint64_t)gid * 0x9E3779B97F4A7C15ull) >> shift);
+    const uint32_t h = (uint32_t)(((uint64_t)gid * 0x9E3779B97F4A7C15ull) >> 32);
+    return (uint32_t)(((uint64_t)h * cap) >> 32);
 }
 
-// Slot that holds gid after the call; fresh = this thread put it there.  The slot is read with a
-// plain load first and the compare-and-swap is only issued when that showed the empty marker: a key
-// changes exactly once (from -1 to an ID), so anything else that is read is final.  Ends because at
-// most half of the slots are ever taken.
-__device__ __forceinline__ uint32_t insert_id(Slot *table, uint32_t mask, int shift, int64_t gid, bool &fresh)
+__device__ __forceinline__ uint32_t next_slot(uint32_t slot, uint32_t cap) { return slot + 1 == cap ? 0u : slot + 1; }
+
+// Slot that holds gid after the call; fresh = this thread put it there.  Keys sit STRIDE bytes apart
+// from `keys` on (16: the key of a Slot; 8: a bare array of keys).  The slot is read with a plain load
+// first and the compare-and-swap is only issued when that showed the empty marker: a key changes
+// exactly once (from -1 to an ID), so anything else that is read is final.  Ends because the table
+// always keeps empty slots.
+template <int STRIDE>
+__device__ __forceinline__ uint32_t insert_key(void *keys, uint32_t cap, int64_t gid, bool &fresh)
 {
-    uint32_t slot = hash_slot(gid, shift);
+    uint32_t slot = hash_slot(gid, cap);
     fresh = false;
     for (;;) {
-        int64_t k = __hip_atomic_load(&table[slot].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int64_t *kp = reinterpret_cast<int64_t *>(static_cast<char *>(keys) + (size_t)slot * STRIDE);
+        int64_t k = __hip_atomic_load(kp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (k == -1) {
-            k = (int64_t)atomicCAS((unsigned long long *)&table[slot].key, (unsigned long long)-1ll,
-                                   (unsigned long long)gid);
+            k = (int64_t)atomicCAS((unsigned long long *)kp, (unsigned long long)-1ll, (unsigned long long)gid);
             if (k == -1) {
                 fresh = true;
                 return slot;
             }
         }
         if (k == gid) return slot;
-        slot = (slot + 1) & mask;
+        slot = next_slot(slot, cap);
     }
 }
 
-// Slot that holds gid in a table that is no longer written, or kNoSlot.  Ends at the first empty slot.
-__device__ __forceinline__ int32_t find_id(const Slot *table, uint32_t mask, int shift, int64_t gid)
+__device__ __forceinline__ uint32_t insert_id(Slot *table, uint32_t cap, int64_t gid, bool &fresh)
 {
-    uint32_t slot = hash_slot(gid, shift);
+    return insert_key<(int)sizeof(Slot)>(table, cap, gid, fresh);
+}
+
+// Slot that holds gid in a table that is no longer written, or kNoSlot.  Ends at the first empty slot.
+__device__ __forceinline__ int32_t find_id(const Slot *table, uint32_t cap, int64_t gid)
+{
+    uint32_t slot = hash_slot(gid, cap);
     for (;;) {
         const int64_t k = table[slot].key;
         if (k == gid) return (int32_t)slot;
         if (k == -1) return kNoSlot;
-        slot = (slot + 1) & mask;
+        slot = next_slot(slot, cap);
     }
 }
 

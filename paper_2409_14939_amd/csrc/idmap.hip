@@ -2,13 +2,16 @@
 // sampled hop -> consecutive local IDs.  See include/fastgl_idmap.h for the contract.
 //
 // Table: open addressing with linear probing, 64-bit keys claimed by compare-and-swap from the
-// empty marker -1, capacity a power of two >= 2 x the number of input IDs.  A thread reads the
+// empty marker -1, capacity 1.5 x the number of input IDs (most of which repeat).  A thread reads the
 // slot with a plain load first and only issues the compare-and-swap when it saw the empty marker:
 // a key changes exactly once (from -1 to an ID), so anything else it reads is final; repeats of a
 // hub node therefore cost loads, not atomics.
 //
 // FUSED mode is Algorithm 2: the claimant of a slot takes the next local ID from a counter (one
 // atomic add per workgroup, the threads that claimed a slot share it), a second kernel translates.
+// Its insertion only touches keys and its translation only local IDs, so it keeps them in two bare
+// arrays (8 + 4 bytes per slot): the array the translation reads at random is a quarter of the size
+// of a table of 16-byte entries and largely stays in L2.
 // ORDERED mode replaces the counter by "smallest position seen at this slot" (atomic min), then a
 // prefix count over the positions that are first occurrences gives every distinct ID its rank in
 // order of first appearance.  Both remember the slot of every input ID, so translation does not
@@ -25,16 +28,16 @@ constexpr int32_t kFirstBit = (int32_t)0x80000000u;
 struct IdmapArgs {
     const int64_t *dst_gid, *nbr_gid;
     int64_t n_dst, n_nbr, n;
-    Slot *table;              // [cap]
+    Slot *table;              // [cap] ORDERED: 16-byte entries
+    int64_t *keys;            // [cap] FUSED: keys ...
+    int32_t *vals;            // [cap]        ... and local IDs
     int32_t *slot_of;         // [n] slot of every input position (kNoSlot: rejected ID); the ordered mode
                               // sets bit 31 on positions that are first occurrences
     int32_t *block_cnt;       // [blocks + 1]
     int32_t *local_nbr;
     int64_t *unique_gid;
     int32_t *result;          // [0] U, [1] violations
-    uint32_t mask;
-    int shift;                // 64 - log2(cap)
-    int64_t cap;
+    int64_t cap;              // slots of the table
     int nblocks;
     int fused;
 };
@@ -52,9 +55,13 @@ __global__ __launch_bounds__(256) void k_idmap_fill(IdmapArgs a)
         a.result[1] = 0;
     }
     if (i >= a.cap) return;
+    if (a.fused) {
+        a.keys[i] = -1;       // a local ID is only read at a slot somebody claimed, after its claimant wrote it
+        return;
+    }
     Slot e;
     e.key = -1;
-    e.val = a.fused ? 0 : INT32_MAX;
+    e.val = INT32_MAX;
     e.lid = 0;
     a.table[i] = e;
 }
@@ -71,7 +78,7 @@ __global__ __launch_bounds__(256) void k_idmap_insert_min(IdmapArgs a)
         return;
     }
     bool fresh;
-    const uint32_t slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
+    const uint32_t slot = insert_id(a.table, (uint32_t)a.cap, gid, fresh);
     a.slot_of[p] = (int32_t)slot;
     // the value only ever decreases, so a (possibly stale) reading that is already smaller settles it
     if (__hip_atomic_load(&a.table[slot].val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > (int32_t)p)
@@ -121,7 +128,7 @@ __global__ __launch_bounds__(256) void k_idmap_translate(IdmapArgs a)
     const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= a.n_nbr) return;
     const int32_t slot = a.slot_of[a.n_dst + e] & kNoSlot;
-    a.local_nbr[e] = slot == kNoSlot ? -1 : (a.fused ? a.table[slot].val : a.table[slot].lid);
+    a.local_nbr[e] = slot == kNoSlot ? -1 : (a.fused ? a.vals[slot] : a.table[slot].lid);
 }
 
 // FUSED pass 1a: destination i takes local ID i.
@@ -132,9 +139,9 @@ __global__ __launch_bounds__(256) void k_idmap_fused_dst(IdmapArgs a)
     const int64_t gid = a.dst_gid[p];
     bool fresh = false;
     if (gid >= 0) {
-        const uint32_t slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
+        const uint32_t slot = insert_key<8>(a.keys, (uint32_t)a.cap, gid, fresh);
         if (fresh) {
-            a.table[slot].val = (int32_t)p;
+            a.vals[slot] = (int32_t)p;
             a.unique_gid[p] = gid;
         }
     }
@@ -152,7 +159,7 @@ __global__ __launch_bounds__(kScanBlock) void k_idmap_fused_nbr(IdmapArgs a)
     const int64_t gid = active ? a.nbr_gid[e] : -1;
     bool fresh = false;
     uint32_t slot = 0;
-    if (gid >= 0) slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
+    if (gid >= 0) slot = insert_key<8>(a.keys, (uint32_t)a.cap, gid, fresh);
     if (active) {
         a.slot_of[a.n_dst + e] = gid >= 0 ? (int32_t)slot : kNoSlot;
         if (gid < 0) atomicAdd(&a.result[1], 1);
@@ -164,7 +171,7 @@ __global__ __launch_bounds__(kScanBlock) void k_idmap_fused_nbr(IdmapArgs a)
     __syncthreads();
     if (fresh) {
         const int l = range_base + mine;
-        a.table[slot].val = l;
+        a.vals[slot] = l;
         a.unique_gid[l] = gid;
     }
 }
@@ -175,7 +182,7 @@ struct Layout {
 
 Layout layout(int64_t n)
 {
-    const int64_t cap = table_slots(n);
+    const int64_t cap = idmap_slots(n);
     Layout L;
     size_t off = 0;
     L.table = off; off += align_up((size_t)cap * sizeof(Slot), 256);
@@ -195,7 +202,7 @@ extern "C" {
 int64_t fastgl_idmap_table_slots(int64_t n_ids)
 {
     if (n_ids < 0 || n_ids >= kMaxIds) return 0;
-    return table_slots(n_ids);
+    return idmap_slots(n_ids);
 }
 
 size_t fastgl_idmap_workspace_bytes(int64_t n_dst, int64_t n_nbr)
@@ -244,12 +251,12 @@ fastgl_status fastgl_idmap(const int64_t *dst_gid, int64_t n_dst, const int64_t 
     a.dst_gid = dst_gid; a.nbr_gid = nbr_gid;
     a.n_dst = n_dst; a.n_nbr = n_nbr; a.n = n;
     a.table = (Slot *)(ws + L.table);
+    a.keys = (int64_t *)(ws + L.table);                       // the fused mode's two arrays share the table's room
     a.slot_of = (int32_t *)(ws + L.slot_of);
     a.block_cnt = (int32_t *)(ws + L.block_cnt);
     a.local_nbr = local_nbr; a.unique_gid = unique_gid; a.result = result;
-    a.cap = table_slots(n);
-    a.mask = (uint32_t)(a.cap - 1);
-    a.shift = table_shift(a.cap);
+    a.cap = idmap_slots(n);
+    a.vals = (int32_t *)(a.keys + a.cap);
     a.nblocks = (int)ceil_div(n, kScanBlock);
     a.fused = mode == FASTGL_IDMAP_FUSED;
     hipStream_t s = (hipStream_t)stream;

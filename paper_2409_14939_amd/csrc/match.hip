@@ -21,8 +21,6 @@ struct MatchArgs {
     int64_t n_prev, n_new;
     Slot *table;
     int64_t cap;
-    uint32_t mask;
-    int shift;
     int32_t *block_cnt;
     int nblocks;
     int32_t *src_row, *load_pos;
@@ -49,7 +47,7 @@ __global__ __launch_bounds__(256) void k_match_insert_prev(MatchArgs a)
     const int64_t gid = a.prev_gid[j];
     bool fresh = false;
     if (gid >= 0) {
-        const uint32_t slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
+        const uint32_t slot = insert_id(a.table, (uint32_t)a.cap, gid, fresh);
         if (fresh) a.table[slot].val = (int32_t)j;
     }
     if (!fresh) atomicAdd(&a.result[1], 1);          // negative or repeated ID
@@ -64,7 +62,7 @@ __global__ __launch_bounds__(kScanBlock) void k_match_probe(MatchArgs a)
         const int64_t gid = a.new_gid[i];
         int32_t row = -1;
         if (gid >= 0) {
-            const int32_t slot = find_id(a.table, a.mask, a.shift, gid);
+            const int32_t slot = find_id(a.table, (uint32_t)a.cap, gid);
             if (slot != kNoSlot) row = a.table[slot].val;
         } else {
             atomicAdd(&a.result[1], 1);
@@ -123,8 +121,7 @@ struct OverlapArgs {
     int n;
     int64_t total;
     Slot *table;
-    uint32_t mask;
-    int shift;
+    int64_t cap;
     int32_t *slot_of;
     unsigned long long *counts;
     int32_t *violations;
@@ -148,7 +145,7 @@ __global__ __launch_bounds__(256) void k_overlap_insert(OverlapArgs a)
         return;
     }
     bool fresh;
-    const uint32_t slot = insert_id(a.table, a.mask, a.shift, gid, fresh);
+    const uint32_t slot = insert_id(a.table, (uint32_t)a.cap, gid, fresh);
     a.slot_of[p] = (int32_t)slot;
     const unsigned long long old = atomicOr(mask_of(&a.table[slot]), 1ull << b);
     if (old & (1ull << b)) atomicAdd(a.violations, 1);           // the mini-batch repeats this ID
@@ -265,8 +262,6 @@ fastgl_status fastgl_match(const int64_t *prev_gid, int64_t n_prev, const int64_
     a.prev_gid = prev_gid; a.new_gid = new_gid; a.n_prev = n_prev; a.n_new = n_new;
     a.table = (Slot *)((char *)workspace + L.table);
     a.cap = table_slots(n_prev);
-    a.mask = (uint32_t)(a.cap - 1);
-    a.shift = table_shift(a.cap);
     a.block_cnt = (int32_t *)((char *)workspace + L.block_cnt);
     a.nblocks = (int)ceil_div(n_new, kScanBlock);
     a.src_row = src_row; a.load_pos = load_pos; a.load_gid = load_gid; a.result = result;
@@ -386,8 +381,7 @@ fastgl_status fastgl_overlap_counts(const int64_t *gid, const int64_t *offsets_h
     for (int b = 0; b <= n; ++b) a.offsets[b] = offsets_host[b];
     a.table = (Slot *)((char *)workspace + L.table);
     const int64_t cap = table_slots(total);
-    a.mask = (uint32_t)(cap - 1);
-    a.shift = table_shift(cap);
+    a.cap = cap;
     a.slot_of = (int32_t *)((char *)workspace + L.slot_of);
     a.counts = (unsigned long long *)counts;
     a.violations = violations;

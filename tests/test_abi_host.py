@@ -143,10 +143,10 @@ def test_update_argument_checks():
 
 def test_idmap_argument_checks():
     L = B.lib()
-    assert B.fastgl_idmap_table_slots(0) == 1024 and B.fastgl_idmap_table_slots(600) == 2048
+    assert B.fastgl_idmap_table_slots(0) == 1024 and B.fastgl_idmap_table_slots(600) == 1024
     assert B.fastgl_idmap_table_slots(-1) == 0 and B.fastgl_idmap_table_slots(2 ** 30) == 0
     cap = B.fastgl_idmap_table_slots(3_000_000)
-    assert cap >= 6_000_000 and cap & (cap - 1) == 0
+    assert cap == 4_500_000                      # 1.5 slots per input ID: never full, whatever repeats
     assert B.fastgl_idmap_workspace_bytes(500_000, 2_500_000) >= 16 * cap + 4 * 3_000_000
     assert B.fastgl_idmap_workspace_bytes(-1, 5) == 0
     f = L.fastgl_idmap
@@ -164,9 +164,9 @@ def test_idmap_argument_checks():
 
 def test_match_argument_checks_and_host_reorder():
     L = B.lib()
-    assert B.fastgl_match_workspace_bytes(1000, 10) >= 16 * 2048
+    assert B.fastgl_match_workspace_bytes(1000, 10) >= 16 * 2000          # two slots per ID of the last mini-batch
     assert B.fastgl_match_workspace_bytes(-1, 10) == 0 and B.fastgl_overlap_workspace_bytes(-1) == 0
-    assert B.fastgl_overlap_workspace_bytes(1000) >= 16 * 2048 + 4000
+    assert B.fastgl_overlap_workspace_bytes(1000) >= 16 * 2000 + 4000
     m = L.fastgl_match
     assert m(FAKE, -1, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.FASTGL_ERR_INVALID_ARG
     assert m(FAKE, 2 ** 30, FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 40, None) == B.FASTGL_ERR_UNSUPPORTED
