@@ -216,6 +216,16 @@ def match_leg(args, w, B, bg, torch, np, with_cpu=False):
                        "assemble_hbm_frac_of_peak": round(asm_bytes / assemble_ms / 1e6 / HBM_PEAK_GBPS, 4),
                        "with_match_ms": round(match_ms + gather_load_ms + assemble_ms, 4),
                        "gather_every_row_ms": round(gather_all_ms, 4)},
+        # the bandwidth-bound kernel of this leg; the match and overlap kernels are bound by random
+        # accesses into the hash table (one 128-byte line per ID for 16 useful bytes), not by bytes
+        "roofline": {"bound": "hbm", "kernel": "k_assemble_rows (new feature matrix from reused and loaded rows)",
+                     "achieved": round(asm_bytes / assemble_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(asm_bytes / assemble_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "launch_ms": round(assemble_ms, 4), "algorithmic_bytes": int(asm_bytes)},
+        "match_lines_per_s": {"what": "hash-table lines touched per second by k_match_insert_prev + k_match_probe "
+                                      "(one 128-byte line per ID of either mini-batch)",
+                              "glines_per_s": round((sizes[a] + sizes[b]) / match_ms / 1e6, 3),
+                              "line_gbps": round((sizes[a] + sizes[b]) * 128 / match_ms / 1e6, 1)},
     }
 
 
@@ -435,7 +445,7 @@ def gcn_step_leg(args, w, layers, workspace, make_plans, B, torch, np, with_cpu=
     for _ in range(steps):
         step(record=True)
     torch.cuda.synchronize()
-    parts = {k: float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in ev.items()}
+    parts = {k: float(np.median([a.elapsed_time(b) for a, b in v])) for k, v in ev.items()}
     flops_fwd = [2.0 * p["M"] * p["K"] * p["N"] for p in P]
     flops = sum(flops_fwd) + sum(f * (2 if i > 0 else 1) for i, f in enumerate(flops_fwd))
     upd_ms = sum(v for k, v in parts.items() if k.startswith("upd"))
