@@ -1,8 +1,7 @@
 // Per-block integer bookkeeping on the GPU: degrees, scale factors, a stable
-// transpose of the CSR (LSD radix sort of the edges by source id), equal-work row
-// sets and degree buckets (ordered compaction of long rows).  Everything is integer work with
-// a single valid answer: no float atomics, no order-dependent results, and (on
-// the full-plan path) no global atomics at all.
+// transpose of the CSR, equal-work row sets and degree buckets (ordered compaction of
+// long rows).  Everything is integer work with a single valid answer: no float atomics,
+// no order-dependent results, and (on the full-plan path) no global atomics at all.
 //
 // Why it exists: the backward pass (paper Section 4.2, Eq. 5) gathers along
 // the reversed edges; pulling along a transposed CSR keeps one writer per
@@ -10,17 +9,24 @@
 // completed by one owner).  Every sampled block is new, so this work is part of
 // each iteration and is kept to a handful of launches.  The work of a plan is a
 // sequence of STAGES; stage k of every plan built in one call shares one launch
-// of k_plan_stage, whose workgroups look up which job they belong to:
+// of k_plan_stage, whose workgroups look up which job they belong to.
 //
-//   stage 0        digit histogram of pass 0    + destination-side row pass (degrees,
-//                  scale factors, edge -> row expansion, equal-work split, bucket counts)
-//   stage 1        stable scatter of pass 0     + destination-side bucket fill
-//   stage 2p,2p+1  histogram / scatter of radix pass p (8-bit digits)
-//   then           row starts (indptr_T from the sorted keys),
-//                  source-side row pass, source-side bucket fill
+// The transpose of a block with at most 2^21 source nodes (every sampled block of the
+// paper's workloads) is BUCKETED: the edges are split, in order, into buckets of 2 048
+// consecutive source ids, and a workgroup then finishes a bucket on chip.
 //
-// A full plan with a 3-pass sort is 9 launches, and so are the plans of all
-// layers of a mini-batch when they are built together.
+//   stage 0   bucket histogram per workgroup      + destination-side row pass (degrees,
+//             scale factors, edge -> row expansion, equal-work split, long-row counts)
+//   stage 1   column prefix of the histograms     + destination-side long-row fill
+//   stage 2   stable scatter of the edges into their buckets
+//   stage 3   per bucket (big ones: per sub-chunk of a bucket): out-degrees of its 2 048
+//             sources, their row starts (indptr_T), the source-side row pass, and the stable
+//             placement of its edges (indices_T, the edge permutation)
+//   stage 4   source-side long-row fill
+//
+// Five launches for the plans of all layers of a mini-batch.  Blocks with more source
+// nodes take an LSD radix sort of the edges by source id instead (8-bit digits:
+// histogram + scatter per pass, then row starts, row pass, fill: 9 launches at 3 passes).
 #include <vector>
 
 #include "internal.h"
@@ -63,11 +69,28 @@ __device__ __forceinline__ int block_excl_scan(int v, int *total, int *lds)
     return off + inc - v;
 }
 
-__device__ __forceinline__ int block_sum(int v, int *lds)
+// Block sums of two values at once.  `lds` needs 32 ints and is free again on return.
+__device__ __forceinline__ void block_sum2(int &a, int &b, int *lds)
 {
-    int tot;
-    block_excl_scan(v, &tot, lds);
-    return tot;
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave, nw = blockDim.x / kWave;
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        a += __shfl_xor(a, o, kWave);
+        b += __shfl_xor(b, o, kWave);
+    }
+    if (lane == 0) {
+        lds[w] = a;
+        lds[16 + w] = b;
+    }
+    __syncthreads();
+    int sa = 0, sb = 0;
+    for (int i = 0; i < nw; ++i) {
+        sa += lds[i];
+        sb += lds[16 + i];
+    }
+    __syncthreads();
+    a = sa;
+    b = sb;
 }
 
 // ---------------------------------------- degrees + long-row buckets (roles) ----
@@ -84,6 +107,49 @@ struct RowsArgs {
     int64_t nsets;
 };
 
+// What one row contributes: its length and scale factors, the long-row counts, and the
+// equal-work row sets that start right after it.  Called by every thread of a wavefront
+// together (rows that start many sets are written by the whole wavefront); valid = the
+// thread has a row.  e0 = first edge of row r, len = its length.
+__device__ __forceinline__ void row_emit(const RowsArgs &A, int64_t r, bool valid, int e0, int len, int &nl,
+                                         int &nc)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    if (valid) {
+        if (A.len_out) A.len_out[r] = len;
+        double d = (double)(len < 1 ? 1 : len);
+        if (A.inv) A.inv[r] = (float)(1.0 / d);
+        if (A.rsq) A.rsq[r] = (float)(1.0 / sqrt(d));
+        if (len > kLongThreshold) {
+            nl += 1;
+            nc += (len + kLongChunk - 1) / kLongChunk;
+        }
+    }
+    if (A.split) {
+        // Equal-work row sets: set g starts at the first row whose work prefix
+        // W[r] = rowptr[r] + r reaches g * kWorkPerGroup.  Row r+1 is that row for
+        // every g in (W[r]/work, W[r+1]/work]; the thread of row r writes them.
+        int64_t g0 = 1, g1 = 0;   // empty
+        if (valid) {
+            g0 = ((int64_t)e0 + r) / kWorkPerGroup + 1;
+            g1 = ((int64_t)e0 + len + r + 1) / kWorkPerGroup;
+            if (r == 0) A.split[0] = 0;
+            if (r == A.n - 1 && g1 < A.nsets) A.split[A.nsets] = (int32_t)A.n;   // partial last set
+        }
+        const bool big = g1 - g0 >= kWave;
+        if (!big)
+            for (int64_t g = g0; g <= g1; ++g) A.split[g] = (int32_t)(r + 1);
+        unsigned long long m = __ballot(big);
+        while (m) {
+            const int leader = __ffsll((long long)m) - 1;
+            const int64_t lg0 = __shfl(g0, leader, kWave), lg1 = __shfl(g1, leader, kWave);
+            const int64_t lr = __shfl(r, leader, kWave);
+            for (int64_t g = lg0 + lane; g <= lg1; g += kWave) A.split[g] = (int32_t)(lr + 1);
+            m &= m - 1;
+        }
+    }
+}
+
 // Pass 1 over row pointers: row lengths, scale factors, per-block counts of long
 // rows / their chunks, and (optionally) the row id of every edge.  A thread
 // expands its own short rows; rows longer than a wavefront are expanded by the
@@ -99,15 +165,8 @@ __device__ __forceinline__ void rows_count(const RowsArgs &A, int b, int *lds)
         if (r < end) {
             e0 = A.rowptr[r];
             len = A.rowptr[r + 1] - e0;
-            if (A.len_out) A.len_out[r] = len;
-            double d = (double)(len < 1 ? 1 : len);
-            if (A.inv) A.inv[r] = (float)(1.0 / d);
-            if (A.rsq) A.rsq[r] = (float)(1.0 / sqrt(d));
-            if (len > kLongThreshold) {
-                nl += 1;
-                nc += (len + kLongChunk - 1) / kLongChunk;
-            }
         }
+        row_emit(A, r, r < end, e0, len, nl, nc);
         if (A.edge_row) {
             const bool big = len > kWave;
             if (!big)
@@ -116,37 +175,13 @@ __device__ __forceinline__ void rows_count(const RowsArgs &A, int b, int *lds)
             while (m) {
                 const int leader = __ffsll((long long)m) - 1;
                 const int le0 = __shfl(e0, leader, kWave), ll = __shfl(len, leader, kWave);
-                const int lr = (int)(base - beg) + (threadIdx.x - lane) + leader;   // row offset in block
-                for (int k = lane; k < ll; k += kWave) A.edge_row[le0 + k] = (int32_t)(beg + lr);
-                m &= m - 1;
-            }
-        }
-        if (A.split) {
-            // Equal-work row sets: set g starts at the first row whose work prefix
-            // W[r] = rowptr[r] + r reaches g * kWorkPerGroup.  Row r+1 is that row for
-            // every g in (W[r]/work, W[r+1]/work]; the thread of row r writes them.
-            int64_t g0 = 1, g1 = 0;   // empty
-            if (r < end) {
-                g0 = ((int64_t)e0 + r) / kWorkPerGroup + 1;
-                g1 = ((int64_t)e0 + len + r + 1) / kWorkPerGroup;
-                if (r == 0) A.split[0] = 0;
-                if (r == A.n - 1 && g1 < A.nsets) A.split[A.nsets] = (int32_t)A.n;   // partial last set
-            }
-            const bool big = g1 - g0 >= kWave;
-            if (!big)
-                for (int64_t g = g0; g <= g1; ++g) A.split[g] = (int32_t)(r + 1);
-            unsigned long long m = __ballot(big);
-            while (m) {
-                const int leader = __ffsll((long long)m) - 1;
-                const int64_t lg0 = __shfl(g0, leader, kWave), lg1 = __shfl(g1, leader, kWave);
-                const int64_t lr = __shfl(r, leader, kWave);
-                for (int64_t g = lg0 + lane; g <= lg1; g += kWave) A.split[g] = (int32_t)(lr + 1);
+                const int lr = __shfl((int)r, leader, kWave);
+                for (int k = lane; k < ll; k += kWave) A.edge_row[le0 + k] = lr;
                 m &= m - 1;
             }
         }
     }
-    nl = block_sum(nl, lds);
-    nc = block_sum(nc, lds);
+    block_sum2(nl, nc, lds);
     if (threadIdx.x == 0) {
         A.counts[2 * b] = nl;
         A.counts[2 * b + 1] = nc;
@@ -157,17 +192,30 @@ __device__ __forceinline__ void rows_count(const RowsArgs &A, int b, int *lds)
 // the i-th long row; totals[0] = number of long rows, totals[1] = number of chunks.
 __device__ __forceinline__ void rows_fill(const RowsArgs &A, int b, int *lds)
 {
-    int pl = 0, pc = 0;
-    for (int i = threadIdx.x; i < A.nb; i += blockDim.x) {
-        if (i < b) {
-            pl += A.counts[2 * i];
-            pc += A.counts[2 * i + 1];
+    // long rows and chunks in the blocks before this one; the loads go out together (past the end
+    // they re-read the block's own pair)
+    const int2 *cnt = reinterpret_cast<const int2 *>(A.counts);
+    const int2 own = cnt[b];
+    int cl = 0, cc = 0;
+    constexpr int kBatch = 4;
+    for (int i0 = threadIdx.x; i0 < b; i0 += kBatch * blockDim.x) {
+        int2 v[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int i = i0 + u * (int)blockDim.x;
+            v[u] = cnt[i < b ? i : b];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (i0 + u * (int)blockDim.x < b) {
+                cl += v[u].x;
+                cc += v[u].y;
+            }
         }
     }
-    int cl = block_sum(pl, lds);
-    int cc = block_sum(pc, lds);
+    block_sum2(cl, cc, lds);
     int64_t beg = b * A.per, end = beg + A.per < A.n ? beg + A.per : A.n;
-    const bool any = A.counts[2 * b] != 0;      // block-uniform: most blocks have no long row
+    const bool any = own.x != 0;      // block-uniform: most blocks have no long row
     for (int64_t base = beg; any && base < end; base += blockDim.x) {
         int64_t r = base + threadIdx.x;
         int len = r < end ? A.rowptr[r + 1] - A.rowptr[r] : 0;
@@ -190,64 +238,205 @@ __device__ __forceinline__ void rows_fill(const RowsArgs &A, int b, int *lds)
     }
 }
 
-// ------------------------------------------------------------ radix sort ----
+// ------------------------------------ bucketed transpose: sizes, workgroup map ----
+constexpr int kBucketBits = 11;
+constexpr int kBucketIds = 1 << kBucketBits;
+constexpr int kMaxBuckets = 1024;                            // one thread per bucket in the scatter's prologue
+constexpr int kLocalThreads = 512;
+constexpr int kLocalWaves = kLocalThreads / kWave;
+constexpr int kSubRounds = 15;                               // rounds of 64 edges per wavefront
+constexpr int kSubChunk = kLocalWaves * kSubRounds * kWave;  // 7 680 edges; below 65 536: 16-bit counts
+constexpr int kLocalKeys = kBucketIds / kLocalThreads;       // sources per thread in the scans: 4 consecutive ones
+static_assert(kMaxBuckets <= kSortThreads && kMaxBuckets <= kMaxScanBlocks, "bucket prologue, fill pass");
+static_assert(kLocalKeys == 4, "a thread scans two words of the count table");
+static_assert(kSubChunk < 65536, "per-wavefront counts are 16 bits wide");
+
+struct BucketOfGroup {   // what workgroup g of k_plan_buckets works on
+    int bucket;          // -1: nothing
+    int sub;             // sub-chunk of the bucket
+    int first_edge;      // of the bucket
+    int edges;           // of the bucket
+};
+
+inline int64_t bucket_groups(int nbuckets, int64_t n) { return nbuckets + n / kSubChunk; }   // >= groups in use
+// >= groups of buckets with several sub-chunks: such a bucket of e > kSubChunk edges takes ceil(e / kSubChunk) < 2e / kSubChunk
+inline int64_t large_bucket_groups(int64_t n) { return n > kSubChunk ? 2 * n / kSubChunk + 1 : 0; }
+
+// Bucket d takes max(1, ceil(tot[d] / kSubChunk)) workgroups.  Those of the buckets with several
+// sub-chunks come first (they have the most to do, and workgroups start in this order), then one per
+// remaining bucket.  Written by one workgroup of the scatter launch (1024 threads: thread t = bucket
+// t; ex = first edge of bucket t).
+__device__ __forceinline__ void write_bucket_map(BucketOfGroup *map, int cap, int nbuckets, int tv, int ex, int *lds)
+{
+    const int t = threadIdx.x;
+    const int ns = t < nbuckets ? (tv > kSubChunk ? (tv + kSubChunk - 1) / kSubChunk : 1) : 0;
+    int large, small;
+    int wf = block_excl_scan(ns > 1 ? ns : 0, &large, lds);
+    const int ws = block_excl_scan(ns == 1 ? 1 : 0, &small, lds);
+    if (ns == 1) wf = large + ws;
+    for (int s = 0; s < ns; ++s) {
+        BucketOfGroup m;
+        m.bucket = t; m.sub = s; m.first_edge = ex; m.edges = tv;
+        if (wf + s < cap) map[wf + s] = m;
+    }
+    for (int i = large + small + t; i < cap; i += blockDim.x) map[i].bucket = -1;
+}
+
+// ------------------------------------------------- stable split by a digit ----
+// One stable counting pass over (source id, destination row[, edge id]) triples: a pass of the
+// LSD radix sort (digit = 8 bits of the key), or the split into buckets of kBucketIds consecutive
+// source ids of the bucketed transpose (digit = key >> kBucketBits: 8 or 10 bits).
 struct SortArgs {
     const int32_t *keys_in, *vals_in;   // vals: the destination row of the edge
-    int32_t *keys_out, *vals_out;       // keys_out == NULL: not needed (never on this path: row starts read them)
+    int32_t *keys_out, *vals_out;
     const int32_t *eid_in;              // second payload, the original edge id; NULL on the first pass = identity
     int32_t *eid_out;                   // NULL: the plan carries no edge permutation
     int64_t n, per;                     // block b owns keys [b*per, min(n,(b+1)*per))
     int nb, shift;
-    int32_t *cnt;                       // [nb][256] digit counts per block
+    int bits;                           // digit width: kRadixBits, or 10 for more than 256 buckets
+    int nbins;                          // digits that occur = row length of cnt
+    int32_t *cnt;                       // [nb][nbins] digit counts per block; after the column prefix of the
+                                        // bucketed transpose: keys of that digit in earlier blocks
+    const int32_t *tot;                 // bucketed transpose: [nbins] keys per digit; NULL: LSD pass
+    struct BucketOfGroup *map;          // bucketed transpose: [map_cap] which bucket each workgroup of the next
+    int map_cap;                        // stage finishes (written by workgroup 0)
     int items;                          // keys per thread and step: 1, 2 or 4
 };
 
-// Digit histogram of the block's key range.
-__device__ __forceinline__ void sort_hist(const SortArgs &S, int b, int *h)
+__device__ __forceinline__ int digit_of(const SortArgs &S, int32_t key) { return (key >> S.shift) & ((1 << S.bits) - 1); }
+
+// Lanes of the wavefront whose `bits`-bit value equals this lane's (lanes with ok == false match
+// nobody and nobody matches them).  One ballot per bit; lo / hi = the mask's halves.
+template <int BITS>
+__device__ __forceinline__ void match_lanes(int v, bool ok, unsigned &lo, unsigned &hi)
 {
-    if (threadIdx.x < kRadixBins) h[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t beg = b * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
-    for (int64_t i = beg + threadIdx.x; i < end; i += kSortThreads)
-        atomicAdd(&h[(S.keys_in[i] >> S.shift) & (kRadixBins - 1)], 1);
-    __syncthreads();
-    if (threadIdx.x < kRadixBins) S.cnt[(int64_t)b * kRadixBins + threadIdx.x] = h[threadIdx.x];
+    const unsigned long long act = __ballot(ok);
+    lo = (unsigned)act;
+    hi = (unsigned)(act >> 32);
+#pragma unroll
+    for (int bit = 0; bit < BITS; ++bit) {
+        const int neg = -((v >> bit) & 1);                 // all ones where the bit is set
+        const unsigned long long bl = __ballot(neg != 0);
+        lo &= ~((unsigned)bl ^ (unsigned)neg);             // keep the lanes that agree in this bit
+        hi &= ~((unsigned)(bl >> 32) ^ (unsigned)neg);
+    }
+    if (!ok) lo = hi = 0;
 }
 
-// Stable scatter of one digit.  Every workgroup derives its own output offsets
-// from the [nb][256] count table (no separate scan launch): for digit d,
-//   base = sum_{d' < d} total[d'] + sum_{b' < b} cnt[b'][d].
+__device__ __forceinline__ int lanes_below(unsigned lo, unsigned hi)   // set bits of the mask below this lane
+{
+    return (int)__builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+}
+
+// Digit histogram of the block's key range.  h: 1 << bits counters.
+__device__ __forceinline__ void sort_hist(const SortArgs &S, int b, int *h)
+{
+    for (int i = threadIdx.x; i < (1 << S.bits); i += kSortThreads) h[i] = 0;
+    __syncthreads();
+    const int64_t beg = b * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
+    constexpr int kBatch = 8;   // loads in flight per thread (past the end they re-read the last key)
+    for (int64_t i0 = beg + threadIdx.x; i0 < end; i0 += (int64_t)kBatch * kSortThreads) {
+        int32_t key[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int64_t i = i0 + (int64_t)u * kSortThreads;
+            key[u] = S.keys_in[i < end ? i : end - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u)
+            if (i0 + (int64_t)u * kSortThreads < end) atomicAdd(&h[digit_of(S, key[u])], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < S.nbins) S.cnt[(int64_t)b * S.nbins + threadIdx.x] = h[threadIdx.x];
+}
+
+// Bucketed transpose, between histogram and scatter: cnt[b][d] becomes the number of keys of digit
+// d in blocks before b, tot[d] the number in all blocks.  A workgroup takes 64 columns (one per
+// lane); each wavefront sums a strip of rows, then walks it again with its running prefix.
+struct ColScanArgs {
+    int32_t *cnt, *tot;
+    int nb, nbins;
+};
+
+__device__ __forceinline__ void col_scan(const ColScanArgs &A, int g, int *part)   // part: [kSortWaves][64]
+{
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const int c = g * kWave + lane;
+    const bool ok = c < A.nbins;
+    const int rp = (A.nb + kSortWaves - 1) / kSortWaves;
+    const int r0 = w * rp < A.nb ? w * rp : A.nb, r1 = r0 + rp < A.nb ? r0 + rp : A.nb;
+    int sum = 0;
+    if (ok) {
+#pragma unroll 4
+        for (int r = r0; r < r1; ++r) sum += A.cnt[(int64_t)r * A.nbins + c];
+    }
+    part[w * kWave + lane] = sum;
+    __syncthreads();
+    int base = 0, total = 0;
+#pragma unroll
+    for (int k = 0; k < kSortWaves; ++k) {
+        const int v = part[k * kWave + lane];
+        if (k < w) base += v;
+        total += v;
+    }
+    if (ok) {
+        if (w == 0) A.tot[c] = total;
+#pragma unroll 4
+        for (int r = r0; r < r1; ++r) {
+            int32_t *q = A.cnt + (int64_t)r * A.nbins + c;
+            const int v = *q;
+            *q = base;
+            base += v;
+        }
+    }
+}
+
+// Stable scatter by one digit.  Output offsets of the block's digits: for an LSD pass every
+// workgroup derives them from the [nb][256] count table (no separate scan launch),
+//   base = sum_{d' < d} total[d'] + sum_{b' < b} cnt[b'][d];
+// for the bucketed transpose the column prefix is already there and only tot[] is scanned.
 // Within a step of 1024*ITEMS keys each wavefront owns 64*ITEMS consecutive keys and ranks
-// them 64 at a time: lanes with equal digits find each other with 8 ballots, the
+// them 64 at a time: lanes with equal digits find each other with one ballot per digit bit, the
 // running per-wavefront digit counts live in LDS, and a column scan over the 16
 // wavefronts plus a scan over the digits give each key its place in the step's
 // sorted order.  The step is sorted into LDS first and written out from there.
 // The payload is the edge's destination row and, if asked for, its original id.
+template <int BITS>
 struct SortShared {
-    int running[kRadixBins], lbase[kRadixBins], gdelta[kRadixBins];
-    int wcnt[kSortWaves][kRadixBins];
+    static constexpr int kBins = 1 << BITS;
+    int running[kBins], lbase[kBins], gdelta[kBins];
+    int wcnt[kSortWaves][kBins];
     int32_t skey[kSortThreads * kMaxSortItems], sval[kSortThreads * kMaxSortItems];
     int32_t seid[kSortThreads * kMaxSortItems];
 };
 
-template <int ITEMS>
-__device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShared &M, int *lds)
+template <int ITEMS, int BITS>
+__device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShared<BITS> &M, int *lds)
 {
-    int (&running)[kRadixBins] = M.running, (&lbase)[kRadixBins] = M.lbase, (&gdelta)[kRadixBins] = M.gdelta;
-    int (&wcnt)[kSortWaves][kRadixBins] = M.wcnt;
+    constexpr int kBins = 1 << BITS;
+    static_assert(kBins <= kSortThreads, "one thread per digit");
+    int (&running)[kBins] = M.running, (&lbase)[kBins] = M.lbase, (&gdelta)[kBins] = M.gdelta;
+    int (&wcnt)[kSortWaves][kBins] = M.wcnt;
     int32_t *skey = M.skey, *sval = M.sval, *seid = M.seid;
     const bool EID = S.eid_out != nullptr;
     const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
-    {   // offsets of this block's digits
-        const int d = t & (kRadixBins - 1), part = t / kRadixBins;   // 4 parts share the blocks
+    if (S.tot) {   // bucketed transpose: start of the bucket + keys of it in earlier blocks
+        int dummy;
+        const int tv = t < S.nbins ? S.tot[t] : 0;
+        const int ex = block_excl_scan(tv, &dummy, lds);
+        if (t < kBins) running[t] = t < S.nbins ? ex + S.cnt[(int64_t)b * S.nbins + t] : 0;
+        if (b == 0) write_bucket_map(S.map, S.map_cap, S.nbins, tv, ex, lds);
+        __syncthreads();
+    } else if constexpr (BITS == kRadixBits) {   // LSD pass: offsets from the whole count table
+        const int d = t & (kBins - 1), part = t / kBins;   // 4 parts share the blocks
         int below = 0, total = 0;
-        constexpr int kParts = kSortThreads / kRadixBins, kBatch = 16;
+        constexpr int kParts = kSortThreads / kBins, kBatch = 16;
         for (int b0 = part; b0 < S.nb; b0 += kParts * kBatch) {
             int c[kBatch];
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {   // independent loads first
                 const int bb = b0 + k * kParts;
-                c[k] = bb < S.nb ? S.cnt[(int64_t)bb * kRadixBins + d] : 0;
+                c[k] = bb < S.nb ? S.cnt[(int64_t)bb * kBins + d] : 0;
             }
 #pragma unroll
             for (int k = 0; k < kBatch; ++k) {
@@ -259,7 +448,7 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
         wcnt[4 + part][d] = total;
         __syncthreads();
         int tot = 0, bel = 0;
-        if (t < kRadixBins) {
+        if (t < kBins) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 bel += wcnt[k][t];
@@ -267,14 +456,28 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
             }
         }
         int dummy;
-        int ex = block_excl_scan(t < kRadixBins ? tot : 0, &dummy, lds);   // threads >= 256 add 0 after the digits
-        if (t < kRadixBins) running[t] = ex + bel;
+        int ex = block_excl_scan(t < kBins ? tot : 0, &dummy, lds);   // threads >= 256 add 0 after the digits
+        if (t < kBins) running[t] = ex + bel;
         __syncthreads();
     }
     const int64_t beg = b * S.per, end = beg + S.per < S.n ? beg + S.per : S.n;
+    // the keys of a step are loaded while the step before it is worked on; the loads carry no
+    // branch of their own (past the end they re-read the last key), so they go out together
+    int32_t nkey[ITEMS], nval[ITEMS], neid[ITEMS];
+    auto load_step = [&](int64_t step) {
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int64_t idx = step + (int64_t)w * (kWave * ITEMS) + i * kWave + lane;
+            const int64_t at = idx < end ? idx : end - 1;
+            nkey[i] = S.keys_in[at];
+            nval[i] = S.vals_in[at];
+            neid[i] = EID ? (S.eid_in ? S.eid_in[at] : (int32_t)at) : 0;
+        }
+    };
+    if (beg < end) load_step(beg);
     for (int64_t step = beg; step < end; step += kSortThreads * ITEMS) {
 #pragma unroll
-        for (int k = 0; k < kSortWaves * kRadixBins / kSortThreads; ++k)
+        for (int k = 0; k < kSortWaves * kBins / kSortThreads; ++k)
             (&wcnt[0][0])[k * kSortThreads + t] = 0;
         __syncthreads();
         int32_t key[ITEMS], val[ITEMS], eid[ITEMS];
@@ -284,31 +487,27 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
         for (int i = 0; i < ITEMS; ++i) {
             const int64_t idx = step + (int64_t)w * (kWave * ITEMS) + i * kWave + lane;
             ok[i] = idx < end;
-            key[i] = ok[i] ? S.keys_in[idx] : 0;
-            val[i] = ok[i] ? S.vals_in[idx] : 0;
-            eid[i] = EID && ok[i] ? (S.eid_in ? S.eid_in[idx] : (int32_t)idx) : 0;
-            dig[i] = (key[i] >> S.shift) & (kRadixBins - 1);
+            key[i] = nkey[i];
+            val[i] = nval[i];
+            eid[i] = neid[i];
+            dig[i] = (key[i] >> S.shift) & (kBins - 1);
         }
+        if (step + kSortThreads * ITEMS < end) load_step(step + kSortThreads * ITEMS);
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            unsigned long long mask = __ballot(ok[i]);
-#pragma unroll
-            for (int bit = 0; bit < kRadixBits; ++bit) {
-                const bool one = (dig[i] >> bit) & 1;
-                const unsigned long long bl = __ballot(one);
-                mask &= one ? bl : ~bl;
-            }
-            const int lower = __popcll(mask & ((1ull << lane) - 1ull));
+            unsigned mlo, mhi;
+            match_lanes<BITS>(dig[i], ok[i], mlo, mhi);
+            const int lower = lanes_below(mlo, mhi);
             const int prior = ok[i] ? wcnt[w][dig[i]] : 0;   // count from this wavefront's earlier rounds
             rank[i] = prior + lower;
             // the LDS read above is issued before this write by the same wavefront
-            if (ok[i] && lower == 0) wcnt[w][dig[i]] = prior + __popcll(mask);
+            if (ok[i] && lower == 0) wcnt[w][dig[i]] = prior + __popc(mlo) + __popc(mhi);
         }
         __syncthreads();
         // column scan over the wavefronts, then a scan over the digits: position of
         // every key inside this step's sorted order
         int tot_t = 0;
-        if (t < kRadixBins) {
+        if (t < kBins) {
 #pragma unroll
             for (int k = 0; k < kSortWaves; ++k) {
                 int c = wcnt[k][t];
@@ -318,7 +517,7 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
         }
         int nvalid;
         const int lb = block_excl_scan(tot_t, &nvalid, lds);
-        if (t < kRadixBins) {
+        if (t < kBins) {
             lbase[t] = lb;
             gdelta[t] = running[t] - lb;   // global position = gdelta[digit] + position in the step
             running[t] += tot_t;
@@ -340,12 +539,228 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
             const int j = i * kSortThreads + t;
             if (j >= nvalid) continue;
             const int32_t k = skey[j], v = sval[j];
-            const int pos = gdelta[(k >> S.shift) & (kRadixBins - 1)] + j;
+            const int64_t pos = (int64_t)gdelta[(k >> S.shift) & (kBins - 1)] + j;
+            if (pos < 0 || pos >= S.n) continue;   // only a source id outside [0, num_src) gets here
             S.keys_out[pos] = k;
             S.vals_out[pos] = v;
             if (EID) S.eid_out[pos] = seid[j];
         }
         __syncthreads();   // wcnt and the staging arrays are reused by the next step
+    }
+}
+
+// ------------------------------------------- bucketed transpose: one bucket ----
+// The edges of bucket d (source ids [d * kBucketIds, (d+1) * kBucketIds), in their original
+// order) are finished by one workgroup of k_plan_buckets per sub-chunk of kSubChunk edges (most
+// buckets are one sub-chunk).  The workgroup places its sub-chunk: each wavefront owns a run of
+// consecutive edges and counts them per source (16-bit counters, two to a word), a column scan
+// over the wavefronts turns the counts into offsets and yields the sub-chunk's edges per source,
+// a scan over the sources gives the row starts, and a second walk ranks 64 edges at a time
+// (equal sources find each other with one ballot per id bit).  Edges of one source thus keep
+// their order: the transposed row lists its destination rows as a stable counting sort does.
+// A bucket of several sub-chunks is first counted per source outside the own sub-chunk (all of
+// it -> out-degrees and row starts; what precedes the sub-chunk -> where the own edges of a
+// source begin).  The first sub-chunk's workgroup also writes what belongs to the bucket's rows:
+// indptr_T, out-degrees, scale factors, row sets, long-row counts.
+struct LocalArgs {
+    const int32_t *keys, *vals, *eids;   // the bucketed edges: source id, destination row, edge id
+    const BucketOfGroup *map;
+    uint16_t *subcnt;                    // [large_groups][kBucketIds] edges per source of every sub-chunk of a bucket
+    int large_groups;                    // that has several (workgroups 0 .. of the map, at most this many)
+    int nbuckets;
+    int64_t n, num_src;
+    int32_t *indptr_T, *indices_T, *perm;   // perm NULL: not wanted (eids is not read then)
+    RowsArgs rows;                       // source-side row outputs; counts[] is per bucket
+};
+
+struct LocalShared {
+    int start[kBucketIds];                          // first edge (within the bucket) of a source's edges of this sub-chunk
+    unsigned tab[kLocalWaves][kBucketIds / 2];      // per wavefront and source: count, then offset (16 bits each); while
+                                                    // a large bucket is counted: edges elsewhere / before, per source
+};
+
+// This wavefront's run of the sub-chunk [c0, c1) of a bucket: seg consecutive edges per wavefront, a
+// multiple of 64 and at most kSubRounds * 64.
+__device__ __forceinline__ void wave_run(int c0, int c1, int w, int &s0, int &s1)
+{
+    const int len = c1 > c0 ? c1 - c0 : 0;
+    const int seg = ((len + kLocalThreads - 1) / kLocalThreads) * kWave;
+    s0 = c0 + w * seg < c1 ? c0 + w * seg : c1;
+    s1 = s0 + seg < c1 ? s0 + seg : c1;
+}
+
+// Local source ids (-1: no edge) of this lane's edges in the rounds of the run [s0, s1).  The loads
+// carry no branch of their own (past the end they re-read the last edge), so all of them are in
+// flight at once.
+__device__ __forceinline__ void load_run(const int32_t *keys, int s0, int s1, int32_t lo, int (&kk)[kSubRounds])
+{
+    const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int u = 0; u < kSubRounds; ++u) kk[u] = -1;
+    if (s1 > s0) {   // same for the whole wavefront
+        int32_t raw[kSubRounds];
+#pragma unroll
+        for (int u = 0; u < kSubRounds; ++u) {
+            const int i = s0 + u * kWave + lane;
+            raw[u] = keys[i < s1 ? i : s1 - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kSubRounds; ++u)
+            if (s0 + u * kWave + lane < s1) kk[u] = (raw[u] - lo) & (kBucketIds - 1);
+    }
+}
+
+// Edges per wavefront and source of the run whose local source ids are kk[] (-1: no edge), 16-bit
+// counts, two to a word; the table is zeroed first.
+__device__ __forceinline__ void count_run(const int (&kk)[kSubRounds], LocalShared &M)
+{
+    const int t = threadIdx.x, w = t / kWave;
+    uint4 *z = reinterpret_cast<uint4 *>(&M.tab[0][0]);
+#pragma unroll
+    for (int k = 0; k < (int)(sizeof(M.tab) / sizeof(uint4)) / kLocalThreads; ++k)
+        z[k * kLocalThreads + t] = make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kSubRounds; ++u)
+        if (kk[u] >= 0) atomicAdd(&M.tab[w][kk[u] >> 1], 1u << ((kk[u] & 1) * 16));
+    __syncthreads();
+}
+
+// Buckets with several sub-chunks, before they are finished: edges per source of every sub-chunk,
+// so that each sub-chunk's workgroup can add up what the others hold.
+__device__ __forceinline__ void bucket_count(const LocalArgs &L, int g, LocalShared &M)
+{
+    const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
+    if (g >= L.large_groups) return;
+    const BucketOfGroup m = L.map[g];
+    if (m.bucket < 0 || m.edges <= kSubChunk) return;   // same for every thread
+    const int32_t lo = m.bucket * kBucketIds;
+    const int c0 = m.sub * kSubChunk, c1 = c0 + kSubChunk < m.edges ? c0 + kSubChunk : m.edges;
+    const int32_t *keys = L.keys + m.first_edge;
+    int s0, s1;
+    wave_run(c0, c1, w, s0, s1);
+    int kk[kSubRounds];
+    load_run(keys, s0, s1, lo, kk);
+    count_run(kk, M);
+    unsigned run0 = 0, run1 = 0;   // sources 4t, 4t+1 and 4t+2, 4t+3: no carry, a sub-chunk has < 65 536 edges
+#pragma unroll
+    for (int k = 0; k < kLocalWaves; ++k) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(&M.tab[k][2 * t]);
+        run0 += v.x;
+        run1 += v.y;
+    }
+    reinterpret_cast<uint2 *>(L.subcnt + (size_t)g * kBucketIds)[t] = make_uint2(run0, run1);
+}
+
+__device__ __forceinline__ void bucket_finish(const LocalArgs &L, int g, LocalShared &M, int *lds)
+{
+    const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
+    const BucketOfGroup m = L.map[g];
+    if (m.bucket < 0) return;   // same for every thread
+    const int d = m.bucket, sub = m.sub, nbk = m.edges;
+    const int64_t B0 = m.first_edge;
+    const int32_t lo = d * kBucketIds;
+    const int c0 = sub * kSubChunk, c1 = c0 + kSubChunk < nbk ? c0 + kSubChunk : nbk;
+    const int32_t *keys = L.keys + B0, *vals = L.vals + B0, *eids = L.eids + B0;
+    // this wavefront's run of the sub-chunk: rounds of 64 consecutive edges, all loaded up front
+    int s0, s1;
+    wave_run(c0, c1, w, s0, s1);
+    int kk[kSubRounds];
+    int32_t vv[kSubRounds];
+    load_run(keys, s0, s1, lo, kk);
+    if (s1 > s0) {   // in flight while the sub-chunk is counted
+#pragma unroll
+        for (int u = 0; u < kSubRounds; ++u) {
+            const int i = s0 + u * kWave + lane;
+            vv[u] = vals[i < s1 ? i : s1 - 1];
+        }
+    }
+    int other[kLocalKeys] = {0, 0, 0, 0}, before[kLocalKeys] = {0, 0, 0, 0};
+    if (nbk > kSubChunk && g < L.large_groups) {   // edges of the bucket's other sub-chunks, per source
+        const int nsub = (nbk + kSubChunk - 1) / kSubChunk;
+        const uint2 *c = reinterpret_cast<const uint2 *>(L.subcnt + (size_t)(g - sub) * kBucketIds) + t;
+#pragma unroll 4
+        for (int j = 0; j < nsub; ++j) {
+            const uint2 v = c[(size_t)j * (kBucketIds / 4)];
+            const int x[kLocalKeys] = {(int)(v.x & 0xFFFFu), (int)(v.x >> 16), (int)(v.y & 0xFFFFu), (int)(v.y >> 16)};
+#pragma unroll
+            for (int k = 0; k < kLocalKeys; ++k) {
+                if (j != sub) other[k] += x[k];
+                if (j < sub) before[k] += x[k];
+            }
+        }
+    }
+    count_run(kk, M);
+    // column scan over the wavefronts, both halves of a word at once (no carry: len < 65 536); the
+    // totals are the sub-chunk's edges of sources 4t .. 4t+3
+    unsigned run0 = 0, run1 = 0;
+#pragma unroll
+    for (int k = 0; k < kLocalWaves; ++k) {
+        uint2 *q = reinterpret_cast<uint2 *>(&M.tab[k][2 * t]);
+        const uint2 v = *q;
+        *q = make_uint2(run0, run1);
+        run0 += v.x;
+        run1 += v.y;
+    }
+    int cnt[kLocalKeys];
+    cnt[0] = (int)(run0 & 0xFFFFu) + other[0];
+    cnt[1] = (int)(run0 >> 16) + other[1];
+    cnt[2] = (int)(run1 & 0xFFFFu) + other[2];
+    cnt[3] = (int)(run1 >> 16) + other[3];
+    int dummy;
+    int e0[kLocalKeys];
+    e0[0] = block_excl_scan(cnt[0] + cnt[1] + cnt[2] + cnt[3], &dummy, lds);
+#pragma unroll
+    for (int k = 1; k < kLocalKeys; ++k) e0[k] = e0[k - 1] + cnt[k - 1];
+#pragma unroll
+    for (int k = 0; k < kLocalKeys; ++k) M.start[kLocalKeys * t + k] = e0[k] + before[k];
+    __syncthreads();
+    // place: rank the 64 edges of a round among each other, add what this wavefront placed of the
+    // source in earlier rounds and what earlier wavefronts hold
+#pragma unroll
+    for (int u = 0; u < kSubRounds; ++u) {
+        if (s0 + u * kWave >= s1) break;   // same for the whole wavefront
+        const bool ok = kk[u] >= 0;
+        const int k = ok ? kk[u] : 0;
+        unsigned mlo, mhi;
+        match_lanes<kBucketBits>(k, ok, mlo, mhi);
+        const int lower = lanes_below(mlo, mhi);
+        const int sh = (k & 1) * 16;
+        const int prior = (int)((M.tab[w][k >> 1] >> sh) & 0xFFFFu);
+        // the LDS read above is issued before this update by the same wavefront
+        if (ok && lower == 0) atomicAdd(&M.tab[w][k >> 1], (unsigned)(__popc(mlo) + __popc(mhi)) << sh);
+        const int64_t pos = B0 + M.start[k] + prior + lower;
+        const bool put = ok && pos < L.n;
+        if (put) L.indices_T[pos] = vv[u];
+        vv[u] = put ? (int32_t)pos : -1;   // the edge's place, for its id below
+    }
+    if (L.perm) {   // the edge ids go to the same places
+        int32_t ee[kSubRounds];
+#pragma unroll
+        for (int u = 0; u < kSubRounds; ++u) {
+            if (kk[u] < 0) vv[u] = -1;   // rounds past the end of the run were not placed
+            const int i = s0 + u * kWave + lane;
+            ee[u] = s1 > s0 ? eids[i < s1 ? i : s1 - 1] : 0;   // no branch per load: they all go out together
+        }
+#pragma unroll
+        for (int u = 0; u < kSubRounds; ++u)
+            if (vv[u] >= 0) L.perm[vv[u]] = ee[u];
+    }
+    if (sub == 0) {   // the bucket's rows
+        int nl = 0, nc = 0;
+#pragma unroll
+        for (int k = 0; k < kLocalKeys; ++k) {
+            const int64_t r = (int64_t)lo + kLocalKeys * t + k;
+            const bool valid = r < L.num_src;
+            if (valid) L.indptr_T[r] = (int32_t)(B0 + e0[k]);
+            row_emit(L.rows, r, valid, (int)(B0 + e0[k]), cnt[k], nl, nc);
+        }
+        if (d == L.nbuckets - 1 && t == 0) L.indptr_T[L.num_src] = (int32_t)L.n;
+        block_sum2(nl, nc, lds);
+        if (t == 0) {
+            L.rows.counts[2 * d] = nl;
+            L.rows.counts[2 * d + 1] = nc;
+        }
     }
 }
 
@@ -385,7 +800,10 @@ __device__ __forceinline__ void row_starts(const StartsArgs &A, int b)
 }
 
 // ------------------------------------------------------- the stage kernel ----
-enum { JOB_ROWS_COUNT = 0, JOB_ROWS_FILL = 1, JOB_SORT_HIST = 2, JOB_SORT_SCATTER = 3, JOB_ROW_STARTS = 4 };
+enum {
+    JOB_ROWS_COUNT = 0, JOB_ROWS_FILL = 1, JOB_SORT_HIST = 2, JOB_SORT_SCATTER = 3, JOB_ROW_STARTS = 4,
+    JOB_COL_SCAN = 5
+};
 constexpr int kMaxJobs = 16;
 
 struct Job {
@@ -394,6 +812,7 @@ struct Job {
         RowsArgs rows;
         SortArgs sort;
         StartsArgs starts;
+        ColScanArgs cols;
     };
 };
 
@@ -403,10 +822,31 @@ struct StageArgs {
     Job job[kMaxJobs];
 };
 
+// LDS a job's workgroups use (the launch reserves the largest of its jobs).
+static size_t job_lds_bytes(const Job &j)
+{
+    switch (j.kind) {
+        case JOB_SORT_HIST: return sizeof(int) << j.sort.bits;
+        case JOB_SORT_SCATTER: return j.sort.bits == kRadixBits ? sizeof(SortShared<kRadixBits>) : sizeof(SortShared<10>);
+        case JOB_COL_SCAN: return sizeof(int) * kSortWaves * kWave;
+        default: return 0;
+    }
+}
+constexpr size_t kMaxStageLds = sizeof(SortShared<10>);
+
+template <int BITS>
+__device__ __forceinline__ void sort_scatter_any(const SortArgs &S, int b, unsigned char *dyn, int *lds)
+{
+    SortShared<BITS> &M = *reinterpret_cast<SortShared<BITS> *>(dyn);
+    if (S.items == 1) sort_scatter<1, BITS>(S, b, M, lds);
+    else if (S.items == 2) sort_scatter<2, BITS>(S, b, M, lds);
+    else sort_scatter<4, BITS>(S, b, M, lds);
+}
+
 __global__ __launch_bounds__(kSortThreads) void k_plan_stage(StageArgs A)
 {
-    __shared__ SortShared M;
-    __shared__ int lds[16];
+    extern __shared__ __align__(16) unsigned char dyn[];
+    __shared__ int lds[32];
     int j = 0;
     while (j + 1 < A.njobs && (int)blockIdx.x >= A.first[j + 1]) ++j;
     const int b = blockIdx.x - A.first[j];
@@ -414,14 +854,39 @@ __global__ __launch_bounds__(kSortThreads) void k_plan_stage(StageArgs A)
     switch (J.kind) {
         case JOB_ROWS_COUNT: rows_count(J.rows, b, lds); break;
         case JOB_ROWS_FILL: rows_fill(J.rows, b, lds); break;
-        case JOB_SORT_HIST: sort_hist(J.sort, b, M.running); break;
+        case JOB_SORT_HIST: sort_hist(J.sort, b, reinterpret_cast<int *>(dyn)); break;
         case JOB_SORT_SCATTER:
-            if (J.sort.items == 1) sort_scatter<1>(J.sort, b, M, lds);
-            else if (J.sort.items == 2) sort_scatter<2>(J.sort, b, M, lds);
-            else sort_scatter<4>(J.sort, b, M, lds);
+            if (J.sort.bits == kRadixBits) sort_scatter_any<kRadixBits>(J.sort, b, dyn, lds);
+            else sort_scatter_any<10>(J.sort, b, dyn, lds);
             break;
+        case JOB_COL_SCAN: col_scan(J.cols, b, reinterpret_cast<int *>(dyn)); break;
         default: row_starts(J.starts, b); break;
     }
+}
+
+// The buckets of every bucketed transpose of a stage: smaller workgroups than k_plan_stage's, three
+// to a compute unit, so that (nearly) all buckets of a mini-batch are in flight at once.
+struct BucketStageArgs {
+    int njobs;
+    int first[kMaxJobs + 1];
+    LocalArgs job[kMaxJobs];
+};
+
+__global__ __launch_bounds__(kLocalThreads, 6) void k_plan_bucket_counts(BucketStageArgs A)
+{
+    __shared__ LocalShared M;
+    int j = 0;
+    while (j + 1 < A.njobs && (int)blockIdx.x >= A.first[j + 1]) ++j;
+    bucket_count(A.job[j], blockIdx.x - A.first[j], M);
+}
+
+__global__ __launch_bounds__(kLocalThreads, 6) void k_plan_buckets(BucketStageArgs A)
+{
+    __shared__ LocalShared M;
+    __shared__ int lds[32];
+    int j = 0;
+    while (j + 1 < A.njobs && (int)blockIdx.x >= A.first[j + 1]) ++j;
+    bucket_finish(A.job[j], blockIdx.x - A.first[j], M, lds);
 }
 
 // --------------------------------------- forward-only GCN: out-degree histogram ----
@@ -482,7 +947,7 @@ static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, fl
                           int32_t *edge_row, int32_t *split, int64_t nnz)
 {
     RowsArgs A;
-    int64_t b = ceil_div(n, (int64_t)kSortThreads * 4);
+    int64_t b = ceil_div(n, (int64_t)kSortThreads);   // one row per thread while that gives at most kMaxScanBlocks blocks
     if (b < 1) b = 1;
     if (b > kMaxScanBlocks) b = kMaxScanBlocks;
     A.rowptr = rowptr; A.n = n; A.nb = (int)b;
@@ -493,6 +958,36 @@ static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, fl
     A.split = split;
     A.nsets = num_row_sets(n, nnz);
     return A;
+}
+
+// How the edges of a transpose are cut into workgroups, and which transpose is taken.
+struct SortGeom {
+    int items;        // keys per thread and step
+    int64_t per;      // keys per workgroup (a multiple of the step)
+    int nb;           // workgroups
+    bool bucketed;    // bucketed transpose (else LSD radix sort)
+    int nbuckets;     // bucketed: buckets of kBucketIds source ids
+    int bits;         // bucketed: digit width of the split
+};
+
+// keys_per_group: 0, or how many keys a workgroup should take at least (plans built together share
+// the compute units: see plans_build); the count table is laid out for keys_per_group == 0.
+static SortGeom sort_geom(int64_t num_src, int64_t n, int64_t keys_per_group = 0)
+{
+    SortGeom g;
+    // one step per workgroup when the keys fit 256 workgroups x 4 keys per thread
+    int64_t want = ceil_div(n, (int64_t)kMaxSortBlocks);
+    if (want < keys_per_group) want = keys_per_group;
+    g.items = 1;
+    while (g.items < kMaxSortItems && (int64_t)g.items * kSortThreads < want) g.items <<= 1;
+    const int64_t step = (int64_t)g.items * kSortThreads;
+    g.per = ceil_div(want, step) * step;
+    if (g.per < step) g.per = step;
+    g.nb = n > 0 ? (int)ceil_div(n, g.per) : 1;
+    g.bucketed = num_src <= (int64_t)kMaxBuckets * kBucketIds;
+    g.nbuckets = g.bucketed ? (int)(num_src > 0 ? ceil_div(num_src, (int64_t)kBucketIds) : 1) : 0;
+    g.bits = g.nbuckets <= kRadixBins ? kRadixBits : 10;
+    return g;
 }
 
 size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src, int64_t num_edges,
@@ -527,19 +1022,37 @@ size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src,
     q->counters = (int32_t *)take(4 * 4);
     for (int i = 0; i < 6; ++i) q->sort_buf[i] = (int32_t *)take_bwd(4 * (size_t)num_edges);
     q->edge_dst = (int32_t *)take_bwd(4 * (size_t)num_edges);
-    q->radix_cnt = (int32_t *)take_bwd(4 * (size_t)kRadixBins * kMaxSortBlocks);
+    const SortGeom sg = sort_geom(num_src, num_edges);
+    q->radix_cnt = (int32_t *)take_bwd(4 * (size_t)sg.nb * (sg.bucketed ? sg.nbuckets : kRadixBins));
+    q->bucket_tot = (int32_t *)take_bwd(4 * (size_t)kMaxBuckets);
+    q->bucket_map = take_bwd(sg.bucketed ? sizeof(BucketOfGroup) * (size_t)bucket_groups(sg.nbuckets, num_edges) : 0);
+    q->bucket_subcnt = take_bwd(sg.bucketed ? sizeof(uint16_t) * kBucketIds * (size_t)large_bucket_groups(num_edges) : 0);
     q->block_sums = (int32_t *)take(4 * 2 * (size_t)kMaxScanBlocks);
     q->block_sums2 = (int32_t *)take_bwd(4 * 2 * (size_t)kMaxScanBlocks);
     return off;
 }
 
 // ---- stages ----------------------------------------------------------------
-using Stages = std::vector<std::vector<Job>>;
+struct BucketJob {
+    LocalArgs args;
+    int nblocks;
+};
+struct Stage {
+    std::vector<Job> jobs;            // workgroups of k_plan_stage
+    std::vector<BucketJob> buckets;   // workgroups of k_plan_buckets
+};
+using Stages = std::vector<Stage>;
 
 static void add_job(Stages &st, size_t k, const Job &j)
 {
     if (st.size() <= k) st.resize(k + 1);
-    st[k].push_back(j);
+    st[k].jobs.push_back(j);
+}
+
+static void add_buckets(Stages &st, size_t k, const BucketJob &j)
+{
+    if (st.size() <= k) st.resize(k + 1);
+    st[k].buckets.push_back(j);
 }
 
 static Job rows_job(int kind, const RowsArgs &A)
@@ -551,7 +1064,7 @@ static Job rows_job(int kind, const RowsArgs &A)
 
 // Append the jobs of one plan.  Stage k of a plan only depends on its own
 // earlier stages, so plans of different depth can share launches.
-static void plan_stages(fastgl_plan *p, int parts, Stages &st)
+static void plan_stages(fastgl_plan *p, int parts, Stages &st, int64_t keys_per_group)
 {
     p->parts = parts;
     const bool full = (parts & FASTGL_PLAN_BWD) != 0;
@@ -565,22 +1078,60 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
     if (!full) return;
 
     const int64_t n = p->num_edges;
+    const bool want_perm = (parts & FASTGL_PLAN_PERM) != 0;
+    const SortGeom sg = sort_geom(p->num_src, n, keys_per_group);
+    SortArgs S;
+    S.n = n;
+    S.items = sg.items;
+    S.per = sg.per;
+    S.nb = sg.nb;
+    S.cnt = p->radix_cnt;
+    RowsArgs srcA = rows_args(p->indptr_T, p->num_src, p->dout, nullptr, p->src_rsqrt, p->block_sums2,
+                              p->long_src, p->chunk_ptr_src, p->counters + 2, nullptr, p->split_src,
+                              p->num_edges);
+    if (sg.bucketed) {
+        S.keys_in = p->indices; S.vals_in = p->edge_dst; S.eid_in = nullptr;
+        S.keys_out = p->sort_buf[0]; S.vals_out = p->sort_buf[1];
+        S.eid_out = want_perm ? p->sort_buf[2] : nullptr;
+        S.shift = kBucketBits; S.bits = sg.bits; S.nbins = sg.nbuckets;
+        S.tot = p->bucket_tot;
+        S.map = reinterpret_cast<BucketOfGroup *>(p->bucket_map);
+        S.map_cap = (int)bucket_groups(sg.nbuckets, n);
+        Job j;
+        j.nblocks = S.nb; j.sort = S;
+        j.kind = JOB_SORT_HIST;
+        add_job(st, 0, j);
+        j.kind = JOB_SORT_SCATTER;
+        add_job(st, 2, j);
+        Job c;
+        c.kind = JOB_COL_SCAN;
+        c.cols.cnt = p->radix_cnt; c.cols.tot = p->bucket_tot; c.cols.nb = S.nb; c.cols.nbins = sg.nbuckets;
+        c.nblocks = (int)ceil_div(sg.nbuckets, kWave);
+        add_job(st, 1, c);
+        // the source-side row pass runs per bucket; the fill pass then sees buckets as its blocks
+        srcA.per = kBucketIds;
+        srcA.nb = sg.nbuckets;
+        BucketJob f;
+        f.args.keys = S.keys_out; f.args.vals = S.vals_out; f.args.eids = S.eid_out;
+        f.args.map = reinterpret_cast<const BucketOfGroup *>(p->bucket_map); f.args.nbuckets = sg.nbuckets;
+        f.args.subcnt = reinterpret_cast<uint16_t *>(p->bucket_subcnt);
+        // no more than the map holds: workgroups past the map's end must not read it
+        f.args.large_groups = (int)(large_bucket_groups(n) < bucket_groups(sg.nbuckets, n) ? large_bucket_groups(n)
+                                                                                          : bucket_groups(sg.nbuckets, n));
+        f.args.n = n; f.args.num_src = p->num_src;
+        f.args.indptr_T = p->indptr_T; f.args.indices_T = p->indices_T;
+        f.args.perm = want_perm ? p->perm : nullptr;
+        f.args.rows = srcA;
+        f.nblocks = (int)bucket_groups(sg.nbuckets, n);
+        add_buckets(st, 3, f);
+        add_job(st, 4, rows_job(JOB_ROWS_FILL, srcA));
+        return;
+    }
+
     int bits = 1;
     while (bits < 31 && ((int64_t)1 << bits) < p->num_src) ++bits;
     const int npass = (bits + kRadixBits - 1) / kRadixBits;
-    SortArgs S;
-    S.n = n;
-    // one step per workgroup when the keys fit 256 workgroups x 4 keys per thread
-    int items = 1;
-    while (items < kMaxSortItems && (int64_t)items * kSortThreads * kMaxSortBlocks < n) items <<= 1;
-    const int64_t step = (int64_t)items * kSortThreads;
-    int64_t per = ceil_div(ceil_div(n, (int64_t)kMaxSortBlocks), step) * step;
-    if (per < step) per = step;
-    S.items = items;
-    S.per = per;
-    S.nb = n > 0 ? (int)ceil_div(n, per) : 1;
-    S.cnt = p->radix_cnt;
-    const bool want_perm = (parts & FASTGL_PLAN_PERM) != 0;
+    S.bits = kRadixBits; S.nbins = kRadixBins; S.tot = nullptr; S.map = nullptr; S.map_cap = 0;
     const int32_t *kin = p->indices, *vin = p->edge_dst, *ein = nullptr;
     for (int pass = 0; pass < npass; ++pass) {
         const bool last = pass == npass - 1;
@@ -605,28 +1156,63 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st)
     if (nb > 1024) nb = 1024;
     t.starts.nb = (int)nb; t.nblocks = (int)nb;
     add_job(st, 2 * npass, t);
-    RowsArgs srcA = rows_args(p->indptr_T, p->num_src, p->dout, nullptr, p->src_rsqrt, p->block_sums2,
-                              p->long_src, p->chunk_ptr_src, p->counters + 2, nullptr, p->split_src,
-                              p->num_edges);
     add_job(st, 2 * npass + 1, rows_job(JOB_ROWS_COUNT, srcA));
     add_job(st, 2 * npass + 2, rows_job(JOB_ROWS_FILL, srcA));
 }
 
 static fastgl_status run_stages(const Stages &st, hipStream_t s)
 {
-    for (const auto &jobs : st) {
+    static_assert(sizeof(StageArgs) <= 4096 && sizeof(BucketStageArgs) <= 4096, "kernel arguments are passed by value");
+    static bool raised = false;   // benign if two threads both do it
+    if (!raised) {   // the split into more than 256 buckets takes more LDS than a launch gets by default
+        FASTGL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_plan_stage),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStageLds));
+        raised = true;
+    }
+    for (const Stage &stage : st) {
+        const auto &jobs = stage.jobs;
         for (size_t at = 0; at < jobs.size(); at += kMaxJobs) {
             StageArgs A;
             A.njobs = (int)(jobs.size() - at < (size_t)kMaxJobs ? jobs.size() - at : kMaxJobs);
             int blocks = 0;
+            size_t lds = 0;
             for (int i = 0; i < A.njobs; ++i) {
                 A.first[i] = blocks;
                 A.job[i] = jobs[at + i];
                 blocks += A.job[i].nblocks;
+                const size_t need = job_lds_bytes(A.job[i]);
+                if (need > lds) lds = need;
             }
             A.first[A.njobs] = blocks;
-            hipLaunchKernelGGL(k_plan_stage, dim3(blocks), dim3(kSortThreads), 0, s, A);
+            // a stage of fill passes only: most of its workgroups find nothing to do, small ones start faster
+            bool fills_only = true;
+            for (int i = 0; i < A.njobs; ++i) fills_only = fills_only && A.job[i].kind == JOB_ROWS_FILL;
+            hipLaunchKernelGGL(k_plan_stage, dim3(blocks), dim3(fills_only ? kBlock : kSortThreads), lds, s, A);
             FASTGL_LAUNCH_CHECK("k_plan_stage");
+        }
+        const auto &bk = stage.buckets;
+        for (size_t at = 0; at < bk.size(); at += kMaxJobs) {
+            BucketStageArgs A;
+            A.njobs = (int)(bk.size() - at < (size_t)kMaxJobs ? bk.size() - at : kMaxJobs);
+            int blocks = 0;   // first the per-source counts of the sub-chunks of large buckets (if there can be any)
+            for (int i = 0; i < A.njobs; ++i) {
+                A.first[i] = blocks;
+                A.job[i] = bk[at + i].args;
+                blocks += A.job[i].large_groups;
+            }
+            A.first[A.njobs] = blocks;
+            if (blocks > 0) {
+                hipLaunchKernelGGL(k_plan_bucket_counts, dim3(blocks), dim3(kLocalThreads), 0, s, A);
+                FASTGL_LAUNCH_CHECK("k_plan_bucket_counts");
+            }
+            blocks = 0;
+            for (int i = 0; i < A.njobs; ++i) {
+                A.first[i] = blocks;
+                blocks += bk[at + i].nblocks;
+            }
+            A.first[A.njobs] = blocks;
+            hipLaunchKernelGGL(k_plan_buckets, dim3(blocks), dim3(kLocalThreads), 0, s, A);
+            FASTGL_LAUNCH_CHECK("k_plan_buckets");
         }
     }
     return FASTGL_OK;
@@ -652,8 +1238,14 @@ static fastgl_status src_degrees(fastgl_plan *p, hipStream_t s)
 // plan for dout / src_rsqrt as well (GCN).
 fastgl_status plans_build(fastgl_plan *const *plans, const int *parts, const bool *src_deg, int n, hipStream_t s)
 {
+    // The split of the edges runs one 1024-thread workgroup per compute unit: the transposes of a
+    // call share the (256) compute units, each workgroup taking about the same number of edges.
+    int64_t edges = 0;
+    for (int i = 0; i < n; ++i)
+        if (parts[i] & FASTGL_PLAN_BWD) edges += plans[i]->num_edges;
+    const int64_t keys_per_group = ceil_div(edges, (int64_t)kMaxSortBlocks);
     Stages st;
-    for (int i = 0; i < n; ++i) plan_stages(plans[i], parts[i], st);
+    for (int i = 0; i < n; ++i) plan_stages(plans[i], parts[i], st, keys_per_group);
     fastgl_status rc = run_stages(st, s);
     if (rc != FASTGL_OK) return rc;
     for (int i = 0; i < n; ++i)

@@ -57,7 +57,10 @@ struct fastgl_plan {
     // scratch
     int32_t *sort_buf[6];   // ping-pong keys / destination rows / edge ids, num_edges each
     int32_t *edge_dst;      // [num_edges] destination row of every edge
-    int32_t *radix_cnt;     // [sort blocks][kRadixBins]
+    int32_t *radix_cnt;     // [sort blocks][digits]: digit counts of a sort pass / of the split into buckets
+    int32_t *bucket_tot;    // [buckets] edges per bucket of the bucketed transpose
+    void *bucket_map;       // which bucket (and part of it) each workgroup of the bucket stage finishes
+    void *bucket_subcnt;    // edges per source of the parts of buckets that are finished in several parts
     int32_t *block_sums;    // 2 * kMaxScanBlocks (destination-side bucket counts)
     int32_t *block_sums2;   // same for the source side
 };

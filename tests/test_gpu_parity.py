@@ -125,14 +125,26 @@ def test_bookkeeping_bit_exact_small():
     rng = np.random.default_rng(31)
     check_bookkeeping(ragged_block(), "ragged")
     check_bookkeeping(bg.random_block(rng, 9, 17, 0.0, empty_frac=1.0), "no-edges")
-    check_bookkeeping(bg.random_block(rng, 70000, 300, 3.0), "few-sources")          # one radix pass... two
+    check_bookkeeping(bg.random_block(rng, 70000, 300, 3.0), "few-sources")          # one bucket, several sub-chunks
+    check_bookkeeping(bg.random_block(rng, 20000, 5000, 12.0), "three-buckets")      # each of them in sub-chunks
+    check_bookkeeping(bg.random_block(rng, 2000, 600_000, 100.0), "ten-bit-split")   # more than 256 buckets
+    check_bookkeeping(bg.random_block(rng, 5000, 2_097_152, 30.0), "most-buckets")   # 1024 buckets, the last one full
+    check_bookkeeping(bg.random_block(rng, 5000, 2_097_153, 30.0), "one-source-more")  # first size of the radix sort
     check_bookkeeping(bg.random_block(rng, 300, 70000, 40.0, hub_rows=2, hub_deg=9000), "many-sources")
     check_bookkeeping(bg.make_config(1).blocks[0], "config1")
     check_bookkeeping(bg.random_block(rng, 50, 200, 30.0), "one-radix-pass")
-    # four radix passes, long runs of sources without edges, a run longer than a wavefront
+    # radix sort of the edges, four passes: long runs of sources without edges, a run longer than a wavefront
     big = bg.random_block(rng, 4000, 17_000_000, 25.0, hub_rows=1, hub_deg=3000)
     big.indices[big.indices > 9_000_000] = 16_999_999
     check_bookkeeping(big, "sparse-id-space")
+
+
+def test_bookkeeping_bit_exact_full_size():
+    """Plans of the products-shaped mini-batch and of the skew stress block: buckets of the transpose from
+    a few hundred to 700 000 edges."""
+    for cfg in (2, 5):
+        for i, blk in enumerate(bg.make_config(cfg).blocks):
+            check_bookkeeping(blk, f"config{cfg}-block{i}")
 
 
 def test_batched_plans_match_single_plans():
