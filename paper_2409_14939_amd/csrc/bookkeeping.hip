@@ -19,14 +19,19 @@
 //             scale factors, edge -> row expansion, equal-work split, long-row counts)
 //   stage 1   column prefix of the histograms     + destination-side long-row fill
 //   stage 2   stable scatter of the edges into their buckets
-//   stage 3   per bucket (big ones: per sub-chunk of a bucket): out-degrees of its 2 048
-//             sources, their row starts (indptr_T), the source-side row pass, and the stable
-//             placement of its edges (indices_T, the edge permutation)
+//   stage 3   k_plan_bucket_counts: buckets of more than 7 680 edges are finished in sub-chunks;
+//             edges per source of each sub-chunk
+//             k_plan_buckets: per bucket (sub-chunk): out-degrees of its 2 048 sources, their row
+//             starts (indptr_T), the source-side row pass, and the stable placement of its edges
+//             (indices_T, the edge permutation)
 //   stage 4   source-side long-row fill
 //
-// Five launches for the plans of all layers of a mini-batch.  Blocks with more source
+// Six launches for the plans of all layers of a mini-batch.  Blocks with more source
 // nodes take an LSD radix sort of the edges by source id instead (8-bit digits:
 // histogram + scatter per pass, then row starts, row pass, fill: 9 launches at 3 passes).
+// These stages are bound by latency and instruction issue, not by bytes: loads are written
+// so that all loads of a phase are in flight together, and a launch holds enough workgroups
+// to fill the compute units once.
 #include <vector>
 
 #include "internal.h"
@@ -37,6 +42,8 @@ constexpr int kSortThreads = 1024;                   // 16 wavefronts per sort w
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxSortItems = 4;                     // keys per thread and step: 1, 2 or 4
 constexpr int kMaxSortBlocks = 256;
+constexpr int kSplitThreads = 512;                   // workgroup of the split into buckets (bucketed transpose)
+constexpr int kMaxSplitBlocks = 512;                 // two of them per compute unit
 
 // -------------------------------------------------- block-wide primitives ----
 __device__ __forceinline__ int wave_incl_scan(int v)
@@ -246,9 +253,10 @@ constexpr int kLocalThreads = 512;
 constexpr int kLocalWaves = kLocalThreads / kWave;
 constexpr int kSubRounds = 15;                               // rounds of 64 edges per wavefront
 constexpr int kSubChunk = kLocalWaves * kSubRounds * kWave;  // 7 680 edges; below 65 536: 16-bit counts
-constexpr int kLocalKeys = kBucketIds / kLocalThreads;       // sources per thread in the scans: 4 consecutive ones
+constexpr int kLocalKeys = kBucketIds / kLocalThreads;       // consecutive sources per thread in the scans
+constexpr int kLocalWords = kLocalKeys / 2;                  // = words of the count table per thread
 static_assert(kMaxBuckets <= kSortThreads && kMaxBuckets <= kMaxScanBlocks, "bucket prologue, fill pass");
-static_assert(kLocalKeys == 4, "a thread scans two words of the count table");
+static_assert(kLocalKeys * kLocalThreads == kBucketIds && kLocalKeys % 2 == 0, "whole words per thread");
 static_assert(kSubChunk < 65536, "per-wavefront counts are 16 bits wide");
 
 struct BucketOfGroup {   // what workgroup g of k_plan_buckets works on
@@ -264,22 +272,39 @@ inline int64_t large_bucket_groups(int64_t n) { return n > kSubChunk ? 2 * n / k
 
 // Bucket d takes max(1, ceil(tot[d] / kSubChunk)) workgroups.  Those of the buckets with several
 // sub-chunks come first (they have the most to do, and workgroups start in this order), then one per
-// remaining bucket.  Written by one workgroup of the scatter launch (1024 threads: thread t = bucket
-// t; ex = first edge of bucket t).
-__device__ __forceinline__ void write_bucket_map(BucketOfGroup *map, int cap, int nbuckets, int tv, int ex, int *lds)
+// remaining bucket.  Written by one workgroup of the scatter launch: a thread has PER consecutive
+// buckets from d0 on, tv[] = their edges, ex[] = their first edges.
+template <int PER>
+__device__ __forceinline__ void write_bucket_map(BucketOfGroup *map, int cap, int nbuckets, int d0,
+                                                 const int (&tv)[PER], const int (&ex)[PER], int *lds)
 {
-    const int t = threadIdx.x;
-    const int ns = t < nbuckets ? (tv > kSubChunk ? (tv + kSubChunk - 1) / kSubChunk : 1) : 0;
-    int large, small;
-    int wf = block_excl_scan(ns > 1 ? ns : 0, &large, lds);
-    const int ws = block_excl_scan(ns == 1 ? 1 : 0, &small, lds);
-    if (ns == 1) wf = large + ws;
-    for (int s = 0; s < ns; ++s) {
-        BucketOfGroup m;
-        m.bucket = t; m.sub = s; m.first_edge = ex; m.edges = tv;
-        if (wf + s < cap) map[wf + s] = m;
+    int ns[PER], nl = 0, nsm = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        ns[i] = d0 + i < nbuckets ? (tv[i] > kSubChunk ? (tv[i] + kSubChunk - 1) / kSubChunk : 1) : 0;
+        nl += ns[i] > 1 ? ns[i] : 0;
+        nsm += ns[i] == 1 ? 1 : 0;
     }
-    for (int i = large + small + t; i < cap; i += blockDim.x) map[i].bucket = -1;
+    int large, small;
+    int wl = block_excl_scan(nl, &large, lds);
+    int ws = large + block_excl_scan(nsm, &small, lds);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        int at = 0;
+        if (ns[i] > 1) {
+            at = wl;
+            wl += ns[i];
+        } else if (ns[i] == 1) {
+            at = ws;
+            ws += 1;
+        }
+        for (int q = 0; q < ns[i]; ++q) {
+            BucketOfGroup m;
+            m.bucket = d0 + i; m.sub = q; m.first_edge = ex[i]; m.edges = tv[i];
+            if (at + q < cap) map[at + q] = m;
+        }
+    }
+    for (int i = large + small + (int)threadIdx.x; i < cap; i += blockDim.x) map[i].bucket = -1;
 }
 
 // ------------------------------------------------- stable split by a digit ----
@@ -311,16 +336,16 @@ template <int BITS>
 __device__ __forceinline__ void match_lanes(int v, bool ok, unsigned &lo, unsigned &hi)
 {
     const unsigned long long act = __ballot(ok);
-    lo = (unsigned)act;
-    hi = (unsigned)(act >> 32);
+    unsigned dlo = 0, dhi = 0;   // lanes that differ from this one in some bit
 #pragma unroll
     for (int bit = 0; bit < BITS; ++bit) {
-        const int neg = -((v >> bit) & 1);                 // all ones where the bit is set
-        const unsigned long long bl = __ballot(neg != 0);
-        lo &= ~((unsigned)bl ^ (unsigned)neg);             // keep the lanes that agree in this bit
-        hi &= ~((unsigned)(bl >> 32) ^ (unsigned)neg);
+        const int neg = (int)((unsigned)v << (31 - bit)) >> 31;   // all ones where the bit is set
+        const unsigned long long bl = __ballot(neg < 0);
+        dlo |= (unsigned)bl ^ (unsigned)neg;
+        dhi |= (unsigned)(bl >> 32) ^ (unsigned)neg;
     }
-    if (!ok) lo = hi = 0;
+    lo = ok ? (unsigned)act & ~dlo : 0u;
+    hi = ok ? (unsigned)(act >> 32) & ~dhi : 0u;
 }
 
 __device__ __forceinline__ int lanes_below(unsigned lo, unsigned hi)   // set bits of the mask below this lane
@@ -401,33 +426,51 @@ __device__ __forceinline__ void col_scan(const ColScanArgs &A, int g, int *part)
 // wavefronts plus a scan over the digits give each key its place in the step's
 // sorted order.  The step is sorted into LDS first and written out from there.
 // The payload is the edge's destination row and, if asked for, its original id.
-template <int BITS>
+template <int BITS, int NT>
 struct SortShared {
     static constexpr int kBins = 1 << BITS;
     int running[kBins], lbase[kBins], gdelta[kBins];
-    int wcnt[kSortWaves][kBins];
-    int32_t skey[kSortThreads * kMaxSortItems], sval[kSortThreads * kMaxSortItems];
-    int32_t seid[kSortThreads * kMaxSortItems];
+    int wcnt[NT / kWave][kBins];
+    int32_t skey[NT * kMaxSortItems], sval[NT * kMaxSortItems];
+    int32_t seid[NT * kMaxSortItems];
 };
 
-template <int ITEMS, int BITS>
-__device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShared<BITS> &M, int *lds)
+// NT threads: 1024 for an LSD pass (its prologue is laid out for that), kSplitThreads for the split
+// into buckets, where two or three smaller workgroups share a compute unit and fill each other's
+// waits at the barriers.
+template <int ITEMS, int BITS, int NT>
+__device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShared<BITS, NT> &M, int *lds)
 {
-    constexpr int kBins = 1 << BITS;
-    static_assert(kBins <= kSortThreads, "one thread per digit");
+    constexpr int kBins = 1 << BITS, kWaves = NT / kWave;
+    constexpr int kPer = kBins > NT ? kBins / NT : 1;   // consecutive digits per thread in the scans
+    static_assert(kPer * NT >= kBins && (kWaves * kBins) % NT == 0, "digits and counters divide among the threads");
     int (&running)[kBins] = M.running, (&lbase)[kBins] = M.lbase, (&gdelta)[kBins] = M.gdelta;
-    int (&wcnt)[kSortWaves][kBins] = M.wcnt;
+    int (&wcnt)[kWaves][kBins] = M.wcnt;
     int32_t *skey = M.skey, *sval = M.sval, *seid = M.seid;
     const bool EID = S.eid_out != nullptr;
     const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
+    const int d0 = t * kPer;   // this thread's digits in the scans: d0 .. d0 + kPer - 1, those below kBins
     if (S.tot) {   // bucketed transpose: start of the bucket + keys of it in earlier blocks
+        int tv[kPer], ex[kPer], sum = 0;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            tv[i] = d0 + i < S.nbins ? S.tot[d0 + i] : 0;
+            sum += tv[i];
+        }
+        int cb[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) cb[i] = d0 + i < S.nbins ? S.cnt[(int64_t)b * S.nbins + d0 + i] : 0;
         int dummy;
-        const int tv = t < S.nbins ? S.tot[t] : 0;
-        const int ex = block_excl_scan(tv, &dummy, lds);
-        if (t < kBins) running[t] = t < S.nbins ? ex + S.cnt[(int64_t)b * S.nbins + t] : 0;
-        if (b == 0) write_bucket_map(S.map, S.map_cap, S.nbins, tv, ex, lds);
+        int at = block_excl_scan(sum, &dummy, lds);
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            ex[i] = at;
+            at += tv[i];
+            if (d0 + i < kBins) running[d0 + i] = d0 + i < S.nbins ? ex[i] + cb[i] : 0;
+        }
+        if (b == 0) write_bucket_map<kPer>(S.map, S.map_cap, S.nbins, d0, tv, ex, lds);
         __syncthreads();
-    } else if constexpr (BITS == kRadixBits) {   // LSD pass: offsets from the whole count table
+    } else if constexpr (BITS == kRadixBits && NT == kSortThreads) {   // LSD pass: offsets from the whole count table
         const int d = t & (kBins - 1), part = t / kBins;   // 4 parts share the blocks
         int below = 0, total = 0;
         constexpr int kParts = kSortThreads / kBins, kBatch = 16;
@@ -475,10 +518,10 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
         }
     };
     if (beg < end) load_step(beg);
-    for (int64_t step = beg; step < end; step += kSortThreads * ITEMS) {
+    for (int64_t step = beg; step < end; step += NT * ITEMS) {
 #pragma unroll
-        for (int k = 0; k < kSortWaves * kBins / kSortThreads; ++k)
-            (&wcnt[0][0])[k * kSortThreads + t] = 0;
+        for (int k = 0; k < kWaves * kBins / NT; ++k)
+            (&wcnt[0][0])[k * NT + t] = 0;
         __syncthreads();
         int32_t key[ITEMS], val[ITEMS], eid[ITEMS];
         int rank[ITEMS], dig[ITEMS];
@@ -492,7 +535,7 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
             eid[i] = neid[i];
             dig[i] = (key[i] >> S.shift) & (kBins - 1);
         }
-        if (step + kSortThreads * ITEMS < end) load_step(step + kSortThreads * ITEMS);
+        if (step + NT * ITEMS < end) load_step(step + NT * ITEMS);
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             unsigned mlo, mhi;
@@ -506,21 +549,30 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
         __syncthreads();
         // column scan over the wavefronts, then a scan over the digits: position of
         // every key inside this step's sorted order
-        int tot_t = 0;
-        if (t < kBins) {
+        int tot_d[kPer], tot_t = 0;
 #pragma unroll
-            for (int k = 0; k < kSortWaves; ++k) {
-                int c = wcnt[k][t];
-                wcnt[k][t] = tot_t;
-                tot_t += c;
+        for (int i = 0; i < kPer; ++i) {
+            tot_d[i] = 0;
+            if (d0 + i < kBins) {
+#pragma unroll
+                for (int k = 0; k < kWaves; ++k) {
+                    int c = wcnt[k][d0 + i];
+                    wcnt[k][d0 + i] = tot_d[i];
+                    tot_d[i] += c;
+                }
             }
+            tot_t += tot_d[i];
         }
         int nvalid;
-        const int lb = block_excl_scan(tot_t, &nvalid, lds);
-        if (t < kBins) {
-            lbase[t] = lb;
-            gdelta[t] = running[t] - lb;   // global position = gdelta[digit] + position in the step
-            running[t] += tot_t;
+        int lb = block_excl_scan(tot_t, &nvalid, lds);
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            if (d0 + i < kBins) {
+                lbase[d0 + i] = lb;
+                gdelta[d0 + i] = running[d0 + i] - lb;   // global position = gdelta[digit] + position in the step
+                running[d0 + i] += tot_d[i];
+                lb += tot_d[i];
+            }
         }
         __syncthreads();
 #pragma unroll
@@ -536,7 +588,7 @@ __device__ __forceinline__ void sort_scatter(const SortArgs &S, int b, SortShare
         // slots: neighbouring threads write neighbouring addresses
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
-            const int j = i * kSortThreads + t;
+            const int j = i * NT + t;
             if (j >= nvalid) continue;
             const int32_t k = skey[j], v = sval[j];
             const int64_t pos = (int64_t)gdelta[(k >> S.shift) & (kBins - 1)] + j;
@@ -589,40 +641,39 @@ __device__ __forceinline__ void wave_run(int c0, int c1, int w, int &s0, int &s1
     s1 = s0 + seg < c1 ? s0 + seg : c1;
 }
 
-// Local source ids (-1: no edge) of this lane's edges in the rounds of the run [s0, s1).  The loads
-// carry no branch of their own (past the end they re-read the last edge), so all of them are in
-// flight at once.
-__device__ __forceinline__ void load_run(const int32_t *keys, int s0, int s1, int32_t lo, int (&kk)[kSubRounds])
+// The source ids of this lane's edges in the rounds of the run [s0, s1), as loaded: the loads carry
+// no branch of their own (past the end they re-read the last edge; an empty run reads nothing), so all
+// of them are in flight at once, and nothing here waits for them.
+__device__ __forceinline__ void load_run(const int32_t *keys, int s0, int s1, int32_t (&raw)[kSubRounds])
 {
     const int lane = threadIdx.x & (kWave - 1);
 #pragma unroll
-    for (int u = 0; u < kSubRounds; ++u) kk[u] = -1;
+    for (int u = 0; u < kSubRounds; ++u) raw[u] = 0;
     if (s1 > s0) {   // same for the whole wavefront
-        int32_t raw[kSubRounds];
 #pragma unroll
         for (int u = 0; u < kSubRounds; ++u) {
             const int i = s0 + u * kWave + lane;
             raw[u] = keys[i < s1 ? i : s1 - 1];
         }
-#pragma unroll
-        for (int u = 0; u < kSubRounds; ++u)
-            if (s0 + u * kWave + lane < s1) kk[u] = (raw[u] - lo) & (kBucketIds - 1);
     }
 }
 
-// Edges per wavefront and source of the run whose local source ids are kk[] (-1: no edge), 16-bit
-// counts, two to a word; the table is zeroed first.
-__device__ __forceinline__ void count_run(const int (&kk)[kSubRounds], LocalShared &M)
+// Edges per wavefront and source of the run (16-bit counts, two to a word), and the local source
+// ids kk[] of the lane's edges (-1: no edge).  The table is zeroed while the loads are under way.
+__device__ __forceinline__ void count_run(const int32_t (&raw)[kSubRounds], int s0, int s1, int32_t lo,
+                                          int (&kk)[kSubRounds], LocalShared &M)
 {
-    const int t = threadIdx.x, w = t / kWave;
+    const int t = threadIdx.x, lane = t & (kWave - 1), w = t / kWave;
     uint4 *z = reinterpret_cast<uint4 *>(&M.tab[0][0]);
 #pragma unroll
     for (int k = 0; k < (int)(sizeof(M.tab) / sizeof(uint4)) / kLocalThreads; ++k)
         z[k * kLocalThreads + t] = make_uint4(0u, 0u, 0u, 0u);
     __syncthreads();
 #pragma unroll
-    for (int u = 0; u < kSubRounds; ++u)
+    for (int u = 0; u < kSubRounds; ++u) {
+        kk[u] = s0 + u * kWave + lane < s1 ? (raw[u] - lo) & (kBucketIds - 1) : -1;
         if (kk[u] >= 0) atomicAdd(&M.tab[w][kk[u] >> 1], 1u << ((kk[u] & 1) * 16));
+    }
     __syncthreads();
 }
 
@@ -640,16 +691,18 @@ __device__ __forceinline__ void bucket_count(const LocalArgs &L, int g, LocalSha
     int s0, s1;
     wave_run(c0, c1, w, s0, s1);
     int kk[kSubRounds];
-    load_run(keys, s0, s1, lo, kk);
-    count_run(kk, M);
-    unsigned run0 = 0, run1 = 0;   // sources 4t, 4t+1 and 4t+2, 4t+3: no carry, a sub-chunk has < 65 536 edges
+    int32_t raw[kSubRounds];
+    load_run(keys, s0, s1, raw);
+    count_run(raw, s0, s1, lo, kk, M);
+    unsigned run[kLocalWords] = {};   // two sources per word: no carry, a sub-chunk has < 65 536 edges
 #pragma unroll
     for (int k = 0; k < kLocalWaves; ++k) {
-        const uint2 v = *reinterpret_cast<const uint2 *>(&M.tab[k][2 * t]);
-        run0 += v.x;
-        run1 += v.y;
+#pragma unroll
+        for (int i = 0; i < kLocalWords; ++i) run[i] += M.tab[k][kLocalWords * t + i];
     }
-    reinterpret_cast<uint2 *>(L.subcnt + (size_t)g * kBucketIds)[t] = make_uint2(run0, run1);
+    unsigned *out = reinterpret_cast<unsigned *>(L.subcnt + (size_t)g * kBucketIds) + kLocalWords * t;
+#pragma unroll
+    for (int i = 0; i < kLocalWords; ++i) out[i] = run[i];
 }
 
 __device__ __forceinline__ void bucket_finish(const LocalArgs &L, int g, LocalShared &M, int *lds)
@@ -666,8 +719,8 @@ __device__ __forceinline__ void bucket_finish(const LocalArgs &L, int g, LocalSh
     int s0, s1;
     wave_run(c0, c1, w, s0, s1);
     int kk[kSubRounds];
-    int32_t vv[kSubRounds];
-    load_run(keys, s0, s1, lo, kk);
+    int32_t vv[kSubRounds], raw[kSubRounds];
+    load_run(keys, s0, s1, raw);
     if (s1 > s0) {   // in flight while the sub-chunk is counted
 #pragma unroll
         for (int u = 0; u < kSubRounds; ++u) {
@@ -675,41 +728,46 @@ __device__ __forceinline__ void bucket_finish(const LocalArgs &L, int g, LocalSh
             vv[u] = vals[i < s1 ? i : s1 - 1];
         }
     }
-    int other[kLocalKeys] = {0, 0, 0, 0}, before[kLocalKeys] = {0, 0, 0, 0};
+    int other[kLocalKeys] = {}, before[kLocalKeys] = {};
     if (nbk > kSubChunk && g < L.large_groups) {   // edges of the bucket's other sub-chunks, per source
         const int nsub = (nbk + kSubChunk - 1) / kSubChunk;
-        const uint2 *c = reinterpret_cast<const uint2 *>(L.subcnt + (size_t)(g - sub) * kBucketIds) + t;
+        const unsigned *c = reinterpret_cast<const unsigned *>(L.subcnt + (size_t)(g - sub) * kBucketIds) + kLocalWords * t;
 #pragma unroll 4
         for (int j = 0; j < nsub; ++j) {
-            const uint2 v = c[(size_t)j * (kBucketIds / 4)];
-            const int x[kLocalKeys] = {(int)(v.x & 0xFFFFu), (int)(v.x >> 16), (int)(v.y & 0xFFFFu), (int)(v.y >> 16)};
+            unsigned v[kLocalWords];
+#pragma unroll
+            for (int i = 0; i < kLocalWords; ++i) v[i] = c[(size_t)j * (kBucketIds / 2) + i];
 #pragma unroll
             for (int k = 0; k < kLocalKeys; ++k) {
-                if (j != sub) other[k] += x[k];
-                if (j < sub) before[k] += x[k];
+                const int x = (int)((v[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu);
+                if (j != sub) other[k] += x;
+                if (j < sub) before[k] += x;
             }
         }
     }
-    count_run(kk, M);
+    count_run(raw, s0, s1, lo, kk, M);
     // column scan over the wavefronts, both halves of a word at once (no carry: len < 65 536); the
-    // totals are the sub-chunk's edges of sources 4t .. 4t+3
-    unsigned run0 = 0, run1 = 0;
+    // totals are the sub-chunk's edges of this thread's sources
+    unsigned run[kLocalWords] = {};
 #pragma unroll
     for (int k = 0; k < kLocalWaves; ++k) {
-        uint2 *q = reinterpret_cast<uint2 *>(&M.tab[k][2 * t]);
-        const uint2 v = *q;
-        *q = make_uint2(run0, run1);
-        run0 += v.x;
-        run1 += v.y;
+#pragma unroll
+        for (int i = 0; i < kLocalWords; ++i) {
+            unsigned *q = &M.tab[k][kLocalWords * t + i];
+            const unsigned v = *q;
+            *q = run[i];
+            run[i] += v;
+        }
     }
-    int cnt[kLocalKeys];
-    cnt[0] = (int)(run0 & 0xFFFFu) + other[0];
-    cnt[1] = (int)(run0 >> 16) + other[1];
-    cnt[2] = (int)(run1 & 0xFFFFu) + other[2];
-    cnt[3] = (int)(run1 >> 16) + other[3];
+    int cnt[kLocalKeys], all = 0;
+#pragma unroll
+    for (int k = 0; k < kLocalKeys; ++k) {
+        cnt[k] = (int)((run[k >> 1] >> ((k & 1) * 16)) & 0xFFFFu) + other[k];
+        all += cnt[k];
+    }
     int dummy;
     int e0[kLocalKeys];
-    e0[0] = block_excl_scan(cnt[0] + cnt[1] + cnt[2] + cnt[3], &dummy, lds);
+    e0[0] = block_excl_scan(all, &dummy, lds);
 #pragma unroll
     for (int k = 1; k < kLocalKeys; ++k) e0[k] = e0[k - 1] + cnt[k - 1];
 #pragma unroll
@@ -827,23 +885,29 @@ static size_t job_lds_bytes(const Job &j)
 {
     switch (j.kind) {
         case JOB_SORT_HIST: return sizeof(int) << j.sort.bits;
-        case JOB_SORT_SCATTER: return j.sort.bits == kRadixBits ? sizeof(SortShared<kRadixBits>) : sizeof(SortShared<10>);
+        case JOB_SORT_SCATTER:
+            if (!j.sort.tot) return sizeof(SortShared<kRadixBits, kSortThreads>);
+            return j.sort.bits == kRadixBits ? sizeof(SortShared<kRadixBits, kSplitThreads>)
+                                             : sizeof(SortShared<10, kSplitThreads>);
         case JOB_COL_SCAN: return sizeof(int) * kSortWaves * kWave;
         default: return 0;
     }
 }
-constexpr size_t kMaxStageLds = sizeof(SortShared<10>);
+constexpr size_t kMaxSplitLds = sizeof(SortShared<10, kSplitThreads>);
 
-template <int BITS>
+template <int BITS, int NT>
 __device__ __forceinline__ void sort_scatter_any(const SortArgs &S, int b, unsigned char *dyn, int *lds)
 {
-    SortShared<BITS> &M = *reinterpret_cast<SortShared<BITS> *>(dyn);
-    if (S.items == 1) sort_scatter<1, BITS>(S, b, M, lds);
-    else if (S.items == 2) sort_scatter<2, BITS>(S, b, M, lds);
-    else sort_scatter<4, BITS>(S, b, M, lds);
+    SortShared<BITS, NT> &M = *reinterpret_cast<SortShared<BITS, NT> *>(dyn);
+    if (S.items == 1) sort_scatter<1, BITS, NT>(S, b, M, lds);
+    else if (S.items == 2) sort_scatter<2, BITS, NT>(S, b, M, lds);
+    else sort_scatter<4, BITS, NT>(S, b, M, lds);
 }
 
-__global__ __launch_bounds__(kSortThreads) void k_plan_stage(StageArgs A)
+// SCATTER: the launch holds passes of the LSD radix sort.  Their registers would otherwise cap
+// every stage at one 1024-thread workgroup per compute unit; the light variant runs two.
+template <bool SCATTER>
+__global__ __launch_bounds__(kSortThreads, SCATTER ? 4 : 8) void k_plan_stage(StageArgs A)
 {
     extern __shared__ __align__(16) unsigned char dyn[];
     __shared__ int lds[32];
@@ -856,12 +920,25 @@ __global__ __launch_bounds__(kSortThreads) void k_plan_stage(StageArgs A)
         case JOB_ROWS_FILL: rows_fill(J.rows, b, lds); break;
         case JOB_SORT_HIST: sort_hist(J.sort, b, reinterpret_cast<int *>(dyn)); break;
         case JOB_SORT_SCATTER:
-            if (J.sort.bits == kRadixBits) sort_scatter_any<kRadixBits>(J.sort, b, dyn, lds);
-            else sort_scatter_any<10>(J.sort, b, dyn, lds);
+            if constexpr (SCATTER) sort_scatter_any<kRadixBits, kSortThreads>(J.sort, b, dyn, lds);
             break;
         case JOB_COL_SCAN: col_scan(J.cols, b, reinterpret_cast<int *>(dyn)); break;
         default: row_starts(J.starts, b); break;
     }
+}
+
+// The split into buckets of every bucketed transpose of a stage (jobs of kind JOB_SORT_SCATTER
+// with a bucket total array).
+__global__ __launch_bounds__(kSplitThreads) void k_plan_split(StageArgs A)
+{
+    extern __shared__ __align__(16) unsigned char dyn[];
+    __shared__ int lds[32];
+    int j = 0;
+    while (j + 1 < A.njobs && (int)blockIdx.x >= A.first[j + 1]) ++j;
+    const int b = blockIdx.x - A.first[j];
+    const SortArgs &S = A.job[j].sort;
+    if (S.bits == kRadixBits) sort_scatter_any<kRadixBits, kSplitThreads>(S, b, dyn, lds);
+    else sort_scatter_any<10, kSplitThreads>(S, b, dyn, lds);
 }
 
 // The buckets of every bucketed transpose of a stage: smaller workgroups than k_plan_stage's, three
@@ -947,7 +1024,7 @@ static RowsArgs rows_args(const int32_t *rowptr, int64_t n, int32_t *len_out, fl
                           int32_t *edge_row, int32_t *split, int64_t nnz)
 {
     RowsArgs A;
-    int64_t b = ceil_div(n, (int64_t)kSortThreads);   // one row per thread while that gives at most kMaxScanBlocks blocks
+    int64_t b = ceil_div(n, (int64_t)kSortThreads * 2);   // two rows per thread while that gives at most kMaxScanBlocks blocks
     if (b < 1) b = 1;
     if (b > kMaxScanBlocks) b = kMaxScanBlocks;
     A.rowptr = rowptr; A.n = n; A.nb = (int)b;
@@ -975,16 +1052,17 @@ struct SortGeom {
 static SortGeom sort_geom(int64_t num_src, int64_t n, int64_t keys_per_group = 0)
 {
     SortGeom g;
-    // one step per workgroup when the keys fit 256 workgroups x 4 keys per thread
-    int64_t want = ceil_div(n, (int64_t)kMaxSortBlocks);
+    g.bucketed = num_src <= (int64_t)kMaxBuckets * kBucketIds;
+    const int threads = g.bucketed ? kSplitThreads : kSortThreads, most = g.bucketed ? kMaxSplitBlocks : kMaxSortBlocks;
+    // one step per workgroup when the keys fit `most` workgroups x 4 keys per thread
+    int64_t want = ceil_div(n, (int64_t)most);
     if (want < keys_per_group) want = keys_per_group;
     g.items = 1;
-    while (g.items < kMaxSortItems && (int64_t)g.items * kSortThreads < want) g.items <<= 1;
-    const int64_t step = (int64_t)g.items * kSortThreads;
+    while (g.items < kMaxSortItems && (int64_t)g.items * threads < want) g.items <<= 1;
+    const int64_t step = (int64_t)g.items * threads;
     g.per = ceil_div(want, step) * step;
     if (g.per < step) g.per = step;
     g.nb = n > 0 ? (int)ceil_div(n, g.per) : 1;
-    g.bucketed = num_src <= (int64_t)kMaxBuckets * kBucketIds;
     g.nbuckets = g.bucketed ? (int)(num_src > 0 ? ceil_div(num_src, (int64_t)kBucketIds) : 1) : 0;
     g.bits = g.nbuckets <= kRadixBins ? kRadixBits : 10;
     return g;
@@ -1039,6 +1117,7 @@ struct BucketJob {
 };
 struct Stage {
     std::vector<Job> jobs;            // workgroups of k_plan_stage
+    std::vector<Job> splits;          // workgroups of k_plan_split
     std::vector<BucketJob> buckets;   // workgroups of k_plan_buckets
 };
 using Stages = std::vector<Stage>;
@@ -1047,6 +1126,12 @@ static void add_job(Stages &st, size_t k, const Job &j)
 {
     if (st.size() <= k) st.resize(k + 1);
     st[k].jobs.push_back(j);
+}
+
+static void add_split(Stages &st, size_t k, const Job &j)
+{
+    if (st.size() <= k) st.resize(k + 1);
+    st[k].splits.push_back(j);
 }
 
 static void add_buckets(Stages &st, size_t k, const BucketJob &j)
@@ -1102,7 +1187,7 @@ static void plan_stages(fastgl_plan *p, int parts, Stages &st, int64_t keys_per_
         j.kind = JOB_SORT_HIST;
         add_job(st, 0, j);
         j.kind = JOB_SORT_SCATTER;
-        add_job(st, 2, j);
+        add_split(st, 2, j);
         Job c;
         c.kind = JOB_COL_SCAN;
         c.cols.cnt = p->radix_cnt; c.cols.tot = p->bucket_tot; c.cols.nb = S.nb; c.cols.nbins = sg.nbuckets;
@@ -1164,9 +1249,12 @@ static fastgl_status run_stages(const Stages &st, hipStream_t s)
 {
     static_assert(sizeof(StageArgs) <= 4096 && sizeof(BucketStageArgs) <= 4096, "kernel arguments are passed by value");
     static bool raised = false;   // benign if two threads both do it
-    if (!raised) {   // the split into more than 256 buckets takes more LDS than a launch gets by default
-        FASTGL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_plan_stage),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStageLds));
+    if (!raised) {   // the scatter kernels take more LDS than a launch gets by default
+        FASTGL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_plan_stage<true>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)sizeof(SortShared<kRadixBits, kSortThreads>)));
+        FASTGL_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_plan_split),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxSplitLds));
         raised = true;
     }
     for (const Stage &stage : st) {
@@ -1184,11 +1272,28 @@ static fastgl_status run_stages(const Stages &st, hipStream_t s)
                 if (need > lds) lds = need;
             }
             A.first[A.njobs] = blocks;
-            // a stage of fill passes only: most of its workgroups find nothing to do, small ones start faster
-            bool fills_only = true;
-            for (int i = 0; i < A.njobs; ++i) fills_only = fills_only && A.job[i].kind == JOB_ROWS_FILL;
-            hipLaunchKernelGGL(k_plan_stage, dim3(blocks), dim3(fills_only ? kBlock : kSortThreads), lds, s, A);
+            bool scatter = false;
+            for (int i = 0; i < A.njobs; ++i) scatter = scatter || A.job[i].kind == JOB_SORT_SCATTER;
+            if (scatter) hipLaunchKernelGGL(k_plan_stage<true>, dim3(blocks), dim3(kSortThreads), lds, s, A);
+            else hipLaunchKernelGGL(k_plan_stage<false>, dim3(blocks), dim3(kSortThreads), lds, s, A);
             FASTGL_LAUNCH_CHECK("k_plan_stage");
+        }
+        const auto &sp = stage.splits;
+        for (size_t at = 0; at < sp.size(); at += kMaxJobs) {
+            StageArgs A;
+            A.njobs = (int)(sp.size() - at < (size_t)kMaxJobs ? sp.size() - at : kMaxJobs);
+            int blocks = 0;
+            size_t lds = 0;
+            for (int i = 0; i < A.njobs; ++i) {
+                A.first[i] = blocks;
+                A.job[i] = sp[at + i];
+                blocks += A.job[i].nblocks;
+                const size_t need = job_lds_bytes(A.job[i]);
+                if (need > lds) lds = need;
+            }
+            A.first[A.njobs] = blocks;
+            hipLaunchKernelGGL(k_plan_split, dim3(blocks), dim3(kSplitThreads), lds, s, A);
+            FASTGL_LAUNCH_CHECK("k_plan_split");
         }
         const auto &bk = stage.buckets;
         for (size_t at = 0; at < bk.size(); at += kMaxJobs) {
@@ -1238,12 +1343,12 @@ static fastgl_status src_degrees(fastgl_plan *p, hipStream_t s)
 // plan for dout / src_rsqrt as well (GCN).
 fastgl_status plans_build(fastgl_plan *const *plans, const int *parts, const bool *src_deg, int n, hipStream_t s)
 {
-    // The split of the edges runs one 1024-thread workgroup per compute unit: the transposes of a
+    // The split of the edges runs two 512-thread workgroups per compute unit: the transposes of a
     // call share the (256) compute units, each workgroup taking about the same number of edges.
     int64_t edges = 0;
     for (int i = 0; i < n; ++i)
         if (parts[i] & FASTGL_PLAN_BWD) edges += plans[i]->num_edges;
-    const int64_t keys_per_group = ceil_div(edges, (int64_t)kMaxSortBlocks);
+    const int64_t keys_per_group = ceil_div(edges, (int64_t)kMaxSplitBlocks);
     Stages st;
     for (int i = 0; i < n; ++i) plan_stages(plans[i], parts[i], st, keys_per_group);
     fastgl_status rc = run_stages(st, s);
