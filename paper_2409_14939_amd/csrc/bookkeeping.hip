@@ -248,7 +248,7 @@ __device__ __forceinline__ void rows_fill(const RowsArgs &A, int b, int *lds)
 // ------------------------------------ bucketed transpose: sizes, workgroup map ----
 constexpr int kBucketBits = 11;
 constexpr int kBucketIds = 1 << kBucketBits;
-constexpr int kMaxBuckets = 1024;                            // one thread per bucket in the scatter's prologue
+constexpr int kMaxBuckets = 1024;                            // one thread per bucket in the histogram, two in the scatter's prologue
 constexpr int kLocalThreads = 512;
 constexpr int kLocalWaves = kLocalThreads / kWave;
 constexpr int kSubRounds = 15;                               // rounds of 64 edges per wavefront
