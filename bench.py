@@ -585,6 +585,7 @@ class Workload:
 
 
 DOM_EVERY = 4   # timed steps per step that also times its dominant launch
+GATHER_CEILING_GBPS = 7000.0   # random row gathers by a bare probe kernel: 6.4-7.6 TB/s, see profiles/
 
 
 def median_ms(pairs):
@@ -711,6 +712,14 @@ def headline(W, steps, warmup, np, traffic_table, copy_gbps, per_layer_reps):
                      "launch_ms": round(dom_ms, 4), "algorithmic_bytes": int(domL["bytes_fwd"])},
         "gen_seconds": round(W.gen_s, 2),
     }
+    moved = res["roofline"]["traffic"]
+    if moved:
+        # the same launch in MOVED bytes (the counter table) against what a bare kernel of random row
+        # gathers reaches on this GPU (profiles/pull_rows_config2_traffic.md: 6.4-6.8 TB/s out of HBM,
+        # 7.2-7.6 TB/s out of a cache-resident table)
+        res["roofline"]["moved_gbps"] = round(moved / (dom_ms * 1e-3) / 1e9, 1)
+        res["roofline"]["gather_ceiling_gbps"] = GATHER_CEILING_GBPS
+        res["roofline"]["moved_frac_of_gather_ceiling"] = round(moved / (dom_ms * 1e-3) / 1e9 / GATHER_CEILING_GBPS, 4)
     return res
 
 
