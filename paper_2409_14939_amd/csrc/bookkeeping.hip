@@ -1098,9 +1098,11 @@ size_t plan_layout(fastgl_plan *p, void *base, int64_t num_dst, int64_t num_src,
     q->split_dst = (int32_t *)take(4 * ((size_t)num_row_sets(num_dst, num_edges) + 1));
     q->split_src = (int32_t *)take_bwd(4 * ((size_t)num_row_sets(num_src, num_edges) + 1));
     q->counters = (int32_t *)take(4 * 4);
-    for (int i = 0; i < 6; ++i) q->sort_buf[i] = (int32_t *)take_bwd(4 * (size_t)num_edges);
-    q->edge_dst = (int32_t *)take_bwd(4 * (size_t)num_edges);
     const SortGeom sg = sort_geom(num_src, num_edges);
+    // the split into buckets writes one set of (source id, destination row, edge id); the radix sort ping-pongs two
+    for (int i = 0; i < 6; ++i)
+        q->sort_buf[i] = i < 3 || !sg.bucketed ? (int32_t *)take_bwd(4 * (size_t)num_edges) : nullptr;
+    q->edge_dst = (int32_t *)take_bwd(4 * (size_t)num_edges);
     q->radix_cnt = (int32_t *)take_bwd(4 * (size_t)sg.nb * (sg.bucketed ? sg.nbuckets : kRadixBins));
     q->bucket_tot = (int32_t *)take_bwd(4 * (size_t)kMaxBuckets);
     q->bucket_map = take_bwd(sg.bucketed ? sizeof(BucketOfGroup) * (size_t)bucket_groups(sg.nbuckets, num_edges) : 0);
