@@ -714,7 +714,7 @@ __device__ __forceinline__ void bucket_finish(const LocalArgs &L, int g, LocalSh
     const int64_t B0 = m.first_edge;
     const int32_t lo = d * kBucketIds;
     const int c0 = sub * kSubChunk, c1 = c0 + kSubChunk < nbk ? c0 + kSubChunk : nbk;
-    const int32_t *keys = L.keys + B0, *vals = L.vals + B0, *eids = L.eids + B0;
+    const int32_t *keys = L.keys + B0, *vals = L.vals + B0, *eids = L.perm ? L.eids + B0 : nullptr;
     // this wavefront's run of the sub-chunk: rounds of 64 consecutive edges, all loaded up front
     int s0, s1;
     wave_run(c0, c1, w, s0, s1);
@@ -788,7 +788,7 @@ __device__ __forceinline__ void bucket_finish(const LocalArgs &L, int g, LocalSh
         // the LDS read above is issued before this update by the same wavefront
         if (ok && lower == 0) atomicAdd(&M.tab[w][k >> 1], (unsigned)(__popc(mlo) + __popc(mhi)) << sh);
         const int64_t pos = B0 + M.start[k] + prior + lower;
-        const bool put = ok && pos < L.n;
+        const bool put = ok && pos >= 0 && pos < L.n;
         if (put) L.indices_T[pos] = vv[u];
         vv[u] = put ? (int32_t)pos : -1;   // the edge's place, for its id below
     }

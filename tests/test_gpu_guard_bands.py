@@ -3,7 +3,8 @@ of a sentinel bit pattern, in ONE allocation, and the bands must be untouched af
 that writes a row too many, or a slice past the end of a row, lands in a band).  The results between
 the bands are checked against the oracle as usual, so that a band is not intact simply because
 nothing ran.  Covers aggregation forward / backward (plan and no plan, long rows, empty blocks),
-row gather, row assembly, the update phase and the one-call layer."""
+row gather, row assembly, the update phase, the one-call layer, and the plan buffer (everything the
+bookkeeping kernels write lies inside the caller's buffer of fastgl_block_plan_bytes bytes)."""
 import numpy as np
 import pytest
 import torch
@@ -11,7 +12,7 @@ import torch
 import blockgen as bg
 import oracle
 from paper_2409_14939_amd import binding as B
-from gpu_util import assert_close, dev_feat, dev_i32, host_feat, make_inputs
+from gpu_util import assert_close, dev_feat, dev_i32, host_feat, make_inputs, read_i32
 
 pytestmark = pytest.mark.gpu
 GUARD_ROWS = 3
@@ -131,3 +132,34 @@ def test_layer_outputs_between_guard_bands(K, N):
     Href = oracle.aggregate_fwd(blk.indptr, blk.indices, None, blk.num_src, "gcn", "f32", X)
     assert_close(H.t.cpu().numpy(), Href, "f32", "layer H")
     np.testing.assert_allclose(Y.t.cpu().numpy(), oracle.update_fwd(Href, W, b, True), rtol=2e-4, atol=2e-4)
+
+
+def test_plan_buffer_between_guard_bands():
+    """The bookkeeping kernels (both transposes, every array of a plan and their scratch) write inside
+    the plan buffer: a buffer of exactly fastgl_block_plan_bytes bytes between two 64 KiB bands."""
+    rng = np.random.default_rng(77)
+    band = 1 << 16
+    cases = list(blocks()) + [
+        ("few-sources", bg.random_block(rng, 70000, 300, 3.0)),                 # one bucket in several parts
+        ("three-buckets", bg.random_block(rng, 20000, 5000, 12.0)),
+        ("ten-bit-split", bg.random_block(rng, 2000, 600_000, 100.0)),
+        ("radix-sort", bg.random_block(rng, 3000, 2_500_000, 20.0)),            # more than 2^21 sources
+    ]
+    for name, blk in cases:
+        for parts in (B.PLAN_ALL | B.PLAN_PERM, B.PLAN_ALL, B.PLAN_FWD | B.PLAN_SRC_DEG):
+            print(f"guard bands: plan of {name} parts={parts} dst={blk.num_dst} src={blk.num_src} E={blk.num_edges}",
+                  flush=True)
+            need = B.fastgl_block_plan_bytes(blk.num_dst, blk.num_src, blk.num_edges)
+            raw = torch.zeros(need + 2 * band, dtype=torch.uint8, device="cuda")
+            raw[:band] = 0xA5
+            raw[band + need:] = 0xA5
+            ip, ix = dev_i32(blk.indptr), dev_i32(blk.indices)
+            plan = B.fastgl_block_plan_create(ip, ix, blk.num_src, parts, raw[band:band + need])
+            torch.cuda.synchronize()
+            assert bool((raw[:band] == 0xA5).all()), f"{name}: store below the plan buffer"
+            assert bool((raw[band + need:] == 0xA5).all()), f"{name}: store above the plan buffer"
+            v = plan.export()
+            din, dout = oracle.degrees(blk.indptr, blk.indices, blk.num_src)
+            assert np.array_equal(read_i32(plan, v.dout, blk.num_src), dout), f"{name}: out-degrees"
+            assert np.array_equal(read_i32(plan, v.din, blk.num_dst), din), f"{name}: in-degrees"
+            plan.destroy()
